@@ -1,0 +1,323 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against facts that do not come from it
+(closed forms, library routines on special cases, exact rational arithmetic, hand-worked tables,
+multilinearity).  The paper prints no worked numeric example of the contraction, so there is no
+golden file from it; the formula is LoRA's (cited in Section 1) batched as Section 3.3 describes."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2511_00101_amd import synth
+
+pytestmark = pytest.mark.filterwarnings("ignore")
+
+
+def f64(bits):
+    return synth.bf16_bits_to_f64(bits)
+
+
+def grid_bits(rng, shape, lo=-128, hi=128, denom=64.0):
+    """bf16-exact values k/denom with |k| <= 128 (8 significant bits)."""
+    v = rng.integers(lo, hi + 1, size=shape).astype(np.float32) / np.float32(denom)
+    bits = synth.f32_to_bf16_bits(v)
+    assert np.array_equal(synth.bf16_bits_to_f32(bits), v)
+    return bits
+
+
+def run_forward(oracle_mod, p):
+    return oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+
+
+# ---------------------------------------------------------------------------------------------
+# bf16 decoding inside the oracle, against numpy's reinterpretation of the same bits
+# ---------------------------------------------------------------------------------------------
+def test_bf16_decode_all_finite_patterns(oracle_mod):
+    bits = np.arange(65536, dtype=np.uint32)
+    finite = ((bits >> 7) & 0xFF) != 0xFF
+    bits = bits[finite].astype(np.uint16)
+    T = bits.shape[0]
+    one = synth.f32_to_bf16_bits(np.ones((1, 1), np.float32))
+    res = oracle_mod.forward(bits.reshape(T, 1), np.zeros((T, 1), np.uint16), [one], [one], [1], [1.0],
+                             np.zeros(T, np.int32), np.full(T, 1, np.uint8))
+    expect = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert np.array_equal(res.y[:, 0], expect)
+
+
+# ---------------------------------------------------------------------------------------------
+# closed forms of the forward
+# ---------------------------------------------------------------------------------------------
+def test_zero_B_leaves_y_unchanged(oracle_mod):
+    p = synth.small_mixed(1, T=37, d_in=24, d_out=40, ranks=[4, 8, 3], drop_frac=0.2)
+    p.B = [np.zeros_like(b) for b in p.B]
+    res = run_forward(oracle_mod, p)
+    assert np.array_equal(res.y, f64(p.y0))
+
+
+def test_single_adapter_equals_dense_matmul(oracle_mod):
+    rng = np.random.default_rng(5)
+    T, d_in, d_out, r, s = 50, 96, 72, 8, 1.75
+    x, y0 = synth.normal_bf16(rng, (T, d_in), 1.0), synth.normal_bf16(rng, (T, d_out), 1.0)
+    A, B = synth.normal_bf16(rng, (r, d_in), 0.02), synth.normal_bf16(rng, (r, d_out), 0.02)
+    kinds = rng.integers(0, 3, size=T).astype(np.uint8)
+    res = oracle_mod.forward(x, y0, [A], [B], [r], [s], np.zeros(T, np.int32), kinds)
+    expect = f64(y0) + s * (f64(x) @ f64(A).T) @ f64(B)
+    np.testing.assert_allclose(res.y, expect, rtol=1e-12, atol=1e-13)
+
+
+def test_transposed_operands_would_fail(oracle_mod):
+    """Guards the layout reading (A is [r, d_in], B is [r, d_out]) with non-square, non-symmetric shapes:
+    the dense form with either operand transposed differently does not even have matching shapes, and
+    with d_in == d_out it gives a different answer."""
+    rng = np.random.default_rng(6)
+    T, d, r = 9, 16, 16
+    x, y0 = synth.normal_bf16(rng, (T, d), 1.0), np.zeros((T, d), np.uint16)
+    A, B = synth.normal_bf16(rng, (r, d), 1.0), synth.normal_bf16(rng, (r, d), 1.0)
+    res = oracle_mod.forward(x, y0, [A], [B], [r], [1.0], np.zeros(T, np.int32), np.ones(T, np.uint8))
+    good = (f64(x) @ f64(A).T) @ f64(B)
+    bad = (f64(x) @ f64(A)) @ f64(B).T
+    np.testing.assert_allclose(res.y, good, rtol=1e-12, atol=1e-12)
+    assert np.abs(res.y - bad).max() > 1.0
+
+
+def test_rank1_is_outer_product(oracle_mod):
+    rng = np.random.default_rng(7)
+    T, d_in, d_out = 11, 33, 29
+    p_x, p_y0 = synth.normal_bf16(rng, (T, d_in), 1.0), synth.normal_bf16(rng, (T, d_out), 1.0)
+    a, b = synth.normal_bf16(rng, (1, d_in), 0.5), synth.normal_bf16(rng, (1, d_out), 0.5)
+    s = 3.0
+    res = oracle_mod.forward(p_x, p_y0, [a], [b], [1], [s], np.zeros(T, np.int32), np.full(T, 2, np.uint8))
+    X, Y0, av, bv = f64(p_x), f64(p_y0), f64(a)[0], f64(b)[0]
+    for t in range(T):
+        dot = sum(X[t, k] * av[k] for k in range(d_in))
+        for n in range(d_out):
+            assert res.y[t, n] == pytest.approx(Y0[t, n] + s * dot * bv[n], rel=1e-13, abs=1e-14)
+
+
+def test_token_permutation_invariance_is_bit_exact(oracle_mod):
+    p = synth.small_mixed(11, T=61, d_in=48, d_out=56, ranks=[2, 16, 5, 8], drop_frac=0.1)
+    base = run_forward(oracle_mod, p)
+    rng = np.random.default_rng(12)
+    order = rng.permutation(p.n_tokens)
+    res = oracle_mod.forward(p.x[order], p.y0[order], p.A, p.B, p.ranks, p.scales,
+                             p.batch.token_adapter[order], p.batch.token_kind[order])
+    assert np.array_equal(res.y, base.y[order])
+    # adapters listed in another order (ids remapped) give the same rows as well
+    remap = rng.permutation(p.n_adapters)            # new id of old adapter i is remap[i]
+    inv = np.argsort(remap)
+    ta = p.batch.token_adapter.copy()
+    live = ta >= 0
+    ta[live] = remap[ta[live]]
+    res2 = oracle_mod.forward(p.x, p.y0, [p.A[i] for i in inv], [p.B[i] for i in inv], p.ranks[inv], p.scales[inv],
+                              ta, p.batch.token_kind)
+    assert np.array_equal(res2.y, base.y)
+
+
+def test_exact_rational_brute_force(oracle_mod):
+    """Tiny shapes, bf16-exact grid inputs, exact arithmetic with fractions: the fp64 oracle must be
+    within a few ulp of the exact value (all products and sums here are in fact exactly representable)."""
+    rng = np.random.default_rng(21)
+    T, d_in, d_out = 7, 6, 5
+    ranks = [1, 3, 2]
+    scales = [0.5, 2.0, -1.25]
+    x, y0 = grid_bits(rng, (T, d_in)), grid_bits(rng, (T, d_out))
+    A = [grid_bits(rng, (r, d_in)) for r in ranks]
+    B = [grid_bits(rng, (r, d_out)) for r in ranks]
+    ta = np.array([2, 0, -1, 1, 1, 0, 2], np.int32)
+    tk = np.array([0, 2, 1, 0, 1, 2, 0], np.uint8)
+    res = oracle_mod.forward(x, y0, A, B, ranks, scales, ta, tk)
+    Fx = [[Fraction(float(v)) for v in row] for row in synth.bf16_bits_to_f32(x)]
+    Fy = [[Fraction(float(v)) for v in row] for row in synth.bf16_bits_to_f32(y0)]
+    FA = [[[Fraction(float(v)) for v in row] for row in synth.bf16_bits_to_f32(a)] for a in A]
+    FB = [[[Fraction(float(v)) for v in row] for row in synth.bf16_bits_to_f32(b)] for b in B]
+    for t in range(T):
+        a = int(ta[t])
+        for n in range(d_out):
+            exact = Fy[t][n]
+            if a >= 0:
+                upd = Fraction(0)
+                for j in range(ranks[a]):
+                    hj = sum(Fx[t][k] * FA[a][j][k] for k in range(d_in))
+                    upd += hj * FB[a][j][n]
+                exact += Fraction(scales[a]) * upd
+            assert abs(Fraction(res.y[t, n]) - exact) <= abs(exact) * Fraction(1, 2 ** 50)
+    # saved h of the fine-tune tokens, exact as well; layout: (kind 0, adapter 1) rows first, then adapter 2
+    #   token 3 -> adapter 1 (rank 3) at offset 0; tokens 0 and 6 -> adapter 2 (rank 2) at offsets 3 and 5
+    expect_h = []
+    for t, a in ((3, 1), (0, 2), (6, 2)):
+        for j in range(ranks[a]):
+            expect_h.append(sum(Fx[t][k] * FA[a][j][k] for k in range(d_in)))
+    assert res.h.shape[0] == len(expect_h) == 7
+    for got, ex in zip(res.h, expect_h):
+        assert Fraction(got) == ex
+
+
+def test_rows_without_adapter_and_empty_batch(oracle_mod):
+    p = synth.small_mixed(31, T=20, d_in=16, d_out=24, ranks=[4, 4], drop_frac=0.5)
+    res = run_forward(oracle_mod, p)
+    dead = p.batch.token_adapter < 0
+    assert dead.any() and (~dead).any()
+    assert np.array_equal(res.y[dead], f64(p.y0)[dead])
+    assert not np.array_equal(res.y[~dead], f64(p.y0)[~dead])
+    # adapter ids beyond the table and unknown kinds are treated like "no adapter"
+    ta = p.batch.token_adapter.copy()
+    tk = p.batch.token_kind.copy()
+    ta[0], tk[1] = 2, 3
+    ta[1] = 0
+    res2 = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, ta, tk)
+    assert np.array_equal(res2.y[:2], f64(p.y0)[:2])
+    empty = oracle_mod.forward(np.zeros((0, 16), np.uint16), np.zeros((0, 24), np.uint16), p.A, p.B, p.ranks, p.scales,
+                               np.zeros(0, np.int32), np.zeros(0, np.uint8))
+    assert empty.y.shape == (0, 24) and empty.h.shape == (0,) and empty.segments.n_segments == 0
+
+
+def test_scale_linearity(oracle_mod):
+    p = synth.small_mixed(41, T=33, d_in=40, d_out=24, ranks=[8, 2, 5], scales=[1.0, 0.5, 4.0])
+    r1 = run_forward(oracle_mod, p)
+    p.scales = p.scales * np.float32(2.0)
+    r2 = run_forward(oracle_mod, p)
+    y0 = f64(p.y0)
+    np.testing.assert_allclose(r2.y - y0, 2.0 * (r1.y - y0), rtol=1e-12, atol=1e-13)
+    assert np.array_equal(r1.h, r2.h)          # the saved h is unscaled
+
+
+def test_saved_h_layout_and_values(oracle_mod):
+    """h rows of fine-tune tokens sit at offsets given by an independent reconstruction of the metadata
+    (Python's stable sort), with values x A^T from a library matmul."""
+    p = synth.small_mixed(51, T=70, d_in=32, d_out=16, ranks=[3, 8, 1, 16], drop_frac=0.15)
+    res = run_forward(oracle_mod, p)
+    ta, tk = p.batch.token_adapter, p.batch.token_kind
+    order = sorted((t for t in range(p.n_tokens) if ta[t] >= 0), key=lambda t: (int(tk[t]), int(ta[t])))
+    X = f64(p.x)
+    expect = []
+    for t in order:
+        if tk[t] == synth.KIND_FINETUNE:
+            expect.extend((X[t] @ f64(p.A[ta[t]]).T).tolist())
+    np.testing.assert_allclose(res.h, np.asarray(expect), rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------------------
+# segment metadata
+# ---------------------------------------------------------------------------------------------
+def python_segments(ta, tk, ranks):
+    n_ad = len(ranks)
+    live = [t for t in range(len(ta)) if 0 <= ta[t] < n_ad and tk[t] <= 2]
+    order = sorted(live, key=lambda t: (int(tk[t]), int(ta[t])))   # sorted() is stable
+    starts, sad, skd, hoff = [0], [], [], [0]
+    for i, t in enumerate(order):
+        if i + 1 == len(order) or (tk[order[i + 1]], ta[order[i + 1]]) != (tk[t], ta[t]):
+            sad.append(int(ta[t]))
+            skd.append(int(tk[t]))
+            length = i + 1 - starts[-1]
+            hoff.append(hoff[-1] + (length * int(ranks[ta[t]]) if tk[t] == 0 else 0))
+            starts.append(i + 1)
+    return order, starts, sad, skd, hoff
+
+
+def test_segments_hand_worked_example(oracle_mod):
+    """Worked by hand from the definition: batch order fine-tune | prefill | decode (Algorithm 1), grouped by
+    adapter inside a kind, ties in original token order."""
+    #            t: 0  1  2  3  4   5  6  7  8  9 10 11
+    ta = np.array([1, 0, 1, -1, 0,  2, 1, 0, 2, 0, 1, 5], np.int32)
+    tk = np.array([2, 0, 0, 0,  1,  2, 0, 2, 2, 0, 2, 0], np.uint8)
+    ranks = np.array([4, 8, 2], np.int32)     # adapter 5 does not exist -> token 11 is dropped, as is token 3
+    seg = oracle_mod.build_segments(ta, tk, ranks)
+    assert seg.perm.tolist() == [1, 9, 2, 6, 4, 7, 0, 10, 5, 8]
+    assert seg.seg_starts.tolist() == [0, 2, 4, 5, 6, 8, 10]
+    assert seg.seg_adapter.tolist() == [0, 1, 0, 0, 1, 2]
+    assert seg.seg_kind.tolist() == [0, 0, 1, 2, 2, 2]
+    assert seg.h_offsets.tolist() == [0, 8, 24, 24, 24, 24, 24]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_segments_match_library_stable_sort(oracle_mod, seed):
+    rng = np.random.default_rng(100 + seed)
+    T = int(rng.integers(0, 400))
+    n_ad = int(rng.integers(1, 40))
+    ranks = rng.integers(1, 65, size=n_ad).astype(np.int32)
+    ta = rng.integers(-1, n_ad + 1, size=T).astype(np.int32)
+    tk = rng.integers(0, 4, size=T).astype(np.uint8)
+    seg = oracle_mod.build_segments(ta, tk, ranks)
+    order, starts, sad, skd, hoff = python_segments(ta, tk, ranks)
+    assert seg.perm.tolist() == order
+    assert seg.seg_starts.tolist() == starts
+    assert seg.seg_adapter.tolist() == sad
+    assert seg.seg_kind.tolist() == skd
+    assert seg.h_offsets.tolist() == hoff
+
+
+def test_config1_structure(oracle_mod):
+    p = synth.config1()
+    seg = oracle_mod.build_segments(p.batch.token_adapter, p.batch.token_kind, p.ranks)
+    assert p.n_tokens == 102
+    assert seg.seg_starts[:3].tolist() == [0, 64, 96] and seg.seg_kind[:2].tolist() == [0, 1]
+    assert seg.perm[:96].tolist() == list(range(96))
+    assert seg.h_offsets[1:].tolist() == [64 * 8] * seg.n_segments
+    assert sorted(seg.perm.tolist()) == list(range(102))
+
+
+# ---------------------------------------------------------------------------------------------
+# backward
+# ---------------------------------------------------------------------------------------------
+def loss_of(oracle_mod, x, y0, A, B, ranks, scales, ta, tk, dy):
+    res = oracle_mod.forward(x, y0, A, B, ranks, scales, ta, tk)
+    ft = (tk == 0) & (ta >= 0)
+    return float(np.sum(f64(dy)[ft] * res.y[ft]))
+
+
+def test_backward_against_exact_differences(oracle_mod):
+    """L = sum dy*y over fine-tune rows is linear in each single input element, so a one-sided difference
+    with a bf16-representable step is exact: L(e + delta) - L(e) = delta * dL/de."""
+    rng = np.random.default_rng(61)
+    T, d_in, d_out = 10, 7, 6
+    ranks = np.array([2, 3], np.int32)
+    scales = np.array([0.75, -1.5], np.float32)
+    x, y0, dy = grid_bits(rng, (T, d_in), -64, 64), grid_bits(rng, (T, d_out)), grid_bits(rng, (T, d_out), -64, 64)
+    A = [grid_bits(rng, (int(r), d_in), -64, 64) for r in ranks]
+    B = [grid_bits(rng, (int(r), d_out), -64, 64) for r in ranks]
+    ta = np.array([0, 1, 1, 0, -1, 1, 0, 0, 1, 1], np.int32)
+    tk = np.array([0, 0, 1, 0, 0, 2, 0, 1, 0, 0], np.uint8)
+    bw = oracle_mod.backward(x, dy, None, A, B, ranks, scales, ta, tk)
+    L0 = loss_of(oracle_mod, x, y0, A, B, ranks, scales, ta, tk, dy)
+    delta = 1.0 / 64.0
+
+    def bump(bits, idx):
+        v = synth.bf16_bits_to_f32(bits).copy()
+        v[idx] += np.float32(delta)
+        out = synth.f32_to_bf16_bits(v)
+        assert synth.bf16_bits_to_f32(out)[idx] == v[idx]
+        return out
+
+    for a in range(2):
+        for j in range(int(ranks[a])):
+            for k in range(d_in):
+                A2 = list(A)
+                A2[a] = bump(A[a], (j, k))
+                d = loss_of(oracle_mod, x, y0, A2, B, ranks, scales, ta, tk, dy) - L0
+                assert d == pytest.approx(delta * bw.dA[a][j, k], rel=1e-9, abs=1e-9)
+            for n in range(d_out):
+                B2 = list(B)
+                B2[a] = bump(B[a], (j, n))
+                d = loss_of(oracle_mod, x, y0, A, B2, ranks, scales, ta, tk, dy) - L0
+                assert d == pytest.approx(delta * bw.dB[a][j, n], rel=1e-9, abs=1e-9)
+    for t in range(T):
+        for k in range(d_in):
+            d = loss_of(oracle_mod, bump(x, (t, k)), y0, A, B, ranks, scales, ta, tk, dy) - L0
+            assert d == pytest.approx(delta * bw.dx[t, k], rel=1e-9, abs=1e-9)
+    assert np.abs(bw.dA[0]).max() > 0 and np.abs(bw.dB[1]).max() > 0 and np.abs(bw.dx).max() > 0
+    # rows that are not fine-tune rows get no gradient
+    assert np.all(bw.dx[(tk != 0) | (ta < 0)] == 0.0)
+
+
+def test_backward_single_adapter_dense_form(oracle_mod):
+    rng = np.random.default_rng(71)
+    T, d_in, d_out, r, s = 40, 48, 36, 8, 2.0
+    x, dy, dx0 = (synth.normal_bf16(rng, (T, d_in), 1.0), synth.normal_bf16(rng, (T, d_out), 1.0),
+                  synth.normal_bf16(rng, (T, d_in), 1.0))
+    A, B = synth.normal_bf16(rng, (r, d_in), 0.02), synth.normal_bf16(rng, (r, d_out), 0.02)
+    bw = oracle_mod.backward(x, dy, dx0, [A], [B], [r], [s], np.zeros(T, np.int32), np.zeros(T, np.uint8))
+    X, DY, Af, Bf = f64(x), f64(dy), f64(A), f64(B)
+    G = DY @ Bf.T
+    np.testing.assert_allclose(bw.dB[0], s * (X @ Af.T).T @ DY, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(bw.dA[0], s * G.T @ X, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(bw.dx, f64(dx0) + s * G @ Af, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(bw.g, G.reshape(-1), rtol=1e-11, atol=1e-12)
