@@ -1,0 +1,156 @@
+/*
+ * lqlora — segmented multi-adapter LoRA forward/backward for AMD MI355X (gfx950), C ABI.
+ *
+ * The operation is the one the paper's SMLM kernel ("Segmented Multi-LoRA Multiplication",
+ * Section 1 and Section 3.3) performs for ONE linear layer over ONE mixed batch: all
+ * (token segment, adapter) LoRA products in one call, with fine-tuning, evaluation/prefill
+ * and decode requests in the same batch, adapters kept as separate per-layer tensors
+ * (never concatenated, so a pointer can be swapped at run time), and a run-time scale:
+ *
+ *     for every segment g with adapter a, rank r_a, scale s_a and token rows R_g:
+ *         h[t, :]  = x[t, :] * A_a^T                     t in R_g      (A_a is [r_a, d_in])
+ *         y[t, :] += s_a * h[t, :] * B_a                 t in R_g      (B_a is [r_a, d_out])
+ *         fine-tune segments also store the unscaled h rows (fp32) for the backward pass.
+ *
+ * Conventions for every entry point
+ *   - Every pointer is a DEVICE pointer (HBM) unless its name starts with host_.  The
+ *     library never allocates, frees or synchronises: each call validates its host scalars,
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the null stream)
+ *     and returns.  The caller owns all buffers, including the workspace, and must keep
+ *     them alive until the stream has passed the call.
+ *   - bf16 tensors are row-major with an explicit leading dimension in ELEMENTS; base
+ *     pointers must be 16-byte aligned and d_in, d_out and the leading dimensions must be
+ *     multiples of 8 (else LQ_ERR_UNSUPPORTED).  Adapter matrices are dense row-major,
+ *     16-byte aligned.  Ranks 1..LQ_MAX_RANK are supported, different per adapter.
+ *   - Errors are return codes; nothing throws or aborts.  Host-side validation returns
+ *     before anything is launched.  Metadata that only the device can see (adapter id out
+ *     of range, rank out of range) never causes an out-of-bounds access: the segment is
+ *     skipped and bit 0 of the int32 at workspace offset 0 is set (the caller may zero and
+ *     read that word; the library only ever ORs into it).
+ *   - x and y must not alias.  Rows of y that no segment covers are untouched bit for bit.
+ *   - Calls on different streams that share a workspace race; give each stream its own.
+ */
+#ifndef LQLORA_H
+#define LQLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LQ_OK = 0,
+    LQ_ERR_INVALID_ARG = 1, /* null pointer, negative size, ld < d, unknown variant */
+    LQ_ERR_UNSUPPORTED = 2, /* alignment / multiple-of-8 / rank or adapter-count limits */
+    LQ_ERR_WORKSPACE = 3,   /* workspace missing or smaller than the *_workspace_bytes answer */
+    LQ_ERR_HIP = 4          /* a HIP launch reported an error */
+} lq_status;
+
+/* Request kinds (Section 3.3: fine-tuning, evaluation, prefilling, decoding; evaluation is
+ * structurally a prefill, so it shares LQ_SEG_PREFILL).  The numeric order is the batch
+ * order of Algorithm 1: fine-tune | prefill+evaluation | decode. */
+enum { LQ_SEG_FINETUNE = 0, LQ_SEG_PREFILL = 1, LQ_SEG_DECODE = 2 };
+
+/* LQ_VARIANT_SPLIT: shrink kernel then expand kernel.  LQ_VARIANT_FUSED: one launch. */
+enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1 };
+
+#define LQ_MAX_RANK 128
+#define LQ_MAX_ADAPTERS 4096
+
+const char* lora_status_string(lq_status status);
+
+/* ---------------------------------------------------------------------------------------------
+ * Segment metadata builder (integer only, deterministic, bit-exact).
+ *
+ * Turns per-token (adapter, kind) into the segment tables the forward consumes.  The paper only
+ * fixes the batch order fine-tune | prefill+evaluation | decode (Algorithm 1 derives its offsets
+ * from it); the tables are that order refined by adapter: a STABLE sort of token indices by
+ * (kind, adapter), one segment per distinct key, ties in original token order.  Tokens whose
+ * adapter id is outside [0, n_adapters) (use -1 for base-model-only requests) or whose kind is
+ * not one of the three are left out of perm.
+ *
+ *   in   token_adapter int32[n_tokens], token_kind uint8[n_tokens], ranks int32[n_adapters]
+ *   out  perm        int32[n_tokens]       token indices in segment order (first seg_starts[n_seg] valid)
+ *        seg_starts  int32[max_segments+1] positions in perm; seg_starts[n_seg] = number of live tokens
+ *        seg_adapter int32[max_segments]
+ *        seg_kind    uint8[max_segments]
+ *        h_offsets   int64[max_segments+1] element offset of each segment's saved h in h_out:
+ *                                          running sum of len * rank over fine-tune segments
+ *        n_segments  int32[1]              device scalar
+ *   max_segments must be >= min(n_tokens, 3 * n_adapters).  n_tokens = 0 is valid (n_segments = 0).
+ *   workspace: lora_build_workspace_bytes(n_tokens, n_adapters) bytes, contents irrelevant.
+ * ------------------------------------------------------------------------------------------- */
+size_t lora_build_workspace_bytes(int32_t n_tokens, int32_t n_adapters);
+
+lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token_kind, int32_t n_tokens,
+                              const int32_t* ranks, int32_t n_adapters,
+                              int32_t* perm, int32_t* seg_starts, int32_t* seg_adapter, uint8_t* seg_kind,
+                              int64_t* h_offsets, int32_t* n_segments, int32_t max_segments,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Forward (Section 3.3; formula above).
+ *
+ *   x        bf16 [n_tokens, d_in], leading dimension ldx          (read only)
+ *   y        bf16 [n_tokens, d_out], leading dimension ldy         (read-modify-write, one rounding
+ *                                                                   to nearest even per call)
+ *   A_ptrs   [n_adapters] device array of device pointers to bf16 [r_a, d_in]
+ *   B_ptrs   [n_adapters] device array of device pointers to bf16 [r_a, d_out]
+ *   ranks    int32[n_adapters], scales float[n_adapters] (applied in fp32 to h * B before the add)
+ *   max_rank host scalar >= every rank in use (sizes the h scratch); <= LQ_MAX_RANK
+ *   perm     int32, row of x / y for each position of the segment order; NULL = identity
+ *   seg_*    as produced by lora_build_segments (or by the caller); n_segments is a device scalar,
+ *            max_segments the capacity of the tables (bounds the launch grid)
+ *   h_out    float, receives the UNSCALED h rows of fine-tune segments, segment g at
+ *            h_out + h_offsets[g], row-major [len_g, r_a]; h_out / h_offsets may be NULL, then
+ *            nothing is saved (inference-only batches)
+ *   variant  LQ_VARIANT_SPLIT or LQ_VARIANT_FUSED; both give the same y and h_out up to fp32
+ *            summation order
+ *   workspace lora_forward_workspace_bytes(...) bytes.  n_tokens = 0 returns LQ_OK with no launch.
+ * ------------------------------------------------------------------------------------------- */
+size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,
+                                    int32_t variant);
+
+lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
+                                 int32_t d_in, int32_t d_out,
+                                 const void* const* A_ptrs, const void* const* B_ptrs,
+                                 const int32_t* ranks, const float* scales, int32_t n_adapters, int32_t max_rank,
+                                 const int32_t* perm, int32_t n_tokens,
+                                 const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
+                                 const int32_t* n_segments, int32_t max_segments,
+                                 float* h_out, const int64_t* h_offsets,
+                                 int32_t variant, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Backward of the forward above for FINE-TUNE segments (other kinds are skipped).  The paper
+ * leaves this to autograd, one call per LoRA linear, and names a dedicated kernel as future
+ * work (Section 4.2, Appendix A).  Exact gradient of the forward as defined here, with
+ * g = dy * B_a^T:
+ *     dB_a += s_a * h^T dy        dA_a += s_a * g^T x        dx[t, :] += s_a * g[t, :] * A_a
+ *
+ *   dy       bf16 [n_tokens, d_out] (rows of fine-tune tokens are read)
+ *   dx       bf16 [n_tokens, d_in], read-modify-write on fine-tune rows only
+ *   h_saved  float, the h_out written by the forward (same h_offsets)
+ *   dA_ptrs / dB_ptrs  [n_adapters] device arrays of device pointers to float [r_a, d_in] / [r_a, d_out],
+ *            accumulated into (caller zeroes); entries of adapters without fine-tune segments may be NULL
+ *   workspace lora_backward_workspace_bytes(...) bytes.
+ * ------------------------------------------------------------------------------------------- */
+size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out);
+
+lq_status lora_segmented_backward(const void* x, int64_t ldx, const void* dy, int64_t lddy, void* dx, int64_t lddx,
+                                  int32_t d_in, int32_t d_out,
+                                  const void* const* A_ptrs, const void* const* B_ptrs,
+                                  float* const* dA_ptrs, float* const* dB_ptrs,
+                                  const int32_t* ranks, const float* scales, int32_t n_adapters, int32_t max_rank,
+                                  const int32_t* perm, int32_t n_tokens,
+                                  const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
+                                  const int32_t* n_segments, int32_t max_segments,
+                                  const float* h_saved, const int64_t* h_offsets,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LQLORA_H */

@@ -1,0 +1,221 @@
+"""Thin ctypes binding over liblqlora.so (include/lqlora.h).  Argument marshalling only: every step
+of the path runs in the library's HIP kernels.  PyTorch is used for device memory and streams.
+
+There is no fallback: if the library has not been built (python -m paper_2511_00101_amd.build)
+loading raises, and every entry point raises LqError on a non-zero status.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, LQ_ERR_HIP = range(5)
+LQ_SEG_FINETUNE, LQ_SEG_PREFILL, LQ_SEG_DECODE = 0, 1, 2
+LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED = 0, 1
+LQ_MAX_RANK = 128
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblqlora.so")
+_lib = None
+
+_i32, _i64, _vp, _sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+
+_SIGNATURES = {
+    "lora_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "lora_build_workspace_bytes": (_sz, [_i32, _i32]),
+    "lora_build_segments": (ctypes.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
+    "lora_forward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
+    "lora_segmented_forward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _i32,
+                                              _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
+    "lora_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
+    "lora_segmented_backward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp,
+                                               _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
+                                               _vp, _vp, _vp, _sz, _vp]),
+}
+
+
+class LqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lora_status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_00101_amd.build` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def exported_symbols() -> List[str]:
+    return list(_SIGNATURES)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream) or None
+
+
+def lora_status_string(status: int) -> str:
+    return lib().lora_status_string(int(status)).decode()
+
+
+def lora_build_workspace_bytes(n_tokens: int, n_adapters: int) -> int:
+    return int(lib().lora_build_workspace_bytes(n_tokens, n_adapters))
+
+
+def lora_forward_workspace_bytes(n_tokens: int, max_rank: int, d_in: int, d_out: int, variant: int) -> int:
+    return int(lib().lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant))
+
+
+def lora_backward_workspace_bytes(n_tokens: int, max_rank: int, d_in: int, d_out: int) -> int:
+    return int(lib().lora_backward_workspace_bytes(n_tokens, max_rank, d_in, d_out))
+
+
+@dataclass
+class SegmentTables:
+    """Device buffers the builder fills and the forward/backward read."""
+    perm: torch.Tensor         # int32[n_tokens]
+    seg_starts: torch.Tensor   # int32[max_segments + 1]
+    seg_adapter: torch.Tensor  # int32[max_segments]
+    seg_kind: torch.Tensor     # uint8[max_segments]
+    h_offsets: torch.Tensor    # int64[max_segments + 1]
+    n_segments: torch.Tensor   # int32[1]
+    max_segments: int
+    n_tokens: int
+
+    @staticmethod
+    def empty(n_tokens: int, n_adapters: int, device="cuda", max_segments: Optional[int] = None) -> "SegmentTables":
+        if max_segments is None:
+            max_segments = min(n_tokens, 3 * n_adapters)
+        dev = torch.device(device)
+        return SegmentTables(
+            perm=torch.zeros(max(n_tokens, 1), dtype=torch.int32, device=dev),
+            seg_starts=torch.zeros(max_segments + 1, dtype=torch.int32, device=dev),
+            seg_adapter=torch.zeros(max(max_segments, 1), dtype=torch.int32, device=dev),
+            seg_kind=torch.zeros(max(max_segments, 1), dtype=torch.uint8, device=dev),
+            h_offsets=torch.zeros(max_segments + 1, dtype=torch.int64, device=dev),
+            n_segments=torch.zeros(1, dtype=torch.int32, device=dev),
+            max_segments=max_segments, n_tokens=n_tokens)
+
+    def to_host(self):
+        """Copies the tables back (synchronises); trims to the live part."""
+        n = int(self.n_segments.item())
+        starts = self.seg_starts[: n + 1].cpu().numpy()
+        n_live = int(starts[n]) if n >= 0 else 0
+        return dict(perm=self.perm[:n_live].cpu().numpy(), seg_starts=starts,
+                    seg_adapter=self.seg_adapter[:n].cpu().numpy(), seg_kind=self.seg_kind[:n].cpu().numpy(),
+                    h_offsets=self.h_offsets[: n + 1].cpu().numpy(), n_segments=n)
+
+
+def lora_build_segments(token_adapter: torch.Tensor, token_kind: torch.Tensor, ranks: torch.Tensor,
+                        out: SegmentTables, workspace: Optional[torch.Tensor] = None, stream=None) -> SegmentTables:
+    n_tokens = int(token_adapter.shape[0])
+    n_adapters = int(ranks.shape[0])
+    assert token_adapter.dtype == torch.int32 and token_kind.dtype == torch.uint8 and ranks.dtype == torch.int32
+    assert token_adapter.is_contiguous() and token_kind.is_contiguous() and ranks.is_contiguous()
+    st = lib().lora_build_segments(_ptr(token_adapter) if n_tokens else None, _ptr(token_kind) if n_tokens else None,
+                                   n_tokens, _ptr(ranks), n_adapters,
+                                   _ptr(out.perm), _ptr(out.seg_starts), _ptr(out.seg_adapter), _ptr(out.seg_kind),
+                                   _ptr(out.h_offsets), _ptr(out.n_segments), out.max_segments,
+                                   _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                   _stream(stream))
+    if st != LQ_OK:
+        raise LqError(st, "lora_build_segments")
+    return out
+
+
+@dataclass
+class AdapterTable:
+    """Per-adapter weights of one linear layer, kept as separate tensors (never concatenated) plus the
+    device pointer tables the library takes.  Swapping an adapter = rewriting one pointer."""
+    A: List[torch.Tensor]      # bf16 [r, d_in]
+    B: List[torch.Tensor]      # bf16 [r, d_out]
+    ranks: torch.Tensor        # int32[n]
+    scales: torch.Tensor       # float32[n]
+    A_ptrs: torch.Tensor       # int64[n]
+    B_ptrs: torch.Tensor       # int64[n]
+    max_rank: int
+
+    @staticmethod
+    def from_tensors(A: Sequence[torch.Tensor], B: Sequence[torch.Tensor], scales, device="cuda") -> "AdapterTable":
+        dev = torch.device(device)
+        A = [a.contiguous() for a in A]
+        B = [b.contiguous() for b in B]
+        ranks = torch.tensor([a.shape[0] for a in A], dtype=torch.int32, device=dev)
+        sc = torch.as_tensor(np.asarray(scales, dtype=np.float32)).to(dev)
+        ap = torch.tensor([a.data_ptr() for a in A], dtype=torch.int64, device=dev)
+        bp = torch.tensor([b.data_ptr() for b in B], dtype=torch.int64, device=dev)
+        return AdapterTable(list(A), list(B), ranks, sc, ap, bp, max(int(a.shape[0]) for a in A))
+
+    @property
+    def n_adapters(self) -> int:
+        return len(self.A)
+
+
+def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,
+                           h_out: Optional[torch.Tensor], workspace: torch.Tensor,
+                           variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None) -> None:
+    assert x.dtype == torch.bfloat16 and y.dtype == torch.bfloat16
+    assert x.stride(1) == 1 and y.stride(1) == 1
+    n_tokens, d_in = int(x.shape[0]), int(x.shape[1])
+    d_out = int(y.shape[1])
+    st = lib().lora_segmented_forward(
+        _ptr(x), x.stride(0), _ptr(y), y.stride(0), d_in, d_out,
+        _ptr(adapters.A_ptrs), _ptr(adapters.B_ptrs), _ptr(adapters.ranks), _ptr(adapters.scales),
+        adapters.n_adapters, adapters.max_rank,
+        _ptr(seg.perm) if use_perm else None, n_tokens,
+        _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
+        _ptr(h_out), _ptr(seg.h_offsets) if h_out is not None else None,
+        variant, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != LQ_OK:
+        raise LqError(st, "lora_segmented_forward")
+
+
+def lora_segmented_backward(x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, adapters: AdapterTable,
+                            dA_ptrs: torch.Tensor, dB_ptrs: torch.Tensor, seg: SegmentTables,
+                            h_saved: torch.Tensor, workspace: torch.Tensor, use_perm: bool = True, stream=None) -> None:
+    assert x.dtype == torch.bfloat16 and dy.dtype == torch.bfloat16 and dx.dtype == torch.bfloat16
+    n_tokens, d_in = int(x.shape[0]), int(x.shape[1])
+    d_out = int(dy.shape[1])
+    st = lib().lora_segmented_backward(
+        _ptr(x), x.stride(0), _ptr(dy), dy.stride(0), _ptr(dx), dx.stride(0), d_in, d_out,
+        _ptr(adapters.A_ptrs), _ptr(adapters.B_ptrs), _ptr(dA_ptrs), _ptr(dB_ptrs),
+        _ptr(adapters.ranks), _ptr(adapters.scales), adapters.n_adapters, adapters.max_rank,
+        _ptr(seg.perm) if use_perm else None, n_tokens,
+        _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
+        _ptr(h_saved), _ptr(seg.h_offsets), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream))
+    if st != LQ_OK:
+        raise LqError(st, "lora_segmented_backward")
+
+
+# ---- plumbing between numpy bf16 bit patterns and device tensors ------------------------------------------------
+def bf16_from_bits(bits: np.ndarray, device="cuda") -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(device)
+
+
+def bits_from_bf16(t: torch.Tensor) -> np.ndarray:
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def workspace(n_bytes: int, device="cuda") -> torch.Tensor:
+    return torch.zeros((max(n_bytes, 256) + 7) // 8, dtype=torch.int64, device=device)

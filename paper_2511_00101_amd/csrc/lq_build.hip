@@ -1,0 +1,200 @@
+// Segment-metadata builder: per-token (adapter, kind) -> perm / seg_starts / seg_adapter / seg_kind /
+// h_offsets / n_segments.  One workgroup of 16 waves performs a stable counting sort on the key
+// kind * n_adapters + adapter (the batch order fine-tune | prefill+evaluation | decode of
+// Algorithm 1, refined by adapter) and run-length encodes the non-empty keys.  Integer only; the
+// result is unique, so it is compared bit for bit with the CPU oracle.
+#include "lq_common.h"
+
+namespace lq {
+namespace {
+
+constexpr int kBuildThreads = 1024;
+constexpr int kBuildWaves = kBuildThreads / kWave;
+constexpr int kBuildLdsBudget = 60000;  // bytes of dynamic LDS used for the histograms when they fit
+
+__device__ __forceinline__ int block_exclusive_scan(int v, int* s_tot, int& total)
+{
+    const int lane = lane_id(), w = (int)threadIdx.x / kWave;
+    const int incl = wave_inclusive_scan(v);
+    __syncthreads();  // s_tot may still be read from a previous scan
+    if (lane == kWave - 1) s_tot[w] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < kBuildWaves; ++i) {
+        const int t = s_tot[i];
+        if (i < w) before += t;
+        all += t;
+    }
+    total = all;
+    return before + incl - v;
+}
+
+__device__ __forceinline__ long long block_exclusive_scan64(long long v, long long* s_tot, long long& total)
+{
+    const int lane = lane_id(), w = (int)threadIdx.x / kWave;
+    const long long incl = wave_inclusive_scan64(v);
+    __syncthreads();
+    if (lane == kWave - 1) s_tot[w] = incl;
+    __syncthreads();
+    long long before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < kBuildWaves; ++i) {
+        const long long t = s_tot[i];
+        if (i < w) before += t;
+        all += t;
+    }
+    total = all;
+    return before + incl - v;
+}
+
+__device__ __forceinline__ int token_key(const int32_t* __restrict__ token_adapter,
+                                         const uint8_t* __restrict__ token_kind, int t, int n_adapters)
+{
+    const int a = token_adapter[t];
+    const int k = token_kind[t];
+    return (a >= 0 && a < n_adapters && k <= LQ_SEG_DECODE) ? k * n_adapters + a : -1;
+}
+
+__global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
+    const int32_t* __restrict__ token_adapter, const uint8_t* __restrict__ token_kind, int n_tokens,
+    const int32_t* __restrict__ ranks, int n_adapters,
+    int32_t* __restrict__ perm, int32_t* __restrict__ seg_starts, int32_t* __restrict__ seg_adapter,
+    uint8_t* __restrict__ seg_kind, int64_t* __restrict__ h_offsets, int32_t* __restrict__ n_segments,
+    int32_t* ws_hist, int use_lds)
+{
+    extern __shared__ int32_t lds_hist[];
+    __shared__ int s_tot[kBuildWaves];
+    __shared__ long long s_tot64[kBuildWaves];
+
+    const int tid = (int)threadIdx.x, lane = lane_id(), w = tid / kWave;
+    const int n_keys = 3 * n_adapters;
+    const int n_entries = n_keys * kBuildWaves;
+    // hist[key * 16 + wave]: tokens with that key in that wave's token range; scanned in place into
+    // the position in perm where that wave's first such token goes.
+    int32_t* hist = use_lds ? lds_hist : ws_hist;
+
+    for (int i = tid; i < n_entries; i += kBuildThreads) hist[i] = 0;
+    __syncthreads();
+
+    // each wave owns a contiguous token range (a multiple of 64 long), walked 64 tokens at a time
+    int per_wave = (n_tokens + kBuildWaves - 1) / kBuildWaves;
+    per_wave = (per_wave + kWave - 1) / kWave * kWave;
+    const int t_begin = min(n_tokens, w * per_wave);
+    const int t_end = min(n_tokens, t_begin + per_wave);
+
+    for (int base = t_begin; base < t_end; base += kWave) {
+        const int t = base + lane;
+        const int key = t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1;
+        if (key >= 0) atomicAdd(&hist[key * kBuildWaves + w], 1);
+    }
+    __syncthreads();
+
+    // exclusive scan over (key major, wave minor)
+    const int per_thread = (n_entries + kBuildThreads - 1) / kBuildThreads;
+    const int e_begin = min(n_entries, tid * per_thread);
+    const int e_end = min(n_entries, e_begin + per_thread);
+    int local = 0;
+    for (int i = e_begin; i < e_end; ++i) local += hist[i];
+    int n_live = 0;
+    int run = block_exclusive_scan(local, s_tot, n_live);
+    for (int i = e_begin; i < e_end; ++i) {
+        const int c = hist[i];
+        hist[i] = run;
+        run += c;
+    }
+    __syncthreads();
+
+    // segments = non-empty keys, in key order
+    const int keys_per_thread = (n_keys + kBuildThreads - 1) / kBuildThreads;
+    const int k_begin = min(n_keys, tid * keys_per_thread);
+    const int k_end = min(n_keys, k_begin + keys_per_thread);
+    int my_segs = 0;
+    long long my_h = 0;
+    for (int k = k_begin; k < k_end; ++k) {
+        const int start = hist[k * kBuildWaves];
+        const int next = (k + 1 < n_keys) ? hist[(k + 1) * kBuildWaves] : n_live;
+        const int cnt = next - start;
+        if (cnt > 0) {
+            ++my_segs;
+            if (k < n_adapters) my_h += (long long)cnt * ranks[k];  // kind 0 = fine-tune keeps h
+        }
+    }
+    int total_segs = 0;
+    long long total_h = 0;
+    int seg = block_exclusive_scan(my_segs, s_tot, total_segs);
+    long long h_run = block_exclusive_scan64(my_h, s_tot64, total_h);
+    for (int k = k_begin; k < k_end; ++k) {
+        const int start = hist[k * kBuildWaves];
+        const int next = (k + 1 < n_keys) ? hist[(k + 1) * kBuildWaves] : n_live;
+        const int cnt = next - start;
+        if (cnt > 0) {
+            const int kind = k / n_adapters, a = k - kind * n_adapters;
+            seg_starts[seg] = start;
+            seg_adapter[seg] = a;
+            seg_kind[seg] = (uint8_t)kind;
+            h_offsets[seg] = h_run;
+            if (kind == LQ_SEG_FINETUNE) h_run += (long long)cnt * ranks[a];
+            ++seg;
+        }
+    }
+    if (tid == 0) {
+        seg_starts[total_segs] = n_live;
+        h_offsets[total_segs] = total_h;
+        *n_segments = total_segs;
+    }
+    __syncthreads();  // all reads of the scanned offsets are done before the scatter advances them
+
+    // stable scatter: within a 64-token round, lanes with equal keys are ranked by lane order
+    for (int base = t_begin; base < t_end; base += kWave) {
+        const int t = base + lane;
+        const int key = t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1;
+        unsigned long long todo = __ballot(key >= 0);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int k = __shfl(key, leader, kWave);
+            const unsigned long long same = __ballot(key == k);
+            int slot = 0;
+            if (lane == leader) slot = atomicAdd(&hist[k * kBuildWaves + w], __popcll(same));
+            slot = __shfl(slot, leader, kWave);
+            if (key == k) perm[slot + __popcll(same & ((1ull << lane) - 1ull))] = t;
+            todo &= ~same;
+        }
+    }
+}
+
+}  // namespace
+}  // namespace lq
+
+extern "C" size_t lora_build_workspace_bytes(int32_t n_tokens, int32_t n_adapters)
+{
+    (void)n_tokens;
+    if (n_adapters < 0) n_adapters = 0;
+    return (size_t)lq::kWsHeaderBytes + (size_t)3 * (size_t)n_adapters * lq::kBuildWaves * sizeof(int32_t);
+}
+
+extern "C" lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token_kind, int32_t n_tokens,
+                                         const int32_t* ranks, int32_t n_adapters,
+                                         int32_t* perm, int32_t* seg_starts, int32_t* seg_adapter, uint8_t* seg_kind,
+                                         int64_t* h_offsets, int32_t* n_segments, int32_t max_segments,
+                                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (n_tokens < 0 || n_adapters <= 0 || max_segments < 0) return LQ_ERR_INVALID_ARG;
+    if (!ranks || !seg_starts || !seg_adapter || !seg_kind || !h_offsets || !n_segments) return LQ_ERR_INVALID_ARG;
+    if (n_tokens > 0 && (!token_adapter || !token_kind || !perm)) return LQ_ERR_INVALID_ARG;
+    if (n_adapters > LQ_MAX_ADAPTERS) return LQ_ERR_UNSUPPORTED;
+    const int64_t n_keys = 3 * (int64_t)n_adapters;
+    const int64_t need_segments = n_tokens < n_keys ? n_tokens : n_keys;
+    if (max_segments < need_segments) return LQ_ERR_INVALID_ARG;
+    const size_t hist_bytes = (size_t)n_keys * lq::kBuildWaves * sizeof(int32_t);
+    const int use_lds = hist_bytes <= (size_t)lq::kBuildLdsBudget;
+    int32_t* ws_hist = nullptr;
+    if (!use_lds) {
+        if (!workspace || workspace_bytes < lora_build_workspace_bytes(n_tokens, n_adapters)) return LQ_ERR_WORKSPACE;
+        ws_hist = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + lq::kWsHeaderBytes);
+    }
+    hipLaunchKernelGGL(lq::build_segments_kernel, dim3(1), dim3(lq::kBuildThreads), use_lds ? hist_bytes : 0,
+                       static_cast<hipStream_t>(stream), token_adapter, token_kind, n_tokens, ranks, n_adapters, perm,
+                       seg_starts, seg_adapter, seg_kind, h_offsets, n_segments, ws_hist, use_lds);
+    return hipGetLastError() == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+}

@@ -1,0 +1,89 @@
+"""Helpers for the GPU parity tests: move a synth.Problem to the device, run the library through the
+Python binding, fetch results back as numpy, compare with the oracle under the stated tolerances."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2511_00101_amd import binding as lq
+from paper_2511_00101_amd import synth
+
+# Acceptance bounds for bf16 inputs with fp32 accumulation and one bf16 rounding of y
+REL_FROBENIUS = 5e-3
+MAX_ABS = 3e-2
+
+
+class DeviceProblem:
+    def __init__(self, p: synth.Problem, device="cuda"):
+        self.p = p
+        self.x = lq.bf16_from_bits(p.x, device)
+        self.y = lq.bf16_from_bits(p.y0, device)
+        self.adapters = lq.AdapterTable.from_tensors([lq.bf16_from_bits(a, device) for a in p.A],
+                                                     [lq.bf16_from_bits(b, device) for b in p.B], p.scales, device)
+        self.token_adapter = torch.from_numpy(p.batch.token_adapter).to(device)
+        self.token_kind = torch.from_numpy(p.batch.token_kind).to(device)
+        self.seg = lq.SegmentTables.empty(p.n_tokens, p.n_adapters, device)
+        self.build_ws = lq.workspace(lq.lora_build_workspace_bytes(p.n_tokens, p.n_adapters), device)
+        self.h_out = None
+        self.dy = lq.bf16_from_bits(p.dy, device) if p.dy is not None else None
+
+    def build(self):
+        lq.lora_build_segments(self.token_adapter, self.token_kind, self.adapters.ranks, self.seg, self.build_ws)
+        return self.seg
+
+    def forward(self, variant=lq.LQ_VARIANT_SPLIT, h_elems=None, use_perm=True):
+        p = self.p
+        if h_elems is None:
+            h_elems = int(self.seg.h_offsets.max().item())
+        # poison so that rows the library does not write are recognisable
+        self.h_out = torch.full((max(h_elems, 1),), float("nan"), dtype=torch.float32, device=self.x.device)
+        ws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, self.adapters.max_rank, p.d_in, p.d_out, variant),
+                          self.x.device)
+        self.fwd_ws = ws
+        lq.lora_segmented_forward(self.x, self.y, self.adapters, self.seg, self.h_out, ws, variant, use_perm)
+        torch.cuda.synchronize()
+        return lq.bits_from_bf16(self.y), self.h_out[:h_elems].cpu().numpy(), int(ws[0].item() & 0xffffffff)
+
+
+def rel_frobenius(got: np.ndarray, ref: np.ndarray) -> float:
+    den = float(np.linalg.norm(ref.astype(np.float64).ravel()))
+    num = float(np.linalg.norm((got.astype(np.float64) - ref.astype(np.float64)).ravel()))
+    return num / den if den > 0 else num
+
+
+def assert_close(got: np.ndarray, ref: np.ndarray, what: str):
+    assert got.shape == ref.shape, what
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
+    if got.size == 0:
+        return
+    rf = rel_frobenius(got, ref)
+    ma = float(np.abs(got.astype(np.float64) - ref).max())
+    assert rf <= REL_FROBENIUS, f"{what}: relative Frobenius error {rf:.3e} > {REL_FROBENIUS}"
+    assert ma <= MAX_ABS, f"{what}: max abs error {ma:.3e} > {MAX_ABS}"
+
+
+def assert_tables_equal(dev_tables: dict, ref) -> None:
+    assert dev_tables["n_segments"] == ref.n_segments
+    assert np.array_equal(dev_tables["seg_starts"], ref.seg_starts)
+    assert np.array_equal(dev_tables["seg_adapter"], ref.seg_adapter)
+    assert np.array_equal(dev_tables["seg_kind"], ref.seg_kind)
+    assert np.array_equal(dev_tables["h_offsets"], ref.h_offsets)
+    assert np.array_equal(dev_tables["perm"], ref.perm)
+
+
+def check_forward(oracle_mod, p: synth.Problem, variant=lq.LQ_VARIANT_SPLIT):
+    """Full element-by-element comparison of one problem with the oracle."""
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    d = DeviceProblem(p)
+    d.build()
+    assert_tables_equal(d.seg.to_host(), ref.segments)
+    y_bits, h, err = d.forward(variant, h_elems=ref.segments.h_elems)
+    assert err == 0
+    y = synth.bf16_bits_to_f64(y_bits)
+    assert_close(y, ref.y, f"{p.name} y")
+    assert_close(h, ref.h, f"{p.name} h_out")
+    # rows no segment covers are untouched bit for bit
+    live = np.zeros(p.n_tokens, bool)
+    live[ref.segments.perm] = True
+    assert np.array_equal(y_bits[~live], p.y0[~live])
+    return y_bits, h, ref

@@ -1,0 +1,138 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_00101_amd import binding as lq
+from paper_2511_00101_amd import synth
+
+from gpu_util import DeviceProblem, assert_close, assert_tables_equal, check_forward
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [lq.LQ_VARIANT_SPLIT]
+
+
+# ---------------------------------------------------------------------------------------------------
+# segment metadata: bit exact
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("T,n_ad", [(0, 3), (1, 1), (63, 4), (64, 4), (65, 7), (1000, 64), (4097, 33), (8192, 32),
+                                    (5000, 300), (20000, 1000)])
+def test_build_segments_bit_exact(oracle_mod, T, n_ad):
+    rng = np.random.default_rng(T * 131 + n_ad)
+    ranks = rng.integers(1, 65, size=n_ad).astype(np.int32)
+    ta = rng.integers(-1, n_ad + 1, size=T).astype(np.int32)       # includes -1 and one id beyond the table
+    tk = rng.integers(0, 4, size=T).astype(np.uint8)               # includes one unknown kind
+    if T > 100:  # long runs as well as scattered tokens
+        ta[: T // 3] = 1 % n_ad
+        tk[: T // 3] = 0
+    ref = oracle_mod.build_segments(ta, tk, ranks)
+    seg = lq.SegmentTables.empty(T, n_ad)
+    ws = lq.workspace(lq.lora_build_workspace_bytes(T, n_ad))
+    lq.lora_build_segments(torch.from_numpy(ta).cuda(), torch.from_numpy(tk).cuda(), torch.from_numpy(ranks).cuda(),
+                           seg, ws)
+    assert_tables_equal(seg.to_host(), ref)
+
+
+def test_build_segments_configs(oracle_mod):
+    for p in (synth.config1(), synth.config2()):
+        d = DeviceProblem(p)
+        d.build()
+        assert_tables_equal(d.seg.to_host(), oracle_mod.build_segments(p.batch.token_adapter, p.batch.token_kind, p.ranks))
+    for b, n_ad, ranks in ((synth.batch_unified(np.random.default_rng(3500)), 32, [16] * 32),
+                           (synth.batch_zipf(np.random.default_rng(4500)), 32, [(8, 16, 32, 64)[i % 4] for i in range(32)]),
+                           (synth.config5_batch(), 16, [32] * 16)):
+        ranks = np.asarray(ranks, np.int32)
+        seg = lq.SegmentTables.empty(b.n_tokens, n_ad)
+        lq.lora_build_segments(torch.from_numpy(b.token_adapter).cuda(), torch.from_numpy(b.token_kind).cuda(),
+                               torch.from_numpy(ranks).cuda(), seg, lq.workspace(lq.lora_build_workspace_bytes(b.n_tokens, n_ad)))
+        assert_tables_equal(seg.to_host(), oracle_mod.build_segments(b.token_adapter, b.token_kind, ranks))
+
+
+# ---------------------------------------------------------------------------------------------------
+# forward: element by element against the oracle
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("y0_zero", [False, True])
+def test_config1_tiny(oracle_mod, variant, y0_zero):
+    check_forward(oracle_mod, synth.config1(y0_zero=y0_zero), variant)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("seed,T,d_in,d_out,ranks", [
+    (1, 37, 520, 264, [1, 3, 8, 64]),           # d not a multiple of the 512-wide wave tile, odd ranks
+    (2, 300, 1032, 776, [16, 128, 5, 24, 33]),  # several tiles, ragged tails, maximum rank
+    (3, 5, 8, 8, [2]),                           # smallest supported shape
+    (4, 130, 2048, 4096, [8, 16, 32]),
+])
+def test_small_mixed(oracle_mod, variant, seed, T, d_in, d_out, ranks):
+    for y0_zero in (False, True):
+        p = synth.small_mixed(seed, T, d_in, d_out, ranks, drop_frac=0.1, y0_zero=y0_zero, w_std=0.05)
+        check_forward(oracle_mod, p, variant)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_zero_B_is_bit_identical(oracle_mod, variant):
+    p = synth.small_mixed(9, 77, 512, 512, [8, 16], drop_frac=0.2)
+    p.B = [np.zeros_like(b) for b in p.B]
+    d = DeviceProblem(p)
+    d.build()
+    y_bits, _, err = d.forward(variant)
+    assert err == 0 and np.array_equal(y_bits, p.y0)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_identity_perm_with_caller_tables(oracle_mod, variant):
+    """Tables written by the caller for a batch that is already in segment order, perm = NULL."""
+    rng = np.random.default_rng(17)
+    lens, ads, kinds = [70, 3, 1, 20], [2, 0, 1, 0], [0, 1, 2, 2]
+    ta = np.concatenate([np.full(l, a, np.int32) for l, a in zip(lens, ads)])
+    tk = np.concatenate([np.full(l, k, np.uint8) for l, k in zip(lens, kinds)])
+    p = synth.make_problem("sorted", synth.Batch(ta, tk), 256, 384, [8, 4, 16], [1.0, 2.0, 0.5], 99)
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, ta, tk)
+    d = DeviceProblem(p)
+    seg = d.seg
+    seg.seg_starts[:5] = torch.tensor(np.cumsum([0] + lens), dtype=torch.int32)
+    seg.seg_adapter[:4] = torch.tensor(ads, dtype=torch.int32)
+    seg.seg_kind[:4] = torch.tensor(kinds, dtype=torch.uint8)
+    seg.h_offsets[:5] = torch.tensor([0, 70 * 16, 70 * 16, 70 * 16, 70 * 16], dtype=torch.int64)
+    seg.n_segments[0] = 4
+    y_bits, h, err = d.forward(variant, h_elems=70 * 16, use_perm=False)
+    assert err == 0
+    assert_close(synth.bf16_bits_to_f64(y_bits), ref.y, "y")
+    assert_close(h, ref.h, "h")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_bad_device_metadata_is_skipped_and_flagged(variant):
+    p = synth.small_mixed(23, 40, 256, 256, [8, 8], n_kinds=1)
+    d = DeviceProblem(p)
+    d.build()
+    d.seg.seg_adapter[0] = 7                    # beyond the adapter table
+    y_bits, _, err = d.forward(variant)
+    assert err & 1
+    rows = d.seg.to_host()
+    first = rows["perm"][rows["seg_starts"][0]: rows["seg_starts"][1]]
+    assert np.array_equal(y_bits[first], p.y0[first])
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_config2_decode_heavy(oracle_mod, variant):
+    for y0_zero in (False, True):
+        check_forward(oracle_mod, synth.config2(y0_zero=y0_zero), variant)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_config3_unified(oracle_mod, variant):
+    check_forward(oracle_mod, synth.config3(), variant)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_repeat_calls_are_bit_identical(variant):
+    p = synth.config2()
+    outs = []
+    for _ in range(3):
+        d = DeviceProblem(p)
+        d.build()
+        outs.append(d.forward(variant)[0])
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
