@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the segmented multi-LoRA hot path on one MI355X.
+
+A step = one pass of the whole path over one batch: segment-metadata builder + forward (shrink,
+h-save, expand; split or fused variant) [+ backward of the fine-tune rows for the layer-stack
+workload].  Inputs are synthetic (paper_2511_00101_amd/synth.py), already resident in HBM, and
+rotated over enough replicas (> 1 GiB in total) that no step finds its operands in L2 or in the
+Infinity Cache left there by the previous step.
+
+Prints ONE JSON line (see README/DESIGN for the fields).  `value` is tokens/s of the headline
+workload (the decode-heavy batch, benchmark configs[1]); `roofline` is the HBM roofline of the
+dominant kernel from HIP-event timing of each launch; `cpu_baseline` is the fp64 oracle on the host
+cores; `configs` carries the same measurements for the other single-call workloads.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+METRIC = "segmented multi-LoRA fwd: tokens/s, HBM GB/s & MFMA util vs peak (1 MI355X)"
+
+
+def algorithmic_work(p):
+    """Bytes the method must move and flops it must do for one call ('Algorithmic bytes'):
+    x once, y read + write, A and B of every adapter in use once, saved h once; 2 r (d_in + d_out) flops/token."""
+    import numpy as np
+    ta, tk = p.batch.token_adapter, p.batch.token_kind
+    live = (ta >= 0) & (ta < p.n_adapters) & (tk <= 2)
+    used = np.unique(ta[live])
+    r_tok = p.ranks[ta[live]].astype(np.int64)
+    n_live = int(live.sum())
+    ft = live & (tk == 0)
+    bytes_x = n_live * p.d_in * 2
+    bytes_y = n_live * p.d_out * 4
+    bytes_A = int(sum(int(p.ranks[a]) * p.d_in * 2 for a in used))
+    bytes_B = int(sum(int(p.ranks[a]) * p.d_out * 2 for a in used))
+    bytes_h = int(p.ranks[ta[ft]].astype(np.int64).sum()) * 4
+    flops = int((2 * r_tok * (p.d_in + p.d_out)).sum())
+    return dict(shrink=bytes_x + bytes_A, expand=bytes_y + bytes_B + bytes_h,
+                total=bytes_x + bytes_y + bytes_A + bytes_B + bytes_h, flops=flops, tokens=n_live)
+
+
+class Replicas:
+    """Device copies of one problem, rotated step by step so that operands come from HBM."""
+
+    def __init__(self, p, variant, min_total_bytes=int(1.25 * 2 ** 30), max_replicas=64):
+        import torch
+        from paper_2511_00101_amd import binding as lq
+        self.lq, self.torch, self.p, self.variant = lq, torch, p, variant
+        per = p.x.nbytes + p.y0.nbytes + sum(a.nbytes for a in p.A) + sum(b.nbytes for b in p.B)
+        self.n = int(min(max_replicas, max(2, -(-min_total_bytes // per))))
+        dev = "cuda"
+        x0, y0 = lq.bf16_from_bits(p.x, dev), lq.bf16_from_bits(p.y0, dev)
+        A0 = [lq.bf16_from_bits(a, dev) for a in p.A]
+        B0 = [lq.bf16_from_bits(b, dev) for b in p.B]
+        self.x = [x0] + [x0.clone() for _ in range(self.n - 1)]
+        self.y = [y0] + [y0.clone() for _ in range(self.n - 1)]
+        self.ad = [lq.AdapterTable.from_tensors([a.clone() for a in A0], [b.clone() for b in B0], p.scales, dev)
+                   for _ in range(self.n)]
+        self.ta = torch.from_numpy(p.batch.token_adapter).to(dev)
+        self.tk = torch.from_numpy(p.batch.token_kind).to(dev)
+        self.seg = lq.SegmentTables.empty(p.n_tokens, p.n_adapters, dev)
+        self.bws = lq.workspace(lq.lora_build_workspace_bytes(p.n_tokens, p.n_adapters), dev)
+        self.fws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, self.ad[0].max_rank, p.d_in, p.d_out, variant), dev)
+        lq.lora_build_segments(self.ta, self.tk, self.ad[0].ranks, self.seg, self.bws)
+        h_elems = int(self.seg.h_offsets.max().item())
+        self.h_out = torch.zeros(max(h_elems, 1), dtype=torch.float32, device=dev)
+
+    def build(self, i):
+        self.lq.lora_build_segments(self.ta, self.tk, self.ad[i % self.n].ranks, self.seg, self.bws)
+
+    def forward(self, i, variant=None):
+        r = i % self.n
+        self.lq.lora_segmented_forward(self.x[r], self.y[r], self.ad[r], self.seg, self.h_out, self.fws,
+                                       self.variant if variant is None else variant)
+
+    def step(self, i):
+        self.build(i)
+        self.forward(i)
+
+
+def time_steps(rep, steps, warmup):
+    """Wall clock over exactly `steps` steps, synchronised on both sides."""
+    torch = rep.torch
+    for i in range(warmup):
+        rep.step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        rep.step(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def time_kernels(rep, steps, warmup):
+    """Average duration of each launch, from events recorded on the launch stream around every call."""
+    torch, lq = rep.torch, rep.lq
+    phases = (("build", None),) + ((("forward_fused", lq.LQ_VARIANT_FUSED),) if rep.variant == lq.LQ_VARIANT_FUSED else
+                                   (("shrink", lq.LQ_VARIANT_SHRINK_ONLY), ("expand", lq.LQ_VARIANT_EXPAND_ONLY)))
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(steps)]
+    for i in range(warmup):
+        rep.step(i)
+    torch.cuda.synchronize()
+    for i in range(steps):
+        ev[i][0].record()
+        for k, (name, variant) in enumerate(phases):
+            if name == "build":
+                rep.build(warmup + i)
+            else:
+                rep.forward(warmup + i, variant)
+            ev[i][k + 1].record()
+    torch.cuda.synchronize()
+    out = {}
+    for k, (name, _) in enumerate(phases):
+        ms = sorted(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(steps))
+        out[name] = dict(avg_us=1e3 * sum(ms) / len(ms), median_us=1e3 * ms[len(ms) // 2], min_us=1e3 * ms[0])
+    return out
+
+
+def measure(p, variant, steps, warmup):
+    work = algorithmic_work(p)
+    rep = Replicas(p, variant)
+    s_per_step = time_steps(rep, steps, warmup)
+    kern = time_kernels(rep, steps, warmup)
+    fwd_names = [k for k in kern if k != "build"]
+    fwd_us = sum(kern[k]["avg_us"] for k in fwd_names)
+    if "forward_fused" in kern:
+        dom, dom_bytes = "forward_fused", work["total"]
+    else:
+        dom = "expand" if work["expand"] >= work["shrink"] else "shrink"
+        dom_bytes = work[dom]
+    dom_gbps = dom_bytes / (kern[dom]["avg_us"] * 1e-6) / 1e9
+    res = dict(
+        workload=p.name, tokens=work["tokens"], d_in=p.d_in, d_out=p.d_out, replicas=rep.n,
+        ms_per_step=s_per_step * 1e3, tokens_per_s=work["tokens"] / s_per_step,
+        forward_us=fwd_us, forward_gbps=work["total"] / (fwd_us * 1e-6) / 1e9,
+        forward_tflops=work["flops"] / (fwd_us * 1e-6) / 1e12,
+        forward_hbm_frac=work["total"] / (fwd_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+        forward_mfma_frac=work["flops"] / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        algorithmic_bytes=work["total"], flops=work["flops"], kernels=kern,
+        roofline=dict(bound="hbm", kernel=dom, achieved=dom_gbps, peak=HBM_PEAK_GBPS, unit="GB/s",
+                      frac=dom_gbps / HBM_PEAK_GBPS, traffic=None, algorithmic_bytes=dom_bytes,
+                      avg_launch_us=kern[dom]["avg_us"]))
+    del rep
+    return res
+
+
+def cpu_baseline(p, budget_s=12.0):
+    """The fp64 oracle, as it stands, on the host cores: repeated whole-batch forwards for ~budget_s."""
+    import oracle
+    oracle.build()
+    n, t0 = 0, time.perf_counter()
+    while True:
+        oracle.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or n >= 10000:
+            break
+    return dict(value=n * p.n_tokens / el, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"{n} whole-batch forwards of {p.name} ({p.n_tokens} tokens each, metadata + forward) in {el:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--variant", choices=["split", "fused"], default="split")
+    ap.add_argument("--workload", default="cfg2", help="headline workload: cfg1, cfg2, cfg3, cfg4up, cfg4down")
+    ap.add_argument("--others", default="cfg3,cfg4up,cfg4down", help="comma list of further workloads ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's throughput; --gpus must be 1 "
+              "(the path shards by token segments with no exchange, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2511_00101_amd import binding as lq
+    from paper_2511_00101_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    lq.lib()
+    torch.cuda.set_device(0)
+    variant = lq.LQ_VARIANT_FUSED if args.variant == "fused" else lq.LQ_VARIANT_SPLIT
+    makers = dict(cfg1=synth.config1, cfg2=synth.config2, cfg3=synth.config3,
+                  cfg4up=lambda: synth.config4("up"), cfg4down=lambda: synth.config4("down"))
+
+    p = makers[args.workload]()
+    head = measure(p, variant, args.steps, args.warmup)
+    others = []
+    for name in [n for n in args.others.split(",") if n and n != args.workload]:
+        q = makers[name]()
+        others.append(measure(q, variant, max(20, args.steps // 4), max(5, args.warmup // 2)))
+        del q
+    cpu = None if args.no_cpu_baseline else cpu_baseline(p)
+
+    line = dict(
+        metric=METRIC, value=head["tokens_per_s"], unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+        ms_per_step=head["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
+        data="synthetic",
+        config=dict(workload=f"{head['workload']}: {head['tokens']} tokens, {head['d_in']}->{head['d_out']}, "
+                             f"{p.n_adapters} adapters rank {int(p.ranks.max())}", variant=args.variant,
+                    replicas=head["replicas"], step="segment builder + forward"),
+        roofline=head["roofline"], cpu_baseline=cpu,
+        forward=dict(us=head["forward_us"], gbps=head["forward_gbps"], tflops=head["forward_tflops"],
+                     hbm_frac=head["forward_hbm_frac"], mfma_frac=head["forward_mfma_frac"], kernels=head["kernels"]),
+        configs=others)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -53,8 +53,11 @@ typedef enum {
  * order of Algorithm 1: fine-tune | prefill+evaluation | decode. */
 enum { LQ_SEG_FINETUNE = 0, LQ_SEG_PREFILL = 1, LQ_SEG_DECODE = 2 };
 
-/* LQ_VARIANT_SPLIT: shrink kernel then expand kernel.  LQ_VARIANT_FUSED: one launch. */
-enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1 };
+/* LQ_VARIANT_SPLIT: shrink kernel then expand kernel.  LQ_VARIANT_FUSED: one launch.
+ * LQ_VARIANT_SHRINK_ONLY / LQ_VARIANT_EXPAND_ONLY: the two halves of the split variant as separate
+ * calls (same arguments, same workspace, shrink first), for callers that put other work between
+ * them and for timing each kernel on its own. */
+enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1, LQ_VARIANT_SHRINK_ONLY = 2, LQ_VARIANT_EXPAND_ONLY = 3 };
 
 #define LQ_MAX_RANK 128
 #define LQ_MAX_ADAPTERS 4096
@@ -106,8 +109,8 @@ lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token
  *   h_out    float, receives the UNSCALED h rows of fine-tune segments, segment g at
  *            h_out + h_offsets[g], row-major [len_g, r_a]; h_out / h_offsets may be NULL, then
  *            nothing is saved (inference-only batches)
- *   variant  LQ_VARIANT_SPLIT or LQ_VARIANT_FUSED; both give the same y and h_out up to fp32
- *            summation order
+ *   variant  one of LQ_VARIANT_*; split and fused give the same y and h_out up to fp32 summation
+ *            order; h_out is written by the expand half of the split variant
  *   workspace lora_forward_workspace_bytes(...) bytes.  n_tokens = 0 returns LQ_OK with no launch.
  * ------------------------------------------------------------------------------------------- */
 size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,
