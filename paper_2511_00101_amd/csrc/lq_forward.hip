@@ -28,9 +28,10 @@ constexpr int kLongMin = 16;   // expand: segments with at least this many rows 
 constexpr int kTT = 4;         // expand, short path: rows per unit
 constexpr int kTileM = 32;     // shrink unit: rows (two 16-row MFMA tiles)
 constexpr int kBlockK = 64;    // shrink: k elements per wave step (two MFMA k steps)
-constexpr int kChunkT = 64;    // expand, long unit: rows
+constexpr int kChunkT = 256;   // expand, long unit: rows (amortises staging the unit's block of B)
 constexpr int kShortN = 512;   // expand, short unit: columns (64 lanes x 8)
 constexpr int kMaxKSplit = 8;
+constexpr int kXcds = 8;        // accelerator complex dies, each with its own L2
 
 struct FwdParams {
     const u16* x; long long ldx;
@@ -53,14 +54,14 @@ struct SegLane { int st, en, ad, kd; };  // table entries of segment (batch * 64
 
 __device__ __forceinline__ SegLane load_seg_lane(const FwdParams& p, int n_seg, int s)
 {
+    // the tables hold max_segments entries, so the loads can go out before n_seg has arrived
+    const int sc = min(s, p.max_segments - 1);
     SegLane c;
-    c.st = c.en = c.ad = c.kd = 0;
-    if (s < n_seg) {
-        c.st = p.seg_starts[s];
-        c.en = p.seg_starts[s + 1];
-        c.ad = p.seg_adapter[s];
-        c.kd = p.seg_kind[s];
-    }
+    c.st = p.seg_starts[sc];
+    c.en = p.seg_starts[sc + 1];
+    c.ad = p.seg_adapter[sc];
+    c.kd = p.seg_kind[sc];
+    if (s >= n_seg) c.st = c.en = c.ad = c.kd = 0;
     return c;
 }
 
@@ -74,7 +75,7 @@ __device__ __forceinline__ int chunks_in(int len, int per, int cls)
     return take ? (len + per - 1) / per : 0;
 }
 
-__device__ __forceinline__ int wave_sum(int v) { return __shfl(wave_inclusive_scan(v), kWave - 1, kWave); }
+__device__ __forceinline__ int wave_sum(int v) { return uniform(__shfl(wave_inclusive_scan(v), kWave - 1, kWave)); }
 
 // number of chunks of `per` rows over the segments of a class; wave uniform
 __device__ __forceinline__ int count_chunks(const FwdParams& p, int n_seg, const SegLane& c0, int per, int cls)
@@ -96,17 +97,17 @@ __device__ __forceinline__ bool find_chunk(const FwdParams& p, int n_seg, const 
         const SegLane c = s0 == 0 ? c0 : load_seg_lane(p, n_seg, s0 + lane_id());
         const int nch = chunks_in(c.en - c.st, per, cls);
         const int incl = wave_inclusive_scan(nch);
-        const int total = __shfl(incl, kWave - 1, kWave);
+        const int total = uniform(__shfl(incl, kWave - 1, kWave));
         if (id < base + total) {
             const unsigned long long m = __ballot(base + incl > id);
             const int l = __ffsll((long long)m) - 1;
-            const int local = id - base - __shfl(incl - nch, l, kWave);
+            const int local = id - base - uniform(__shfl(incl - nch, l, kWave));
             u.seg = s0 + l;
-            u.first = __shfl(c.st, l, kWave);
+            u.first = uniform(__shfl(c.st, l, kWave));
             u.pos = u.first + local * per;
-            u.len = min(per, __shfl(c.en, l, kWave) - u.pos);
-            u.ad = __shfl(c.ad, l, kWave);
-            u.kd = __shfl(c.kd, l, kWave);
+            u.len = min(per, uniform(__shfl(c.en, l, kWave)) - u.pos);
+            u.ad = uniform(__shfl(c.ad, l, kWave));
+            u.kd = uniform(__shfl(c.kd, l, kWave));
             return true;
         }
         base += total;
@@ -114,8 +115,12 @@ __device__ __forceinline__ bool find_chunk(const FwdParams& p, int n_seg, const 
     return false;
 }
 
+// Adapter matrices come from a pointer table, so the compiler cannot infer their address space; saying
+// "global" turns flat loads into global loads.
+typedef const __attribute__((address_space(1))) u16* gconst_u16;
+
 struct SegInfo {
-    const u16* A; const u16* B;
+    gconst_u16 A; gconst_u16 B;
     int rank; float scale;
     bool ok;
 };
@@ -130,8 +135,8 @@ __device__ __forceinline__ SegInfo load_adapter(const FwdParams& p, const Unit& 
     if (s.ok) {
         s.rank = p.ranks[u.ad];
         s.scale = p.scales[u.ad];
-        s.A = static_cast<const u16*>(p.A_ptrs[u.ad]);
-        s.B = static_cast<const u16*>(p.B_ptrs[u.ad]);
+        s.A = (gconst_u16)(p.A_ptrs[u.ad]);
+        s.B = (gconst_u16)(p.B_ptrs[u.ad]);
         s.ok = s.rank >= 1 && s.rank <= p.max_rank && s.A && s.B;
     }
     if (!s.ok && threadIdx.x == 0) atomicOr(p.err, kErrBadSegment);
@@ -141,7 +146,10 @@ __device__ __forceinline__ SegInfo load_adapter(const FwdParams& p, const Unit& 
 // row of x / y for a position of the segment order; -1 if the table holds an invalid row
 __device__ __forceinline__ int row_of(const FwdParams& p, int pos)
 {
-    const int row = p.perm ? p.perm[pos] : pos;
+    // branch free: with perm == NULL a dummy entry is loaded and ignored
+    const int32_t* tab = p.perm ? p.perm : p.seg_starts;
+    const int v = tab[p.perm ? pos : 0];
+    const int row = p.perm ? v : pos;
     return (row >= 0 && row < p.n_tokens) ? row : -1;
 }
 
@@ -157,42 +165,42 @@ template <int NT>  // 16-rank tiles: ranks up to 16 * NT
 __device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, float* lds)
 {
     constexpr int MT = kTileM / 16;
-    const int lane = lane_id(), w = (int)threadIdx.x / kWave, c = lane & 15, kg = lane >> 4;
+    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, kg = lane >> 4;
 
+    // Rows and ranks beyond the live ones read a live row instead: MFMA rows and columns are independent,
+    // and the results of such rows and columns are never stored.  So the loads need no branches.
+    const int safe_row = max(row_of(p, u.pos), 0);
     const u16* xrow[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int i = mt * 16 + c;
         const int row = i < u.len ? row_of(p, u.pos + i) : -1;
-        xrow[mt] = row >= 0 ? p.x + (long long)row * p.ldx : nullptr;
+        xrow[mt] = p.x + (long long)(row >= 0 ? row : safe_row) * p.ldx + kg * 8;
     }
-    const u16* arow[NT];
+    gconst_u16 arow[NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int j = nt * 16 + c;
-        arow[nt] = j < s.rank ? s.A + (long long)j * p.d_in : nullptr;
-    }
+    for (int nt = 0; nt < NT; ++nt) arow[nt] = s.A + (long long)min(nt * 16 + c, s.rank - 1) * p.d_in + kg * 8;
     f32x4 acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto load = [&](int blk, u32x4 (&xv)[MT][2], u32x4 (&av)[NT][2]) {
+    // Workgroups that run side by side would otherwise sweep the same k range of different rows in step,
+    // which (with a power-of-two row pitch) keeps hitting the same few HBM channels; so every tile starts
+    // its sweep at a different block and wraps around.
+    const int n_full = p.d_in / kBlockK;  // blocks that lie fully inside d_in; a shorter last block may follow
+    const int rot = n_full > 0 ? (int)(((unsigned)u.pos / kTileM * 37u) % (unsigned)n_full) : 0;  // same for all slices
+    auto load = [&](int blk, u32x4 (&xv)[MT][2], u32x4 (&av)[NT][2]) {  // a block that lies fully inside d_in
+        blk += rot;
+        if (blk >= n_full) blk -= n_full;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            const int k = blk * kBlockK + kg * 8 + 32 * q;
-            const bool in = k < p.d_in;
+            const int k = blk * kBlockK + 32 * q;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                xv[mt][q] = u32x4{0u, 0u, 0u, 0u};
-                if (in && xrow[mt]) xv[mt][q] = *reinterpret_cast<const u32x4*>(xrow[mt] + k);
-            }
+            for (int mt = 0; mt < MT; ++mt) xv[mt][q] = *reinterpret_cast<const u32x4*>(xrow[mt] + k);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                av[nt][q] = u32x4{0u, 0u, 0u, 0u};
-                if (in && arow[nt]) av[nt][q] = *reinterpret_cast<const u32x4*>(arow[nt] + k);
-            }
+            for (int nt = 0; nt < NT; ++nt) av[nt][q] = *(const __attribute__((address_space(1))) u32x4*)(arow[nt] + k);
         }
     };
     auto mma = [&](const u32x4 (&xv)[MT][2], const u32x4 (&av)[NT][2]) {
@@ -206,29 +214,60 @@ __device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, c
                                                                           acc[mt][nt], 0, 0, 0);
     };
 
-    const int n_blocks = (p.d_in + kBlockK - 1) / kBlockK;
     const int stride = kWaves * p.ksplit;
     int blk = ks * kWaves + w;
     if constexpr (NT <= 4) {
-        // two blocks in flight per wave
+        // Two blocks in flight per wave.  The prefetch is unconditional (past the end it re-reads the
+        // current block) so that the number of loads in flight is static and the wait before the MFMAs
+        // covers only the older block.
         u32x4 xa[MT][2], aa[NT][2], xb[MT][2], ab[NT][2];
-        if (blk < n_blocks) load(blk, xa, aa);
-        while (blk < n_blocks) {
-            if (blk + stride < n_blocks) load(blk + stride, xb, ab);
-            mma(xa, aa);
-            blk += stride;
-            if (blk >= n_blocks) break;
-            if (blk + stride < n_blocks) load(blk + stride, xa, aa);
-            mma(xb, ab);
-            blk += stride;
+        if (blk < n_full) {
+            load(blk, xa, aa);
+            while (true) {
+                bool more = blk + stride < n_full;
+                load(more ? blk + stride : blk, xb, ab);
+                __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMAs
+                mma(xa, aa);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!more) break;
+                blk += stride;
+                more = blk + stride < n_full;
+                load(more ? blk + stride : blk, xa, aa);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(xb, ab);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!more) break;
+                blk += stride;
+            }
         }
     } else {
         // ranks above 64: the fragments of one block already fill the register budget
-        for (; blk < n_blocks; blk += stride) {
+        for (; blk < n_full; blk += stride) {
             u32x4 xa[MT][2], aa[NT][2];
             load(blk, xa, aa);
             mma(xa, aa);
         }
+    }
+    if (n_full * kBlockK < p.d_in && (n_full / kWaves) % p.ksplit == ks && n_full % kWaves == w) {
+        // the last, shorter block: read inside the row and zero what lies beyond d_in
+        u32x4 xa[MT][2], aa[NT][2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int k = n_full * kBlockK + 32 * q;
+            const bool in = k + kg * 8 < p.d_in;
+            const int kc = in ? k : 0;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(xrow[mt] + kc);
+                xa[mt][q] = in ? v : u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const u32x4 v = *(const __attribute__((address_space(1))) u32x4*)(arow[nt] + kc);
+                aa[nt][q] = in ? v : u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+        mma(xa, aa);
     }
 
     // tree reduction over the 8 waves in a fixed order: slots[4][MT * NT * 4][64 lanes]
@@ -291,21 +330,46 @@ __device__ __forceinline__ void split_bf16(const float (&v)[8], u32x4& hi, u32x4
     lo = u32x4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
 }
 
-template <int KSTEPS, int PAIRS>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, the unit 8 waves
+template <int KSTEPS, int PAIRS, bool MULTI>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, the unit
+                                              // 8 waves; MULTI: h arrives as several partials (ksplit > 1)
 __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
                                                  u16* lds_b)
 {
     constexpr int WN = 32 * PAIRS, UN = kWaves * WN, ROWS = 32 * KSTEPS;
     constexpr int PITCH = UN + 8;  // elements; keeps rows 16-byte aligned and spreads them over banks
-    const int lane = lane_id(), w = (int)threadIdx.x / kWave, c = lane & 15, g = lane >> 4;
+    constexpr int STAGE = ROWS * (UN / 8) / kThreads;  // 16-byte pieces of the B block per thread
+    static_assert(ROWS * (UN / 8) % kThreads == 0, "staging loop assumes an even split");
+    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, g = lane >> 4;
     const int n_unit = n_block * UN;
 
-    __syncthreads();  // the previous unit's fragment reads are done
-    for (int id = (int)threadIdx.x; id < ROWS * (UN / 8); id += kThreads) {
-        const int j = id / (UN / 8), n = n_unit + (id % (UN / 8)) * 8;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (j < s.rank && n < p.d_out) v = *reinterpret_cast<const u32x4*>(s.B + (long long)j * p.d_out + n);
-        *reinterpret_cast<u32x4*>(lds_b + j * PITCH + (n - n_unit)) = v;
+    {
+        u32x4 v[STAGE];
+#pragma unroll
+        for (int i = 0; i < STAGE; ++i) {
+            const int id = (int)threadIdx.x + i * kThreads;
+            const int j = id / (UN / 8), n = n_unit + (id % (UN / 8)) * 8;
+            v[i] = *(const __attribute__((address_space(1))) u32x4*)(s.B + (long long)min(j, s.rank - 1) * p.d_out +
+                                                                     min(n, p.d_out - 8));
+        }
+        __syncthreads();  // the previous unit's fragment reads are done
+#pragma unroll
+        for (int i = 0; i < STAGE; ++i) {
+            const int id = (int)threadIdx.x + i * kThreads;
+            const int j = id / (UN / 8), n = n_unit + (id % (UN / 8)) * 8;
+            const bool live = j < s.rank && n < p.d_out;
+            *reinterpret_cast<u32x4*>(lds_b + j * PITCH + (n - n_unit)) = live ? v[i] : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+    // fine-tune segments: the unit of the first column block also stores the unscaled h rows
+    if (u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0) {
+        float* dst = p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank;
+        for (int id = (int)threadIdx.x; id < u.len * s.rank; id += kThreads) {
+            const int i = id / s.rank, j = id - i * s.rank;
+            float sum = 0.f;
+            for (int part = 0; part < p.ksplit; ++part)
+                sum += p.hpart[((long long)part * p.n_tokens + u.pos + i) * p.rstride + j];
+            dst[id] = sum;
+        }
     }
     __syncthreads();
 
@@ -328,34 +392,36 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
 
     const int n_tiles = (u.len + 15) / 16;
     const int n_lane = n_wave + 8 * g;  // + 32 q
-    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && w == 0;
-    const long long h_base = save ? p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : 0;
 
-    // software pipeline: the next tile's row index, y and h are in flight while this one is computed
+    // software pipeline: the next tile's row index, y and h are in flight while this one is computed.
+    // Loads are unconditional (dead rows and columns read a live address); only the stores are masked.
+    const int safe_row = max(row_of(p, u.pos), 0);
+    int n_ld[PAIRS];
+#pragma unroll
+    for (int q = 0; q < PAIRS; ++q) n_ld[q] = min(n_lane + 32 * q, p.d_out - 8);
     int row_n;
     u32x4 y_n[PAIRS];
     f32x4 h_n[KSTEPS][2];
     auto fetch = [&](int tile) {
         const int i = tile * 16 + c;
         row_n = i < u.len ? row_of(p, u.pos + i) : -1;
+        const u16* yrow = p.y + (long long)(row_n >= 0 ? row_n : safe_row) * p.ldy;
 #pragma unroll
-        for (int q = 0; q < PAIRS; ++q) {
-            y_n[q] = u32x4{0u, 0u, 0u, 0u};
-            if (row_n >= 0 && n_lane + 32 * q < p.d_out)
-                y_n[q] = *reinterpret_cast<const u32x4*>(p.y + (long long)row_n * p.ldy + n_lane + 32 * q);
-        }
+        for (int q = 0; q < PAIRS; ++q) y_n[q] = *reinterpret_cast<const u32x4*>(yrow + n_ld[q]);
         const float* hp = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             h_n[ks][0] = *reinterpret_cast<const f32x4*>(hp + 32 * ks);
             h_n[ks][1] = *reinterpret_cast<const f32x4*>(hp + 32 * ks + 4);
         }
-        for (int part = 1; part < p.ksplit; ++part) {
-            const float* hq = hp + (long long)part * p.n_tokens * p.rstride;
+        if constexpr (MULTI) {
+            for (int part = 1; part < p.ksplit; ++part) {
+                const float* hq = hp + (long long)part * p.n_tokens * p.rstride;
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                h_n[ks][0] += *reinterpret_cast<const f32x4*>(hq + 32 * ks);
-                h_n[ks][1] += *reinterpret_cast<const f32x4*>(hq + 32 * ks + 4);
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    h_n[ks][0] += *reinterpret_cast<const f32x4*>(hq + 32 * ks);
+                    h_n[ks][1] += *reinterpret_cast<const f32x4*>(hq + 32 * ks + 4);
+                }
             }
         }
     };
@@ -368,7 +434,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         for (int q = 0; q < PAIRS; ++q) yv[q] = y_n[q];
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) { hv[ks][0] = h_n[ks][0]; hv[ks][1] = h_n[ks][1]; }
-        if (tile + 1 < n_tiles) fetch(tile + 1);
+        fetch(min(tile + 1, n_tiles - 1));  // unconditional, so the loads in flight are counted statically
 
         u32x4 h_hi[KSTEPS], h_lo[KSTEPS];
 #pragma unroll
@@ -378,9 +444,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
             for (int i = 0; i < 8; ++i) {
                 const int j = 32 * ks + 8 * g + i;
                 const float raw = i < 4 ? hv[ks][0][i & 3] : hv[ks][1][i & 3];
-                const bool live = tile * 16 + c < u.len && j < s.rank;
-                if (save && live) p.h_out[h_base + (long long)(tile * 16 + c) * s.rank + j] = raw;
-                v[i] = (row >= 0 && live) ? raw * s.scale : 0.f;
+                v[i] = (row >= 0 && j < s.rank) ? raw * s.scale : 0.f;
             }
             split_bf16(v, h_hi[ks], h_lo[ks]);
         }
@@ -428,7 +492,7 @@ struct ShortLds {
 __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
                                                   ShortLds& sh)
 {
-    const int lane = lane_id(), w = (int)threadIdx.x / kWave;
+    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
     float (*hs)[kTT] = sh.hs[w];
     const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0;
     const long long h_base = save ? p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : 0;
@@ -451,12 +515,11 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     for (int t = 0; t < kTT; ++t) row[t] = t < u.len ? row_of(p, u.pos + t) : -1;
     const int n = n_block * kShortN + lane * 8;
     if (n < p.d_out) {
+        const int safe_row = max(row[0], 0);
         u32x4 yv[kTT];
 #pragma unroll
-        for (int t = 0; t < kTT; ++t) {
-            yv[t] = u32x4{0u, 0u, 0u, 0u};
-            if (row[t] >= 0) yv[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)row[t] * p.ldy + n);
-        }
+        for (int t = 0; t < kTT; ++t)
+            yv[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row[t] >= 0 ? row[t] : safe_row) * p.ldy + n);
         float acc[kTT][8];
 #pragma unroll
         for (int t = 0; t < kTT; ++t)
@@ -464,7 +527,7 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
             for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
 #pragma unroll 8
         for (int j = 0; j < s.rank; ++j) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(s.B + (long long)j * p.d_out + n);
+            const u32x4 v = *(const __attribute__((address_space(1))) u32x4*)(s.B + (long long)j * p.d_out + n);
             const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs[j]);
             float bf[8];
             unpack8(v, bf);
@@ -499,10 +562,15 @@ template <int NT>
 __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
-    const int n_seg = min(*p.n_segments, p.max_segments);
+    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegLane c0 = load_seg_lane(p, n_seg, lane_id());
     const int n_units = count_chunks(p, n_seg, c0, kTileM, kAll) * p.ksplit;
-    for (int id = (int)blockIdx.x; id < n_units; id += (int)gridDim.x) {
+    // Workgroup b runs on XCD b % 8 (round-robin dispatch).  Each XCD takes one contiguous eighth of the
+    // units, so the tiles of a segment share their adapter's A through one L2 instead of eight.
+    const int n_xcd = (int)gridDim.x % kXcds == 0 ? kXcds : 1;
+    const int per_xcd = (n_units + n_xcd - 1) / n_xcd;
+    const int first = ((int)blockIdx.x % n_xcd) * per_xcd, last = min(n_units, first + per_xcd);
+    for (int id = first + (int)blockIdx.x / n_xcd; id < last; id += (int)gridDim.x / n_xcd) {
         Unit u;
         if (!find_chunk(p, n_seg, c0, id / p.ksplit, kTileM, kAll, u)) continue;
         const SegInfo s = load_adapter(p, u);
@@ -511,12 +579,12 @@ __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
     }
 }
 
-template <int KSTEPS, int PAIRS>
+template <int KSTEPS, int PAIRS, bool MULTI>
 __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) u16 lds_b[];
     __shared__ ShortLds sh;
-    const int n_seg = min(*p.n_segments, p.max_segments);
+    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegLane c0 = load_seg_lane(p, n_seg, lane_id());
 
     // long units, one per workgroup iteration
@@ -528,14 +596,14 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
         if (!find_chunk(p, n_seg, c0, id / long_blocks, kChunkT, kLong, u)) continue;
         const SegInfo s = load_adapter(p, u);
         if (!s.ok) continue;
-        expand_long_unit<KSTEPS, PAIRS>(p, u, s, id % long_blocks, lds_b);
+        expand_long_unit<KSTEPS, PAIRS, MULTI>(p, u, s, id % long_blocks, lds_b);
     }
 
     // short units, one per wave iteration, dealt round-robin over the workgroups first so that a few
     // hundred units spread over all compute units
     const int short_blocks = (p.d_out + kShortN - 1) / kShortN;
     const int n_short = count_chunks(p, n_seg, c0, kTT, kShort) * short_blocks;
-    const int w = (int)threadIdx.x / kWave;
+    const int w = uniform((int)threadIdx.x / kWave);
     for (int id = w * (int)gridDim.x + (int)blockIdx.x; id < n_short; id += kWaves * (int)gridDim.x) {
         Unit u;
         if (!find_chunk(p, n_seg, c0, id / short_blocks, kTT, kShort, u)) continue;
@@ -590,19 +658,25 @@ hipError_t launch_shrink(const FwdParams& p, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int KSTEPS, int PAIRS>
-hipError_t launch_expand(const FwdParams& p, hipStream_t st)
+template <int KSTEPS, int PAIRS, bool MULTI>
+hipError_t launch_expand_as(const FwdParams& p, hipStream_t st)
 {
     static int grid = 0;
     const size_t lds = expand_lds_bytes(KSTEPS, PAIRS);
     if (!grid) {
         if (lds > 48 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(expand_kernel<KSTEPS, PAIRS>),
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(expand_kernel<KSTEPS, PAIRS, MULTI>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        grid = resident_grid(expand_kernel<KSTEPS, PAIRS>, lds);
+        grid = resident_grid(expand_kernel<KSTEPS, PAIRS, MULTI>, lds);
     }
-    hipLaunchKernelGGL((expand_kernel<KSTEPS, PAIRS>), dim3(grid), dim3(kThreads), lds, st, p);
+    hipLaunchKernelGGL((expand_kernel<KSTEPS, PAIRS, MULTI>), dim3(grid), dim3(kThreads), lds, st, p);
     return hipGetLastError();
+}
+
+template <int KSTEPS, int PAIRS>
+hipError_t launch_expand(const FwdParams& p, hipStream_t st)
+{
+    return p.ksplit > 1 ? launch_expand_as<KSTEPS, PAIRS, true>(p, st) : launch_expand_as<KSTEPS, PAIRS, false>(p, st);
 }
 
 }  // namespace
