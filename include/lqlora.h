@@ -110,7 +110,7 @@ lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token
  *            h_out + h_offsets[g], row-major [len_g, r_a]; h_out / h_offsets may be NULL, then
  *            nothing is saved (inference-only batches)
  *   variant  one of LQ_VARIANT_*; split and fused give the same y and h_out up to fp32 summation
- *            order; h_out is written by the expand half of the split variant
+ *            order; h_out may be written by either half of the split variant
  *   workspace lora_forward_workspace_bytes(...) bytes.  n_tokens = 0 returns LQ_OK with no launch.
  * ------------------------------------------------------------------------------------------- */
 size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,

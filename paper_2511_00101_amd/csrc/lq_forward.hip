@@ -1,37 +1,46 @@
 // Segmented multi-adapter LoRA forward (Section 3.3): shrink (h = x A_a^T per segment), h-save for
 // fine-tune segments, expand (y += s_a h B_a).
 //
-// Work decomposition.  Every workgroup (8 waves) reads the segment tables itself (one wave scan per 64
-// segments, cached in registers), so the grid is a fixed number of resident workgroups that stride
-// over "units" and no plan buffer or extra launch is needed.
-//   shrink unit        : 32 rows of one segment x one of `ksplit` interleaved slices of d_in.  16x16x32
-//                        bf16 MFMA; the 8 waves take alternate 64-wide k blocks and tree-reduce through
-//                        LDS (fixed order, so results are reproducible); the unit stores one partial h.
-//                        Segments of any length take this path (the MFMA does the k reduction for free
-//                        even when only a few of the 16 tile rows are live).
-//   expand, long unit  : 64 rows of a segment with >= 16 rows x 512 columns of d_out.  The B_a block is
-//                        staged once in LDS and transposed into MFMA fragments held in registers; y is
-//                        streamed once (read-modify-write).
+// Every workgroup (8 waves) reads the segment tables itself, so the grids are a fixed number of
+// resident workgroups that stride over "units"; no plan buffer or extra launch is needed.
+//
+//   shrink, tall unit  : 128 rows of a segment with >= 64 rows x one of `ksplit` interleaved slices of
+//                        d_in.  A GEMM with a skinny output: each wave owns 16 rows and streams its x
+//                        rows straight into MFMA fragments; the 256-wide k stage of A_a is staged in
+//                        LDS once per workgroup (coalesced loads, double buffered) and shared by the
+//                        8 waves, so A_a crosses the L2->L1 path once per 128 rows.
+//   shrink, short unit : <= 32 rows of a segment with < 64 rows x one slice of d_in.  GEMV-like: the 8
+//                        waves take alternate 64-wide k blocks of x and A_a and tree-reduce through LDS
+//                        in a fixed order.  The MFMA does the k reduction even when few rows are live.
+//   (with ksplit > 1 every shrink unit stores the h of its slice and the expand kernel adds the slices
+//    in order, so no workgroup waits for another and the sum does not depend on timing)
+//   expand, long unit  : 256 rows of a segment with >= 16 rows x 512 columns of d_out.  The B_a block is
+//                        staged in LDS and transposed into MFMA fragments that stay in registers; the
+//                        unit's h rows are scaled, split into bf16 high and low parts and laid out as
+//                        fragments in LDS once; then y streams by, 32 rows per step, read-modify-write.
 //   expand, short unit : one wave: <= 4 rows of a segment with < 16 rows x 512 columns.  B_a rows are
 //                        streamed with 16-byte loads, h is broadcast from LDS, plain FMAs.
 // x and y are accessed with 16-byte loads/stores straight in the MFMA operand layout (16 rows x 64
-// contiguous bytes per instruction), which on MI355X streams within a few percent of a row-contiguous
-// pattern, so neither goes through LDS.
-#include "lq_common.h"
+// contiguous bytes per instruction); on MI355X that streams from HBM within a few percent of a
+// row-contiguous pattern as long as nothing else competes for the address path, which is why A_a, B_a
+// and h reach the MFMA through LDS instead.
+#include "lq_segments.h"
 
 namespace lq {
 namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kLongMin = 16;   // expand: segments with at least this many rows take the MFMA path
-constexpr int kTT = 4;         // expand, short path: rows per unit
-constexpr int kTileM = 32;     // shrink unit: rows (two 16-row MFMA tiles)
-constexpr int kBlockK = 64;    // shrink: k elements per wave step (two MFMA k steps)
-constexpr int kChunkT = 256;   // expand, long unit: rows (amortises staging the unit's block of B)
-constexpr int kShortN = 512;   // expand, short unit: columns (64 lanes x 8)
+constexpr int kTallMin = 64;     // shrink: segments with at least this many rows take the row-split path
+constexpr int kTallRows = 128;   // shrink, tall unit: rows (8 waves x 16)
+constexpr int kStageK = 256;     // shrink, tall unit: k elements of A staged per step
+constexpr int kShortRows = 32;   // shrink, short unit: rows (two 16-row MFMA tiles)
+constexpr int kBlockK = 64;      // shrink: k elements per wave step (two MFMA k steps)
+constexpr int kLongMin = 16;     // expand: segments with at least this many rows take the MFMA path
+constexpr int kTT = 4;           // expand, short unit: rows
+constexpr int kShortN = 512;     // expand, short unit: columns (64 lanes x 8)
 constexpr int kMaxKSplit = 8;
-constexpr int kXcds = 8;        // accelerator complex dies, each with its own L2
+constexpr int kBig = 0x7fffffff;
 
 struct FwdParams {
     const u16* x; long long ldx;
@@ -43,128 +52,152 @@ struct FwdParams {
     const int32_t* seg_starts; const int32_t* seg_adapter; const uint8_t* seg_kind;
     const int32_t* n_segments; int max_segments;
     float* h_out; const long long* h_offsets;
-    float* hpart;    // [ksplit][n_tokens][rstride] partial h by position in segment order (unscaled)
+    float* hpart;    // [ksplit][n_tokens][rstride] h of each slice of d_in by position in segment order (unscaled)
     int ksplit;
-    int rstride;     // multiple of 32
+    int rstride;     // 32, 64 or 128
     int* err;
 };
 
-// ---- segment tables -----------------------------------------------------------------------------
-struct SegLane { int st, en, ad, kd; };  // table entries of segment (batch * 64 + lane); empty beyond n_seg
-
-__device__ __forceinline__ SegLane load_seg_lane(const FwdParams& p, int n_seg, int s)
+// Where a shrink unit stores its h values: slice ks of the partial-h buffer.  With ksplit == 1 that is
+// the finished h, and fine-tune segments store it to h_out as well; with ksplit > 1 the expand kernel
+// adds the slices in order (and stores h_out), so no workgroup ever waits for another.
+struct HDest { float* base; float* save; int save_ld; };
+__device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const SegInfo& s, int ks)
 {
-    // the tables hold max_segments entries, so the loads can go out before n_seg has arrived
-    const int sc = min(s, p.max_segments - 1);
-    SegLane c;
-    c.st = p.seg_starts[sc];
-    c.en = p.seg_starts[sc + 1];
-    c.ad = p.seg_adapter[sc];
-    c.kd = p.seg_kind[sc];
-    if (s >= n_seg) c.st = c.en = c.ad = c.kd = 0;
-    return c;
+    HDest d;
+    d.base = p.hpart + ((long long)ks * p.n_tokens + u.pos) * p.rstride;
+    const bool save = p.ksplit == 1 && u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets;
+    d.save = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
+    d.save_ld = s.rank;
+    return d;
 }
 
-struct Unit { int seg, pos, len, first, ad, kd; };
-
-enum { kAll = 0, kLong = 1, kShort = 2 };  // which segments a chunk enumeration covers
-
-__device__ __forceinline__ int chunks_in(int len, int per, int cls)
+// finished h of one element: the slices added in order
+__device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j)
 {
-    const bool take = len > 0 && (cls == kAll || (len >= kLongMin) == (cls == kLong));
-    return take ? (len + per - 1) / per : 0;
+    float sum = p.hpart[pos * p.rstride + j];
+    for (int part = 1; part < p.ksplit; ++part) sum += p.hpart[((long long)part * p.n_tokens + pos) * p.rstride + j];
+    return sum;
 }
-
-__device__ __forceinline__ int wave_sum(int v) { return uniform(__shfl(wave_inclusive_scan(v), kWave - 1, kWave)); }
-
-// number of chunks of `per` rows over the segments of a class; wave uniform
-__device__ __forceinline__ int count_chunks(const FwdParams& p, int n_seg, const SegLane& c0, int per, int cls)
-{
-    int total = wave_sum(chunks_in(c0.en - c0.st, per, cls));
-    for (int s0 = kWave; s0 < n_seg; s0 += kWave) {
-        const SegLane c = load_seg_lane(p, n_seg, s0 + lane_id());
-        total += wave_sum(chunks_in(c.en - c.st, per, cls));
-    }
-    return total;
-}
-
-// the id-th chunk (ids count through the segments of the class in order); wave uniform result
-__device__ __forceinline__ bool find_chunk(const FwdParams& p, int n_seg, const SegLane& c0, int id, int per,
-                                           int cls, Unit& u)
-{
-    int base = 0;
-    for (int s0 = 0; s0 < n_seg; s0 += kWave) {
-        const SegLane c = s0 == 0 ? c0 : load_seg_lane(p, n_seg, s0 + lane_id());
-        const int nch = chunks_in(c.en - c.st, per, cls);
-        const int incl = wave_inclusive_scan(nch);
-        const int total = uniform(__shfl(incl, kWave - 1, kWave));
-        if (id < base + total) {
-            const unsigned long long m = __ballot(base + incl > id);
-            const int l = __ffsll((long long)m) - 1;
-            const int local = id - base - uniform(__shfl(incl - nch, l, kWave));
-            u.seg = s0 + l;
-            u.first = uniform(__shfl(c.st, l, kWave));
-            u.pos = u.first + local * per;
-            u.len = min(per, uniform(__shfl(c.en, l, kWave)) - u.pos);
-            u.ad = uniform(__shfl(c.ad, l, kWave));
-            u.kd = uniform(__shfl(c.kd, l, kWave));
-            return true;
-        }
-        base += total;
-    }
-    return false;
-}
-
-// Adapter matrices come from a pointer table, so the compiler cannot infer their address space; saying
-// "global" turns flat loads into global loads.
-typedef const __attribute__((address_space(1))) u16* gconst_u16;
-
-struct SegInfo {
-    gconst_u16 A; gconst_u16 B;
-    int rank; float scale;
-    bool ok;
-};
-
-__device__ __forceinline__ SegInfo load_adapter(const FwdParams& p, const Unit& u)
-{
-    SegInfo s;
-    s.A = s.B = nullptr;
-    s.rank = 0;
-    s.scale = 0.f;
-    s.ok = u.ad >= 0 && u.ad < p.n_adapters;
-    if (s.ok) {
-        s.rank = p.ranks[u.ad];
-        s.scale = p.scales[u.ad];
-        s.A = (gconst_u16)(p.A_ptrs[u.ad]);
-        s.B = (gconst_u16)(p.B_ptrs[u.ad]);
-        s.ok = s.rank >= 1 && s.rank <= p.max_rank && s.A && s.B;
-    }
-    if (!s.ok && threadIdx.x == 0) atomicOr(p.err, kErrBadSegment);
-    return s;
-}
-
-// row of x / y for a position of the segment order; -1 if the table holds an invalid row
-__device__ __forceinline__ int row_of(const FwdParams& p, int pos)
-{
-    // branch free: with perm == NULL a dummy entry is loaded and ignored
-    const int32_t* tab = p.perm ? p.perm : p.seg_starts;
-    const int v = tab[p.perm ? pos : 0];
-    const int row = p.perm ? v : pos;
-    return (row >= 0 && row < p.n_tokens) ? row : -1;
-}
-
-__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
 
 // =================================================================================================
-// shrink: D[row][rank] = sum_k x[row][k] A[rank][k] with 16x16x32 bf16 MFMA.
-// Lane (c = lane % 16, kg = lane / 16) supplies x[row c][8 kg ..] and A[rank c][8 kg ..] of a 32-wide k
-// step and receives D[row 4 kg + v][rank c].  d_in is cut into 64-wide blocks; block b belongs to
-// slice (b / 8) % ksplit and to wave b % 8 of the workgroup that owns the slice.
+// shrink, tall unit.  D[row][rank] = sum_k x[row][k] A[rank][k] with 16x16x32 bf16 MFMA: lane
+// (c = lane % 16, kg = lane / 16) supplies x[row c][8 kg ..] and A[rank c][8 kg ..] of a 32-wide k step
+// and receives D[row 4 kg + v][rank c].  d_in is cut into 256-wide stages; stage t belongs to slice
+// t % ksplit.
 // =================================================================================================
 template <int NT>  // 16-rank tiles: ranks up to 16 * NT
-__device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, float* lds)
+__device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, u16* lds)
 {
-    constexpr int MT = kTileM / 16;
+    constexpr int PITCH = kStageK + 8;           // elements per staged A row (16-byte aligned, bank spread)
+    constexpr int BUF = NT * 16 * PITCH;         // elements per stage buffer
+    constexpr int NB = kStageK / kBlockK;        // x blocks per stage
+    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, kg = lane >> 4;
+    const bool wave_live = w * 16 < u.len;
+
+    const int i_row = w * 16 + c;
+    const int row = i_row < u.len ? row_of(p, u.pos + i_row) : -1;
+    const int safe_row = max(row_of(p, u.pos), 0);
+    const u16* xrow = p.x + (long long)(row >= 0 ? row : safe_row) * p.ldx;
+
+    // Stages of this slice, visited from a tile-dependent start with wrap-around: workgroups that run
+    // side by side would otherwise sweep the same k range of different rows in step, which (with a
+    // power-of-two row pitch) keeps hitting the same few HBM channels.
+    const int n_stages = (p.d_in + kStageK - 1) / kStageK;
+    const int n_my = (n_stages - ks + p.ksplit - 1) / p.ksplit;
+    const int rot = n_my > 0 ? (int)(((unsigned)u.pos / kTallRows * 5u) % (unsigned)n_my) : 0;
+    auto stage_of = [&](int i) {
+        i += rot;
+        if (i >= n_my) i -= n_my;
+        return ks + i * p.ksplit;
+    };
+
+    // staging assignment: 32 threads cover the 512 bytes of one A row, 16 rows per pass
+    const int a_row = (int)threadIdx.x / 32, a_col = ((int)threadIdx.x % 32) * 8;
+    auto stage_load = [&](int stage, u32x4 (&ga)[NT]) {
+        const int k = stage * kStageK + a_col;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int j = nt * 16 + a_row;
+            const u32x4 v = *(gconst_u32x4)(s.A + (long long)min(j, s.rank - 1) * p.d_in + min(k, p.d_in - 8));
+            ga[nt] = (j < s.rank && k < p.d_in) ? v : u32x4{0u, 0u, 0u, 0u};  // zeros beyond the rank and beyond d_in
+        }
+    };
+    auto stage_store = [&](int buf, const u32x4 (&ga)[NT]) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            *reinterpret_cast<u32x4*>(lds + buf * BUF + (nt * 16 + a_row) * PITCH + a_col) = ga[nt];
+    };
+    // x block `blk` of this slice: stage ks + (blk / NB) * ksplit, block blk % NB inside it.  Past d_in
+    // the address is clamped into the row; the staged A is zero there, so those products vanish.
+    auto xload = [&](int blk, u32x4 (&xv)[2]) {
+        const int k0 = stage_of(blk / NB) * kStageK + (blk % NB) * kBlockK + kg * 8;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) xv[q] = *reinterpret_cast<const u32x4*>(xrow + min(k0 + 32 * q, p.d_in - 8));
+    };
+    f32x4 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto mma = [&](const u32x4 (&xv)[2], int buf, int b) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const u32x4 af = *reinterpret_cast<const u32x4*>(lds + buf * BUF + (nt * 16 + c) * PITCH + b * kBlockK +
+                                                                 32 * q + kg * 8);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(xv[q]), as_bf16x8(af), acc[nt], 0, 0, 0);
+            }
+    };
+
+    const int n_blk = n_my * NB;
+    u32x4 ga[NT], xa[2], xb[2];
+    if (n_my > 0) {
+        stage_load(stage_of(0), ga);
+        if (wave_live) xload(0, xa);
+    }
+    for (int i = 0; i < n_my; ++i) {
+        const int buf = i & 1;
+        stage_store(buf, ga);
+        stage_load(stage_of(min(i + 1, n_my - 1)), ga);  // unconditional; the last one re-reads
+        __syncthreads();  // one barrier per stage: the buffer written now was last read two stages ago
+        if (wave_live) {
+            const int b0 = i * NB;
+#pragma unroll
+            for (int b = 0; b < NB; b += 2) {
+                xload(min(b0 + b + 1, n_blk - 1), xb);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(xa, buf, b);
+                __builtin_amdgcn_sched_barrier(0);
+                xload(min(b0 + b + 2, n_blk - 1), xa);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(xb, buf, b + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    const HDest d = h_dest(p, u, s, ks);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int i = w * 16 + kg * 4 + v, j = nt * 16 + c;
+            if (i < u.len && j < s.rank) {
+                d.base[(long long)i * p.rstride + j] = acc[nt][v];
+                if (d.save) d.save[(long long)i * d.save_ld + j] = acc[nt][v];
+            }
+        }
+    __syncthreads();  // all waves are done with the stage buffers before the next unit writes them
+}
+
+// =================================================================================================
+// shrink, short unit: <= 32 rows; the 8 waves take alternate 64-wide k blocks (block b belongs to slice
+// (b / 8) % ksplit and wave b % 8) and tree-reduce their accumulators through LDS in a fixed order.
+// =================================================================================================
+template <int NT>
+__device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, float* lds)
+{
+    constexpr int MT = kShortRows / 16;
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, kg = lane >> 4;
 
     // Rows and ranks beyond the live ones read a live row instead: MFMA rows and columns are independent,
@@ -190,7 +223,7 @@ __device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, c
     // which (with a power-of-two row pitch) keeps hitting the same few HBM channels; so every tile starts
     // its sweep at a different block and wraps around.
     const int n_full = p.d_in / kBlockK;  // blocks that lie fully inside d_in; a shorter last block may follow
-    const int rot = n_full > 0 ? (int)(((unsigned)u.pos / kTileM * 37u) % (unsigned)n_full) : 0;  // same for all slices
+    const int rot = n_full > 0 ? (int)(((unsigned)u.pos * 37u) % (unsigned)n_full) : 0;  // same for all slices
     auto load = [&](int blk, u32x4 (&xv)[MT][2], u32x4 (&av)[NT][2]) {  // a block that lies fully inside d_in
         blk += rot;
         if (blk >= n_full) blk -= n_full;
@@ -200,7 +233,7 @@ __device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, c
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) xv[mt][q] = *reinterpret_cast<const u32x4*>(xrow[mt] + k);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) av[nt][q] = *(const __attribute__((address_space(1))) u32x4*)(arow[nt] + k);
+            for (int nt = 0; nt < NT; ++nt) av[nt][q] = *(gconst_u32x4)(arow[nt] + k);
         }
     };
     auto mma = [&](const u32x4 (&xv)[MT][2], const u32x4 (&av)[NT][2]) {
@@ -263,7 +296,7 @@ __device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, c
             }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const u32x4 v = *(const __attribute__((address_space(1))) u32x4*)(arow[nt] + kc);
+                const u32x4 v = *(gconst_u32x4)(arow[nt] + kc);
                 aa[nt][q] = in ? v : u32x4{0u, 0u, 0u, 0u};
             }
         }
@@ -297,7 +330,7 @@ __device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, c
     }
 
     if (w == 0) {
-        float* part = p.hpart + ((long long)ks * p.n_tokens + u.pos) * p.rstride;
+        const HDest d = h_dest(p, u, s, ks);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -305,18 +338,20 @@ __device__ __forceinline__ void shrink_unit(const FwdParams& p, const Unit& u, c
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int i = mt * 16 + kg * 4 + v, j = nt * 16 + c;
-                    if (i < u.len && j < s.rank) part[(long long)i * p.rstride + j] = acc[mt][nt][v];
+                    if (i < u.len && j < s.rank) {
+                        d.base[(long long)i * p.rstride + j] = acc[mt][nt][v];
+                        if (d.save) d.save[(long long)i * d.save_ld + j] = acc[mt][nt][v];
+                    }
                 }
     }
 }
 
 // =================================================================================================
-// expand, long segments: D[col][row] = sum_j B[j][col] (s h[row][j]) with 16x16x32 bf16 MFMA, h split
-// into a bf16 high and low part so that it keeps fp32 accuracy.  The output columns of two MFMA tiles
-// are interleaved so that a lane ends up with 8 consecutive columns of one row: a 16-byte access to y.
-// For pair q and tile m, MFMA row rho maps to column 32 q + 8 (rho / 4) + 4 m + (rho % 4) of the wave's
-// column range.  The unit's block of B is staged in LDS with coalesced loads, transposed into
-// fragments once and kept in registers while the rows stream by.
+// expand, long unit: D[col][row] = sum_j B[j][col] (s h[row][j]) with 16x16x32 bf16 MFMA, h split into
+// a bf16 high and low part so that it keeps fp32 accuracy.  The output columns of two MFMA tiles are
+// interleaved so that a lane ends up with 8 consecutive columns of one row: a 16-byte access to y.  For
+// pair q and tile m, MFMA row rho maps to column 32 q + 8 (rho / 4) + 4 m + (rho % 4) of the wave's
+// column range.
 // =================================================================================================
 __device__ __forceinline__ void split_bf16(const float (&v)[8], u32x4& hi, u32x4& lo)
 {
@@ -330,160 +365,178 @@ __device__ __forceinline__ void split_bf16(const float (&v)[8], u32x4& hi, u32x4
     lo = u32x4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
 }
 
-template <int KSTEPS, int PAIRS, bool MULTI>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, the unit
-                                              // 8 waves; MULTI: h arrives as several partials (ksplit > 1)
-__device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
-                                                 u16* lds_b)
-{
-    constexpr int WN = 32 * PAIRS, UN = kWaves * WN, ROWS = 32 * KSTEPS;
-    constexpr int PITCH = UN + 8;  // elements; keeps rows 16-byte aligned and spreads them over banks
-    constexpr int STAGE = ROWS * (UN / 8) / kThreads;  // 16-byte pieces of the B block per thread
-    static_assert(ROWS * (UN / 8) % kThreads == 0, "staging loop assumes an even split");
-    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, g = lane >> 4;
-    const int n_unit = n_block * UN;
+template <int KSTEPS, int PAIRS>
+struct ExpandCfg {
+    static constexpr int WN = 32 * PAIRS;            // columns per wave
+    static constexpr int UN = kWaves * WN;           // columns per unit
+    static constexpr int ROWS = 32 * KSTEPS;         // rank rows staged (ranks beyond the adapter's are zero)
+    static constexpr int CT = KSTEPS >= 4 ? 128 : 256;  // token rows per unit
+    static constexpr int BPITCH = UN + 8;            // elements per staged B row
+    static constexpr size_t B_BYTES = (size_t)ROWS * BPITCH * sizeof(u16);
+    static constexpr size_t H_BYTES = (size_t)(CT / 16) * KSTEPS * 2 * kWave * 16;  // [tile][kstep][hi|lo][lane] x 16 B
+    static constexpr size_t ROW_BYTES = (size_t)CT * sizeof(int);
+    static constexpr size_t LDS_BYTES = (B_BYTES > H_BYTES ? B_BYTES : H_BYTES) + ROW_BYTES;
+};
 
+template <int KSTEPS, int PAIRS>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, the unit 8 waves
+__device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
+                                                 unsigned char* lds)
+{
+    using C = ExpandCfg<KSTEPS, PAIRS>;
+    constexpr int STAGE = C::ROWS * (C::UN / 8) / kThreads;  // 16-byte pieces of the B block per thread
+    static_assert(C::ROWS * (C::UN / 8) % kThreads == 0, "staging loop assumes an even split");
+    u16* lds_b = reinterpret_cast<u16*>(lds);
+    u32x4* lds_h = reinterpret_cast<u32x4*>(lds);  // reuses the B region once the fragments are in registers
+    int* lds_row = reinterpret_cast<int*>(lds + (C::B_BYTES > C::H_BYTES ? C::B_BYTES : C::H_BYTES));
+    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, g = lane >> 4;
+    const int n_unit = n_block * C::UN;
+
+    // 1. the unit's block of B: coalesced loads -> LDS -> transposed MFMA fragments in registers
     {
         u32x4 v[STAGE];
 #pragma unroll
         for (int i = 0; i < STAGE; ++i) {
             const int id = (int)threadIdx.x + i * kThreads;
-            const int j = id / (UN / 8), n = n_unit + (id % (UN / 8)) * 8;
-            v[i] = *(const __attribute__((address_space(1))) u32x4*)(s.B + (long long)min(j, s.rank - 1) * p.d_out +
-                                                                     min(n, p.d_out - 8));
+            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
+            v[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
         }
-        __syncthreads();  // the previous unit's fragment reads are done
+        __syncthreads();  // the previous unit's LDS reads are done
 #pragma unroll
         for (int i = 0; i < STAGE; ++i) {
             const int id = (int)threadIdx.x + i * kThreads;
-            const int j = id / (UN / 8), n = n_unit + (id % (UN / 8)) * 8;
+            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
             const bool live = j < s.rank && n < p.d_out;
-            *reinterpret_cast<u32x4*>(lds_b + j * PITCH + (n - n_unit)) = live ? v[i] : u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(lds_b + j * C::BPITCH + (n - n_unit)) = live ? v[i] : u32x4{0u, 0u, 0u, 0u};
         }
-    }
-    // fine-tune segments: the unit of the first column block also stores the unscaled h rows
-    if (u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0) {
-        float* dst = p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank;
-        for (int id = (int)threadIdx.x; id < u.len * s.rank; id += kThreads) {
-            const int i = id / s.rank, j = id - i * s.rank;
-            float sum = 0.f;
-            for (int part = 0; part < p.ksplit; ++part)
-                sum += p.hpart[((long long)part * p.n_tokens + u.pos + i) * p.rstride + j];
-            dst[id] = sum;
-        }
+        for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
     }
     __syncthreads();
-
-    const int n_wave = n_unit + w * WN;
-    if (n_wave >= p.d_out) return;
+    const int n_wave = n_unit + w * C::WN;
     u32x4 bfrag[PAIRS][2][KSTEPS];
 #pragma unroll
     for (int q = 0; q < PAIRS; ++q)
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
-            const u16* col = lds_b + w * WN + 32 * q + 8 * (c >> 2) + 4 * m + (c & 3);
+            const u16* col = lds_b + w * C::WN + 32 * q + 8 * (c >> 2) + 4 * m + (c & 3);
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
                 unsigned int e[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) e[i] = col[(32 * ks + 8 * g + i) * PITCH];
+                for (int i = 0; i < 8; ++i) e[i] = col[(32 * ks + 8 * g + i) * C::BPITCH];
                 bfrag[q][m][ks] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
             }
         }
+    __syncthreads();  // all fragments are in registers; the region is reused for h
 
-    const int n_tiles = (u.len + 15) / 16;
+    // 2. the unit's h rows: slices added, (fine-tune segments, first column block: stored to h_out,)
+    // scaled, split into bf16 high/low, stored as ready-made fragments
+    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && p.ksplit > 1;
+    float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
+    for (int id = (int)threadIdx.x; id < C::CT * (C::ROWS / 8); id += kThreads) {
+        const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
+        const float* hp = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * jg;
+        f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
+        for (int part = 1; part < p.ksplit; ++part) {
+            const float* hq = hp + (long long)part * p.n_tokens * p.rstride;
+            h0 += *reinterpret_cast<const f32x4*>(hq);
+            h1 += *reinterpret_cast<const f32x4*>(hq + 4);
+        }
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float raw = e < 4 ? h0[e & 3] : h1[e & 3];
+            const bool live = i < u.len && 8 * jg + e < s.rank;
+            if (save && live) h_dst[(long long)i * s.rank + 8 * jg + e] = raw;
+            v[e] = live ? raw * s.scale : 0.f;
+        }
+        u32x4 hi, lo;
+        split_bf16(v, hi, lo);
+        const int slot = ((i / 16) * KSTEPS + jg / 4) * 2;
+        const int ln = (jg % 4) * 16 + (i % 16);
+        lds_h[(slot + 0) * kWave + ln] = hi;
+        lds_h[(slot + 1) * kWave + ln] = lo;
+    }
+    __syncthreads();
+    if (n_wave >= p.d_out) return;
+
+    // 3. stream y: 32 rows per step, the next step's loads in flight while this one is computed.  Loads
+    // are unconditional (dead rows and columns read a live address); only the stores are masked.
+    const int n_steps = (u.len + 31) / 32;
     const int n_lane = n_wave + 8 * g;  // + 32 q
-
-    // software pipeline: the next tile's row index, y and h are in flight while this one is computed.
-    // Loads are unconditional (dead rows and columns read a live address); only the stores are masked.
-    const int safe_row = max(row_of(p, u.pos), 0);
     int n_ld[PAIRS];
 #pragma unroll
     for (int q = 0; q < PAIRS; ++q) n_ld[q] = min(n_lane + 32 * q, p.d_out - 8);
-    int row_n;
-    u32x4 y_n[PAIRS];
-    f32x4 h_n[KSTEPS][2];
-    auto fetch = [&](int tile) {
-        const int i = tile * 16 + c;
-        row_n = i < u.len ? row_of(p, u.pos + i) : -1;
-        const u16* yrow = p.y + (long long)(row_n >= 0 ? row_n : safe_row) * p.ldy;
+    const int safe_row = max(lds_row[0], 0);
+    int row_n[2];
+    u32x4 y_n[2][PAIRS];
+    auto fetch = [&](int step) {
 #pragma unroll
-        for (int q = 0; q < PAIRS; ++q) y_n[q] = *reinterpret_cast<const u32x4*>(yrow + n_ld[q]);
-        const float* hp = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * g;
+        for (int t = 0; t < 2; ++t) {
+            row_n[t] = lds_row[min(step * 32 + t * 16 + c, C::CT - 1)];
+            const u16* yrow = p.y + (long long)(row_n[t] >= 0 ? row_n[t] : safe_row) * p.ldy;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            h_n[ks][0] = *reinterpret_cast<const f32x4*>(hp + 32 * ks);
-            h_n[ks][1] = *reinterpret_cast<const f32x4*>(hp + 32 * ks + 4);
-        }
-        if constexpr (MULTI) {
-            for (int part = 1; part < p.ksplit; ++part) {
-                const float* hq = hp + (long long)part * p.n_tokens * p.rstride;
-#pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks) {
-                    h_n[ks][0] += *reinterpret_cast<const f32x4*>(hq + 32 * ks);
-                    h_n[ks][1] += *reinterpret_cast<const f32x4*>(hq + 32 * ks + 4);
-                }
-            }
+            for (int q = 0; q < PAIRS; ++q) y_n[t][q] = *reinterpret_cast<const u32x4*>(yrow + n_ld[q]);
         }
     };
     fetch(0);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int row = row_n;
-        u32x4 yv[PAIRS];
-        f32x4 hv[KSTEPS][2];
+    for (int step = 0; step < n_steps; ++step) {
+        int row[2];
+        u32x4 yv[2][PAIRS];
 #pragma unroll
-        for (int q = 0; q < PAIRS; ++q) yv[q] = y_n[q];
+        for (int t = 0; t < 2; ++t) {
+            row[t] = row_n[t];
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) { hv[ks][0] = h_n[ks][0]; hv[ks][1] = h_n[ks][1]; }
-        fetch(min(tile + 1, n_tiles - 1));  // unconditional, so the loads in flight are counted statically
-
-        u32x4 h_hi[KSTEPS], h_lo[KSTEPS];
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            float v[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int j = 32 * ks + 8 * g + i;
-                const float raw = i < 4 ? hv[ks][0][i & 3] : hv[ks][1][i & 3];
-                v[i] = (row >= 0 && j < s.rank) ? raw * s.scale : 0.f;
-            }
-            split_bf16(v, h_hi[ks], h_lo[ks]);
+            for (int q = 0; q < PAIRS; ++q) yv[t][q] = y_n[t][q];
         }
-        f32x4 acc[PAIRS][2];
+        fetch(min(step + 1, n_steps - 1));  // unconditional, so the loads in flight are counted statically
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < PAIRS; ++q)
+        for (int t = 0; t < 2; ++t) {
+            const int tile = min(step * 2 + t, C::CT / 16 - 1);
+            u32x4 h_hi[KSTEPS], h_lo[KSTEPS];
 #pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                acc[q][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                h_hi[ks] = lds_h[((tile * KSTEPS + ks) * 2 + 0) * kWave + lane];
+                h_lo[ks] = lds_h[((tile * KSTEPS + ks) * 2 + 1) * kWave + lane];
+            }
+            f32x4 acc[PAIRS][2];
 #pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks) {
-                    acc[q][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bfrag[q][m][ks]), as_bf16x8(h_lo[ks]),
-                                                                        acc[q][m], 0, 0, 0);
-                    acc[q][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bfrag[q][m][ks]), as_bf16x8(h_hi[ks]),
-                                                                        acc[q][m], 0, 0, 0);
+            for (int q = 0; q < PAIRS; ++q)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    acc[q][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KSTEPS; ++ks) {
+                        acc[q][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bfrag[q][m][ks]), as_bf16x8(h_lo[ks]),
+                                                                            acc[q][m], 0, 0, 0);
+                        acc[q][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bfrag[q][m][ks]), as_bf16x8(h_hi[ks]),
+                                                                            acc[q][m], 0, 0, 0);
+                    }
+                }
+            if (row[t] >= 0 && step * 32 + t * 16 + c < u.len) {
+#pragma unroll
+                for (int q = 0; q < PAIRS; ++q) {
+                    if (n_lane + 32 * q < p.d_out) {
+                        float yf[8];
+                        unpack8(yv[t][q], yf);
+                        u32x4 o;
+                        o.x = pack_bf16x2(yf[0] + acc[q][0][0], yf[1] + acc[q][0][1]);
+                        o.y = pack_bf16x2(yf[2] + acc[q][0][2], yf[3] + acc[q][0][3]);
+                        o.z = pack_bf16x2(yf[4] + acc[q][1][0], yf[5] + acc[q][1][1]);
+                        o.w = pack_bf16x2(yf[6] + acc[q][1][2], yf[7] + acc[q][1][3]);
+                        *reinterpret_cast<u32x4*>(p.y + (long long)row[t] * p.ldy + n_lane + 32 * q) = o;
+                    }
                 }
             }
-        if (row >= 0) {
-#pragma unroll
-            for (int q = 0; q < PAIRS; ++q) {
-                if (n_lane + 32 * q < p.d_out) {
-                    float yf[8];
-                    unpack8(yv[q], yf);
-                    u32x4 o;
-                    o.x = pack_bf16x2(yf[0] + acc[q][0][0], yf[1] + acc[q][0][1]);
-                    o.y = pack_bf16x2(yf[2] + acc[q][0][2], yf[3] + acc[q][0][3]);
-                    o.z = pack_bf16x2(yf[4] + acc[q][1][0], yf[5] + acc[q][1][1]);
-                    o.w = pack_bf16x2(yf[6] + acc[q][1][2], yf[7] + acc[q][1][3]);
-                    *reinterpret_cast<u32x4*>(p.y + (long long)row * p.ldy + n_lane + 32 * q) = o;
-                }
-            }
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
 // =================================================================================================
-// expand, short segments: one wave per unit of <= 4 rows x 512 columns.  The wave sums the partial h
-// of its rows into its own LDS slab (scaled), then for every rank row j streams B[j][n .. n + 8) with
-// one 16-byte load per lane and accumulates h[t][j] * B[j][n + i] for the four rows.
+// expand, short unit: one wave per unit of <= 4 rows x 512 columns.  The wave puts the scaled h of its
+// rows into its own LDS slab, then for every rank row j streams B[j][n .. n + 8) with one 16-byte load
+// per lane and accumulates h[t][j] * B[j][n + i] for the four rows.
 // =================================================================================================
 struct ShortLds {
     __attribute__((aligned(16))) float hs[kWaves][LQ_MAX_RANK][kTT];  // per wave: hs[rank][row], scaled
@@ -494,17 +547,13 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
 {
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
     float (*hs)[kTT] = sh.hs[w];
-    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0;
-    const long long h_base = save ? p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : 0;
+    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && p.ksplit > 1;
+    float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     for (int i = lane; i < s.rank * kTT; i += kWave) {
         const int t = i / s.rank, j = i - t * s.rank;
-        float sum = 0.f;
-        if (t < u.len) {
-            for (int part = 0; part < p.ksplit; ++part)
-                sum += p.hpart[((long long)part * p.n_tokens + u.pos + t) * p.rstride + j];
-            if (save) p.h_out[h_base + (long long)t * s.rank + j] = sum;
-        }
-        hs[j][t] = sum * s.scale;
+        const float h = t < u.len ? h_sum(p, u.pos + t, j) : 0.f;
+        if (save && t < u.len) h_dst[(long long)t * s.rank + j] = h;
+        hs[j][t] = h * s.scale;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -527,7 +576,7 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
             for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
 #pragma unroll 8
         for (int j = 0; j < s.rank; ++j) {
-            const u32x4 v = *(const __attribute__((address_space(1))) u32x4*)(s.B + (long long)j * p.d_out + n);
+            const u32x4 v = *(gconst_u32x4)(s.B + (long long)j * p.d_out + n);
             const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs[j]);
             float bf[8];
             unpack8(v, bf);
@@ -559,65 +608,73 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
 // kernels
 // =================================================================================================
 template <int NT>
+constexpr size_t shrink_lds_bytes()
+{
+    const size_t tall = (size_t)2 * NT * 16 * (kStageK + 8) * sizeof(u16);
+    const size_t small = (size_t)(kWaves / 2) * (kShortRows / 16) * NT * 4 * kWave * sizeof(float);
+    return tall > small ? tall : small;
+}
+
+template <int NT>
 __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegLane c0 = load_seg_lane(p, n_seg, lane_id());
-    const int n_units = count_chunks(p, n_seg, c0, kTileM, kAll) * p.ksplit;
-    // Workgroup b runs on XCD b % 8 (round-robin dispatch).  Each XCD takes one contiguous eighth of the
-    // units, so the tiles of a segment share their adapter's A through one L2 instead of eight.
-    const int n_xcd = (int)gridDim.x % kXcds == 0 ? kXcds : 1;
-    const int per_xcd = (n_units + n_xcd - 1) / n_xcd;
-    const int first = ((int)blockIdx.x % n_xcd) * per_xcd, last = min(n_units, first + per_xcd);
-    for (int id = first + (int)blockIdx.x / n_xcd; id < last; id += (int)gridDim.x / n_xcd) {
+    const LenClass tall{kTallMin, kBig}, small{1, kTallMin};
+    const int n_tall = count_chunks(p, n_seg, c0, kTallRows, tall) * p.ksplit;
+    const int n_small = count_chunks(p, n_seg, c0, kShortRows, small) * p.ksplit;
+    const UnitRange r = xcd_unit_range(n_tall + n_small);
+    for (int id = r.start; id < r.last; id += r.step) {
         Unit u;
-        if (!find_chunk(p, n_seg, c0, id / p.ksplit, kTileM, kAll, u)) continue;
+        const bool is_tall = id < n_tall;
+        const int cid = is_tall ? id : id - n_tall;
+        if (!find_chunk(p, n_seg, c0, cid / p.ksplit, is_tall ? kTallRows : kShortRows, is_tall ? tall : small, u)) continue;
         const SegInfo s = load_adapter(p, u);
         if (!s.ok) continue;
-        shrink_unit<NT>(p, u, s, id % p.ksplit, lds_f);
+        if (is_tall) shrink_tall_unit<NT>(p, u, s, cid % p.ksplit, reinterpret_cast<u16*>(lds_raw));
+        else shrink_short_unit<NT>(p, u, s, cid % p.ksplit, reinterpret_cast<float*>(lds_raw));
     }
 }
 
-template <int KSTEPS, int PAIRS, bool MULTI>
+template <int KSTEPS, int PAIRS>
 __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) u16 lds_b[];
+    using C = ExpandCfg<KSTEPS, PAIRS>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegLane c0 = load_seg_lane(p, n_seg, lane_id());
+    const LenClass longs{kLongMin, kBig}, shorts{1, kLongMin};
 
     // long units, one per workgroup iteration
-    constexpr int UN = kWaves * 32 * PAIRS;
-    const int long_blocks = (p.d_out + UN - 1) / UN;
-    const int n_long = count_chunks(p, n_seg, c0, kChunkT, kLong) * long_blocks;
+    const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
+    const int n_long = count_chunks(p, n_seg, c0, C::CT, longs) * long_blocks;
     for (int id = (int)blockIdx.x; id < n_long; id += (int)gridDim.x) {
         Unit u;
-        if (!find_chunk(p, n_seg, c0, id / long_blocks, kChunkT, kLong, u)) continue;
+        if (!find_chunk(p, n_seg, c0, id / long_blocks, C::CT, longs, u)) continue;
         const SegInfo s = load_adapter(p, u);
         if (!s.ok) continue;
-        expand_long_unit<KSTEPS, PAIRS, MULTI>(p, u, s, id % long_blocks, lds_b);
+        expand_long_unit<KSTEPS, PAIRS>(p, u, s, id % long_blocks, lds_raw);
     }
 
     // short units, one per wave iteration, dealt round-robin over the workgroups first so that a few
     // hundred units spread over all compute units
     const int short_blocks = (p.d_out + kShortN - 1) / kShortN;
-    const int n_short = count_chunks(p, n_seg, c0, kTT, kShort) * short_blocks;
+    const int n_short = count_chunks(p, n_seg, c0, kTT, shorts) * short_blocks;
     const int w = uniform((int)threadIdx.x / kWave);
     for (int id = w * (int)gridDim.x + (int)blockIdx.x; id < n_short; id += kWaves * (int)gridDim.x) {
         Unit u;
-        if (!find_chunk(p, n_seg, c0, id / short_blocks, kTT, kShort, u)) continue;
+        if (!find_chunk(p, n_seg, c0, id / short_blocks, kTT, shorts, u)) continue;
         const SegInfo s = load_adapter(p, u);
         if (!s.ok) continue;
         expand_short_unit(p, u, s, id % short_blocks, sh);
     }
 }
 
-int rstride_for(int max_rank) { return (max_rank + 31) / 32 * 32; }
-int ksplit_cap(int n_tokens) { return n_tokens <= 16384 ? kMaxKSplit : 1; }
+int rstride_for(int max_rank) { return max_rank <= 32 ? 32 : max_rank <= 64 ? 64 : 128; }  // what the expand kernel reads per row
+int ksplit_cap(int n_tokens) { return n_tokens <= 32768 ? kMaxKSplit : 1; }
 int nt_for(int max_rank) { return max_rank <= 16 ? 1 : max_rank <= 32 ? 2 : max_rank <= 64 ? 4 : 8; }
-size_t shrink_lds_bytes(int nt) { return (size_t)(kWaves / 2) * (kTileM / 16) * nt * 4 * kWave * sizeof(float); }
-size_t expand_lds_bytes(int ksteps, int pairs) { return (size_t)32 * ksteps * (kWaves * 32 * pairs + 8) * sizeof(u16); }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -626,6 +683,9 @@ template <typename K>
 int resident_grid(K kernel, size_t dyn_lds)
 {
     int dev = 0, cus = 0, per_cu = 0;
+    if (dyn_lds > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)dyn_lds);
     if (hipGetDevice(&dev) != hipSuccess) return 256;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, dyn_lds) != hipSuccess || per_cu <= 0)
@@ -637,58 +697,48 @@ template <int NT>
 int shrink_grid()
 {
     static int grid = 0;
-    if (!grid) grid = resident_grid(shrink_kernel<NT>, shrink_lds_bytes(NT));
+    if (!grid) grid = resident_grid(shrink_kernel<NT>, shrink_lds_bytes<NT>());
     return grid;
 }
 
 // Few rows: cut d_in into slices so that the shrink units still cover the machine.  A pure function of
-// host arguments, so the two halves of the split variant agree on it.
+// host arguments.
 int choose_ksplit(int n_tokens, int seg_bound, int d_in, int grid)
 {
-    const long long tiles_est = (n_tokens + kTileM - 1) / kTileM + seg_bound / 2;
+    const long long units_est = (n_tokens + kTallRows - 1) / kTallRows + seg_bound / 2;
     int ks = 1;
-    while (ks < ksplit_cap(n_tokens) && tiles_est * ks * 2 <= grid && d_in >= ks * 2 * kWaves * kBlockK) ks *= 2;
+    while (ks < ksplit_cap(n_tokens) && units_est * ks * 2 <= grid && d_in >= ks * 2 * 2 * kStageK) ks *= 2;
     return ks;
 }
 
 template <int NT>
 hipError_t launch_shrink(const FwdParams& p, hipStream_t st)
 {
-    hipLaunchKernelGGL(shrink_kernel<NT>, dim3(shrink_grid<NT>()), dim3(kThreads), shrink_lds_bytes(NT), st, p);
-    return hipGetLastError();
-}
-
-template <int KSTEPS, int PAIRS, bool MULTI>
-hipError_t launch_expand_as(const FwdParams& p, hipStream_t st)
-{
-    static int grid = 0;
-    const size_t lds = expand_lds_bytes(KSTEPS, PAIRS);
-    if (!grid) {
-        if (lds > 48 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(expand_kernel<KSTEPS, PAIRS, MULTI>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        grid = resident_grid(expand_kernel<KSTEPS, PAIRS, MULTI>, lds);
-    }
-    hipLaunchKernelGGL((expand_kernel<KSTEPS, PAIRS, MULTI>), dim3(grid), dim3(kThreads), lds, st, p);
+    hipLaunchKernelGGL(shrink_kernel<NT>, dim3(shrink_grid<NT>()), dim3(kThreads), shrink_lds_bytes<NT>(), st, p);
     return hipGetLastError();
 }
 
 template <int KSTEPS, int PAIRS>
 hipError_t launch_expand(const FwdParams& p, hipStream_t st)
 {
-    return p.ksplit > 1 ? launch_expand_as<KSTEPS, PAIRS, true>(p, st) : launch_expand_as<KSTEPS, PAIRS, false>(p, st);
+    static int grid = 0;
+    const size_t lds = ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
+    if (!grid) grid = resident_grid(expand_kernel<KSTEPS, PAIRS>, lds);
+    hipLaunchKernelGGL((expand_kernel<KSTEPS, PAIRS>), dim3(grid), dim3(kThreads), lds, st, p);
+    return hipGetLastError();
 }
 
 }  // namespace
 }  // namespace lq
 
+// workspace: [header 256 B][hpart: cap x n_tokens x rstride floats]
 extern "C" size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,
                                                int32_t variant)
 {
     (void)d_in; (void)d_out; (void)variant;
     if (n_tokens < 0 || max_rank < 1) return lq::kWsHeaderBytes;
-    return (size_t)lq::kWsHeaderBytes +
-           (size_t)lq::ksplit_cap(n_tokens) * (size_t)n_tokens * (size_t)lq::rstride_for(max_rank) * sizeof(float);
+    const size_t h = (size_t)n_tokens * (size_t)lq::rstride_for(max_rank) * sizeof(float);
+    return (size_t)lq::kWsHeaderBytes + (size_t)lq::ksplit_cap(n_tokens) * h;
 }
 
 extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
@@ -730,10 +780,9 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     p.seg_starts = seg_starts; p.seg_adapter = seg_adapter; p.seg_kind = seg_kind;
     p.n_segments = n_segments; p.max_segments = max_segments;
     p.h_out = h_out; p.h_offsets = reinterpret_cast<const long long*>(h_offsets);
+    p.rstride = rstride_for(max_rank);
     p.err = static_cast<int*>(workspace);
     p.hpart = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWsHeaderBytes);
-    p.rstride = rstride_for(max_rank);
-    p.ksplit = 1;
 
     int seg_bound = max_segments;
     if (seg_bound > n_tokens) seg_bound = n_tokens;

@@ -1,0 +1,143 @@
+// Device-side reading of the segment tables, shared by the forward and backward kernels.
+//
+// The token rows of segment g are perm[seg_starts[g] .. seg_starts[g+1]).  Work is handed out in
+// chunks of at most `per` consecutive positions of one segment; chunk ids count through the segments
+// of a length class in order.  Every wave resolves chunk ids on its own with one wave scan per 64
+// segments (the first 64 are cached in registers; the tables are small and cache resident), so no
+// plan buffer or extra launch is needed and the grid can be a fixed number of resident workgroups.
+//
+// P is a kernel parameter block with the members seg_starts, seg_adapter, seg_kind, n_segments,
+// max_segments, n_adapters, max_rank, ranks, scales, A_ptrs, B_ptrs, perm, n_tokens, err.
+#pragma once
+
+#include "lq_common.h"
+
+namespace lq {
+
+struct SegLane { int st, en, ad, kd; };  // table entries of segment (batch * 64 + lane); empty beyond n_seg
+
+template <class P>
+__device__ __forceinline__ SegLane load_seg_lane(const P& p, int n_seg, int s)
+{
+    // the tables hold max_segments entries, so the loads can go out before n_seg has arrived
+    const int sc = min(s, p.max_segments - 1);
+    SegLane c;
+    c.st = p.seg_starts[sc];
+    c.en = p.seg_starts[sc + 1];
+    c.ad = p.seg_adapter[sc];
+    c.kd = p.seg_kind[sc];
+    if (s >= n_seg) c.st = c.en = c.ad = c.kd = 0;
+    return c;
+}
+
+struct Unit { int seg, pos, len, first, ad, kd; };
+
+struct LenClass { int lo, hi; };  // segments with lo <= rows < hi
+
+__device__ __forceinline__ int chunks_in(int len, int per, LenClass cls)
+{
+    return (len >= cls.lo && len < cls.hi && len > 0) ? (len + per - 1) / per : 0;
+}
+
+__device__ __forceinline__ int wave_sum(int v) { return uniform(__shfl(wave_inclusive_scan(v), kWave - 1, kWave)); }
+
+// number of chunks of `per` rows over the segments of a class; wave uniform
+template <class P>
+__device__ __forceinline__ int count_chunks(const P& p, int n_seg, const SegLane& c0, int per, LenClass cls)
+{
+    int total = wave_sum(chunks_in(c0.en - c0.st, per, cls));
+    for (int s0 = kWave; s0 < n_seg; s0 += kWave) {
+        const SegLane c = load_seg_lane(p, n_seg, s0 + lane_id());
+        total += wave_sum(chunks_in(c.en - c.st, per, cls));
+    }
+    return total;
+}
+
+// the id-th chunk (ids count through the segments of the class in order); wave uniform result
+template <class P>
+__device__ __forceinline__ bool find_chunk(const P& p, int n_seg, const SegLane& c0, int id, int per, LenClass cls,
+                                           Unit& u)
+{
+    int base = 0;
+    for (int s0 = 0; s0 < n_seg; s0 += kWave) {
+        const SegLane c = s0 == 0 ? c0 : load_seg_lane(p, n_seg, s0 + lane_id());
+        const int nch = chunks_in(c.en - c.st, per, cls);
+        const int incl = wave_inclusive_scan(nch);
+        const int total = uniform(__shfl(incl, kWave - 1, kWave));
+        if (id < base + total) {
+            const unsigned long long m = __ballot(base + incl > id);
+            const int l = __ffsll((long long)m) - 1;
+            const int local = id - base - uniform(__shfl(incl - nch, l, kWave));
+            u.seg = s0 + l;
+            u.first = uniform(__shfl(c.st, l, kWave));
+            u.pos = u.first + local * per;
+            u.len = min(per, uniform(__shfl(c.en, l, kWave)) - u.pos);
+            u.ad = uniform(__shfl(c.ad, l, kWave));
+            u.kd = uniform(__shfl(c.kd, l, kWave));
+            return true;
+        }
+        base += total;
+    }
+    return false;
+}
+
+// Adapter matrices come from a pointer table, so the compiler cannot infer their address space; saying
+// "global" turns flat loads into global loads.
+typedef const __attribute__((address_space(1))) u16* gconst_u16;
+typedef const __attribute__((address_space(1))) u32x4* gconst_u32x4;
+
+struct SegInfo {
+    gconst_u16 A; gconst_u16 B;
+    int rank; float scale;
+    bool ok;
+};
+
+template <class P>
+__device__ __forceinline__ SegInfo load_adapter(const P& p, const Unit& u)
+{
+    SegInfo s;
+    s.A = s.B = nullptr;
+    s.rank = 0;
+    s.scale = 0.f;
+    s.ok = u.ad >= 0 && u.ad < p.n_adapters;
+    if (s.ok) {
+        s.rank = p.ranks[u.ad];
+        s.scale = p.scales[u.ad];
+        s.A = (gconst_u16)(p.A_ptrs[u.ad]);
+        s.B = (gconst_u16)(p.B_ptrs[u.ad]);
+        s.ok = s.rank >= 1 && s.rank <= p.max_rank && s.A && s.B;
+    }
+    if (!s.ok && threadIdx.x == 0) atomicOr(p.err, kErrBadSegment);
+    return s;
+}
+
+// row of the activations for a position of the segment order; -1 if the table holds an invalid row
+template <class P>
+__device__ __forceinline__ int row_of(const P& p, int pos)
+{
+    // branch free: with perm == NULL a dummy entry is loaded and ignored
+    const int32_t* tab = p.perm ? p.perm : p.seg_starts;
+    const int v = tab[p.perm ? pos : 0];
+    const int row = p.perm ? v : pos;
+    return (row >= 0 && row < p.n_tokens) ? row : -1;
+}
+
+// Workgroup b runs on XCD b % 8 (round-robin dispatch).  Giving each XCD one contiguous eighth of the
+// unit ids keeps units that share an adapter (or a row range) on one L2 instead of eight.
+constexpr int kXcds = 8;
+struct UnitRange { int first, last, step, start; };
+__device__ __forceinline__ UnitRange xcd_unit_range(int n_units)
+{
+    const int n_xcd = (int)gridDim.x % kXcds == 0 ? kXcds : 1;
+    const int per_xcd = (n_units + n_xcd - 1) / n_xcd;
+    UnitRange r;
+    r.first = ((int)blockIdx.x % n_xcd) * per_xcd;
+    r.last = min(n_units, r.first + per_xcd);
+    r.step = (int)gridDim.x / n_xcd;
+    r.start = r.first + (int)blockIdx.x / n_xcd;
+    return r;
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
+
+}  // namespace lq
