@@ -111,7 +111,10 @@ lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token
  *            nothing is saved (inference-only batches)
  *   variant  one of LQ_VARIANT_*; split and fused give the same y and h_out up to fp32 summation
  *            order; h_out may be written by either half of the split variant
- *   workspace lora_forward_workspace_bytes(...) bytes.  n_tokens = 0 returns LQ_OK with no launch.
+ *   workspace lora_forward_workspace_bytes(...) bytes; its first 256 bytes must be ZERO before the first
+ *            call that uses it (error word, which the library only ORs into, and work counters that
+ *            every launch leaves at zero); the rest may hold anything.  n_tokens = 0 returns LQ_OK
+ *            with no launch.
  * ------------------------------------------------------------------------------------------- */
 size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,
                                     int32_t variant);

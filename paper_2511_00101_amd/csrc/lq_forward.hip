@@ -56,7 +56,51 @@ struct FwdParams {
     int ksplit;
     int rstride;     // 32, 64 or 128
     int* err;
+    int* tickets;    // workspace header words 4..7: ticket counters of the two kernels, zero between launches
 };
+
+// ---- unit hand-out --------------------------------------------------------------------------------
+// Units differ in size by more than 10x, so when there are more units than workgroups a workgroup draws
+// its units after the first one from a ticket counter instead of striding; the next ticket is fetched
+// while the current unit runs.  Relaxed device-scope atomics: no data depends on the counters.  The
+// last workgroup to leave puts both counters back to zero, so they are zero between launches.
+struct Tickets {
+    int* ctr;       // [0] next ticket, [1] workgroups that left
+    bool on;
+    int next;
+    int n_units;
+};
+__device__ __forceinline__ Tickets tickets_begin(int* ctr, int n_units)
+{
+    Tickets t;
+    t.ctr = ctr;
+    t.on = n_units > (int)gridDim.x;
+    t.next = (int)blockIdx.x;
+    t.n_units = n_units;
+    return t;
+}
+// returns this iteration's unit id (workgroup uniform) or -1; contains two barriers
+__device__ __forceinline__ int tickets_take(Tickets& t, int* lds_slot)
+{
+    __syncthreads();  // everyone has read the previous ticket
+    if (threadIdx.x == 0) *lds_slot = t.next;
+    __syncthreads();
+    const int id = *lds_slot;
+    if (id >= t.n_units) return -1;
+    if (threadIdx.x == 0)
+        t.next = t.on ? (int)gridDim.x + __hip_atomic_fetch_add(t.ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                      : t.n_units;
+    return id;
+}
+__device__ __forceinline__ void tickets_end(const Tickets& t)
+{
+    if (!t.on || threadIdx.x != 0) return;
+    const int left = __hip_atomic_fetch_add(t.ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (left == (int)gridDim.x - 1) {
+        __hip_atomic_store(t.ctr + 0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(t.ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
 
 // Where a shrink unit stores its h values: slice ks of the partial-h buffer.  With ksplit == 1 that is
 // the finished h, and fine-tune segments store it to h_out as well; with ksplit > 1 the expand kernel
@@ -128,52 +172,57 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
         for (int nt = 0; nt < NT; ++nt)
             *reinterpret_cast<u32x4*>(lds + buf * BUF + (nt * 16 + a_row) * PITCH + a_col) = ga[nt];
     };
-    // x block `blk` of this slice: stage ks + (blk / NB) * ksplit, block blk % NB inside it.  Past d_in
-    // the address is clamped into the row; the staged A is zero there, so those products vanish.
-    auto xload = [&](int blk, u32x4 (&xv)[2]) {
-        const int k0 = stage_of(blk / NB) * kStageK + (blk % NB) * kBlockK + kg * 8;
+    // x of a whole stage (4 blocks of 64 k) for this wave's 16 rows.  Past d_in the address is clamped
+    // into the row; the staged A is zero there, so those products vanish.
+    auto xload = [&](int stage, u32x4 (&xv)[NB][2]) {
+        const int k0 = stage * kStageK + kg * 8;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) xv[q] = *reinterpret_cast<const u32x4*>(xrow + min(k0 + 32 * q, p.d_in - 8));
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                xv[b][q] = *reinterpret_cast<const u32x4*>(xrow + min(k0 + b * kBlockK + 32 * q, p.d_in - 8));
     };
     f32x4 acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    auto mma = [&](const u32x4 (&xv)[2], int buf, int b) {
+    auto mma = [&](const u32x4 (&xv)[NB][2], int buf) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const u32x4 af = *reinterpret_cast<const u32x4*>(lds + buf * BUF + (nt * 16 + c) * PITCH + b * kBlockK +
-                                                                 32 * q + kg * 8);
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(xv[q]), as_bf16x8(af), acc[nt], 0, 0, 0);
-            }
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const u32x4 af = *reinterpret_cast<const u32x4*>(lds + buf * BUF + (nt * 16 + c) * PITCH +
+                                                                     b * kBlockK + 32 * q + kg * 8);
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(xv[b][q]), as_bf16x8(af), acc[nt], 0, 0, 0);
+                }
     };
 
-    const int n_blk = n_my * NB;
-    u32x4 ga[NT], xa[2], xb[2];
+    // Pipeline: while stage i is multiplied out of LDS (A) and registers (x), stage i + 1 is in flight:
+    // its A piece to registers (stored to the other LDS buffer at the top of the next iteration) and all
+    // of its x for this wave.  All loads are unconditional (past the end they re-read the last stage), so
+    // the count in flight is static.
+    u32x4 ga[NT], xa[NB][2], xb[NB][2];
     if (n_my > 0) {
         stage_load(stage_of(0), ga);
-        if (wave_live) xload(0, xa);
+        xload(stage_of(0), xa);
     }
-    for (int i = 0; i < n_my; ++i) {
-        const int buf = i & 1;
-        stage_store(buf, ga);
-        stage_load(stage_of(min(i + 1, n_my - 1)), ga);  // unconditional; the last one re-reads
+    for (int i = 0; i < n_my; i += 2) {
+        stage_store(0, ga);
+        stage_load(stage_of(min(i + 1, n_my - 1)), ga);
+        xload(stage_of(min(i + 1, n_my - 1)), xb);
         __syncthreads();  // one barrier per stage: the buffer written now was last read two stages ago
-        if (wave_live) {
-            const int b0 = i * NB;
-#pragma unroll
-            for (int b = 0; b < NB; b += 2) {
-                xload(min(b0 + b + 1, n_blk - 1), xb);
-                __builtin_amdgcn_sched_barrier(0);
-                mma(xa, buf, b);
-                __builtin_amdgcn_sched_barrier(0);
-                xload(min(b0 + b + 2, n_blk - 1), xa);
-                __builtin_amdgcn_sched_barrier(0);
-                mma(xb, buf, b + 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (wave_live) mma(xa, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + 1 >= n_my) break;
+        stage_store(1, ga);
+        stage_load(stage_of(min(i + 2, n_my - 1)), ga);
+        xload(stage_of(min(i + 2, n_my - 1)), xa);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (wave_live) mma(xb, 1);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     const HDest d = h_dest(p, u, s, ks);
@@ -368,71 +417,39 @@ __device__ __forceinline__ void split_bf16(const float (&v)[8], u32x4& hi, u32x4
 template <int KSTEPS, int PAIRS>
 struct ExpandCfg {
     static constexpr int WN = 32 * PAIRS;            // columns per wave
-    static constexpr int UN = kWaves * WN;           // columns per unit
+    static constexpr int UN = kWaves * WN;           // columns per block
     static constexpr int ROWS = 32 * KSTEPS;         // rank rows staged (ranks beyond the adapter's are zero)
     static constexpr int CT = KSTEPS >= 4 ? 128 : 256;  // token rows per unit
     static constexpr int BPITCH = UN + 8;            // elements per staged B row
     static constexpr size_t B_BYTES = (size_t)ROWS * BPITCH * sizeof(u16);
     static constexpr size_t H_BYTES = (size_t)(CT / 16) * KSTEPS * 2 * kWave * 16;  // [tile][kstep][hi|lo][lane] x 16 B
     static constexpr size_t ROW_BYTES = (size_t)CT * sizeof(int);
-    static constexpr size_t LDS_BYTES = (B_BYTES > H_BYTES ? B_BYTES : H_BYTES) + ROW_BYTES;
+    static constexpr size_t LDS_BYTES = B_BYTES + H_BYTES + ROW_BYTES;
 };
 
-template <int KSTEPS, int PAIRS>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, the unit 8 waves
-__device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
-                                                 unsigned char* lds)
+// One unit = up to CT rows of one segment x the column blocks [nb_begin, nb_end).  The rows' h (and row
+// indices) are prepared once and reused for every column block of the unit.
+template <int KSTEPS, int PAIRS>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, a block 8 waves
+__device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int nb_begin,
+                                                 int nb_end, unsigned char* lds)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
     constexpr int STAGE = C::ROWS * (C::UN / 8) / kThreads;  // 16-byte pieces of the B block per thread
     static_assert(C::ROWS * (C::UN / 8) % kThreads == 0, "staging loop assumes an even split");
     u16* lds_b = reinterpret_cast<u16*>(lds);
-    u32x4* lds_h = reinterpret_cast<u32x4*>(lds);  // reuses the B region once the fragments are in registers
-    int* lds_row = reinterpret_cast<int*>(lds + (C::B_BYTES > C::H_BYTES ? C::B_BYTES : C::H_BYTES));
+    u32x4* lds_h = reinterpret_cast<u32x4*>(lds + C::B_BYTES);
+    int* lds_row = reinterpret_cast<int*>(lds + C::B_BYTES + C::H_BYTES);
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, g = lane >> 4;
-    const int n_unit = n_block * C::UN;
 
-    // 1. the unit's block of B: coalesced loads -> LDS -> transposed MFMA fragments in registers
-    {
-        u32x4 v[STAGE];
-#pragma unroll
-        for (int i = 0; i < STAGE; ++i) {
-            const int id = (int)threadIdx.x + i * kThreads;
-            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
-            v[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
-        }
-        __syncthreads();  // the previous unit's LDS reads are done
-#pragma unroll
-        for (int i = 0; i < STAGE; ++i) {
-            const int id = (int)threadIdx.x + i * kThreads;
-            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
-            const bool live = j < s.rank && n < p.d_out;
-            *reinterpret_cast<u32x4*>(lds_b + j * C::BPITCH + (n - n_unit)) = live ? v[i] : u32x4{0u, 0u, 0u, 0u};
-        }
-        for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
-    }
-    __syncthreads();
-    const int n_wave = n_unit + w * C::WN;
-    u32x4 bfrag[PAIRS][2][KSTEPS];
-#pragma unroll
-    for (int q = 0; q < PAIRS; ++q)
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const u16* col = lds_b + w * C::WN + 32 * q + 8 * (c >> 2) + 4 * m + (c & 3);
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                unsigned int e[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) e[i] = col[(32 * ks + 8 * g + i) * C::BPITCH];
-                bfrag[q][m][ks] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-            }
-        }
-    __syncthreads();  // all fragments are in registers; the region is reused for h
+    __syncthreads();  // the previous unit's LDS reads are done
 
-    // 2. the unit's h rows: slices added, (fine-tune segments, first column block: stored to h_out,)
-    // scaled, split into bf16 high/low, stored as ready-made fragments
-    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && p.ksplit > 1;
+    // 1. the unit's rows and their h: slices added, (fine-tune segments, first column block: stored to
+    // h_out,) scaled, split into bf16 high/low, stored as ready-made fragments
+    for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
+    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && nb_begin == 0 && p.ksplit > 1;
     float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
-    for (int id = (int)threadIdx.x; id < C::CT * (C::ROWS / 8); id += kThreads) {
+    const int n_tiles = (u.len + 15) / 16;
+    for (int id = (int)threadIdx.x; id < n_tiles * 16 * (C::ROWS / 8); id += kThreads) {
         const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
         const float* hp = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * jg;
         f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
@@ -456,8 +473,44 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         lds_h[(slot + 0) * kWave + ln] = hi;
         lds_h[(slot + 1) * kWave + ln] = lo;
     }
+
+    for (int n_block = nb_begin; n_block < nb_end; ++n_block) {
+    const int n_unit = n_block * C::UN;
+    // 2. the block of B: coalesced loads -> LDS -> transposed MFMA fragments in registers
+    {
+        u32x4 v[STAGE];
+#pragma unroll
+        for (int i = 0; i < STAGE; ++i) {
+            const int id = (int)threadIdx.x + i * kThreads;
+            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
+            v[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
+        }
+        __syncthreads();  // the previous block's fragment reads are done
+#pragma unroll
+        for (int i = 0; i < STAGE; ++i) {
+            const int id = (int)threadIdx.x + i * kThreads;
+            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
+            const bool live = j < s.rank && n < p.d_out;
+            *reinterpret_cast<u32x4*>(lds_b + j * C::BPITCH + (n - n_unit)) = live ? v[i] : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
     __syncthreads();
-    if (n_wave >= p.d_out) return;
+    const int n_wave = n_unit + w * C::WN;
+    u32x4 bfrag[PAIRS][2][KSTEPS];
+#pragma unroll
+    for (int q = 0; q < PAIRS; ++q)
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const u16* col = lds_b + w * C::WN + 32 * q + 8 * (c >> 2) + 4 * m + (c & 3);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                unsigned int e[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) e[i] = col[(32 * ks + 8 * g + i) * C::BPITCH];
+                bfrag[q][m][ks] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+            }
+        }
+    if (n_wave >= p.d_out) continue;
 
     // 3. stream y: 32 rows per step, the next step's loads in flight while this one is computed.  Loads
     // are unconditional (dead rows and columns read a live address); only the stores are masked.
@@ -531,6 +584,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+    }  // column blocks
 }
 
 // =================================================================================================
@@ -620,21 +674,36 @@ __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
-    const SegLane c0 = load_seg_lane(p, n_seg, lane_id());
+    const SegCache c0 = load_seg_cache(p, n_seg);
     const LenClass tall{kTallMin, kBig}, small{1, kTallMin};
     const int n_tall = count_chunks(p, n_seg, c0, kTallRows, tall) * p.ksplit;
     const int n_small = count_chunks(p, n_seg, c0, kShortRows, small) * p.ksplit;
-    const UnitRange r = xcd_unit_range(n_tall + n_small);
-    for (int id = r.start; id < r.last; id += r.step) {
+    __shared__ int s_ticket;
+    Tickets tk = tickets_begin(p.tickets + 0, n_tall + n_small);
+    for (int id; (id = tickets_take(tk, &s_ticket)) >= 0;) {
         Unit u;
         const bool is_tall = id < n_tall;
         const int cid = is_tall ? id : id - n_tall;
         if (!find_chunk(p, n_seg, c0, cid / p.ksplit, is_tall ? kTallRows : kShortRows, is_tall ? tall : small, u)) continue;
         const SegInfo s = load_adapter(p, u);
         if (!s.ok) continue;
-        if (is_tall) shrink_tall_unit<NT>(p, u, s, cid % p.ksplit, reinterpret_cast<u16*>(lds_raw));
-        else shrink_short_unit<NT>(p, u, s, cid % p.ksplit, reinterpret_cast<float*>(lds_raw));
+        // the unit runs with as many 16-rank tiles as its adapter needs (at most NT, the launch's maximum)
+        const int ks = cid % p.ksplit;
+        u16* lds_a = reinterpret_cast<u16*>(lds_raw);
+        float* lds_r = reinterpret_cast<float*>(lds_raw);
+        if (is_tall) {
+            if (NT >= 8 && s.rank > 64) shrink_tall_unit<(NT >= 8 ? 8 : NT)>(p, u, s, ks, lds_a);
+            else if (NT >= 4 && s.rank > 32) shrink_tall_unit<(NT >= 4 ? 4 : NT)>(p, u, s, ks, lds_a);
+            else if (NT >= 2 && s.rank > 16) shrink_tall_unit<(NT >= 2 ? 2 : NT)>(p, u, s, ks, lds_a);
+            else shrink_tall_unit<1>(p, u, s, ks, lds_a);
+        } else {
+            if (NT >= 8 && s.rank > 64) shrink_short_unit<(NT >= 8 ? 8 : NT)>(p, u, s, ks, lds_r);
+            else if (NT >= 4 && s.rank > 32) shrink_short_unit<(NT >= 4 ? 4 : NT)>(p, u, s, ks, lds_r);
+            else if (NT >= 2 && s.rank > 16) shrink_short_unit<(NT >= 2 ? 2 : NT)>(p, u, s, ks, lds_r);
+            else shrink_short_unit<1>(p, u, s, ks, lds_r);
+        }
     }
+    tickets_end(tk);
 }
 
 template <int KSTEPS, int PAIRS>
@@ -644,19 +713,28 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
-    const SegLane c0 = load_seg_lane(p, n_seg, lane_id());
+    const SegCache c0 = load_seg_cache(p, n_seg);
     const LenClass longs{kLongMin, kBig}, shorts{1, kLongMin};
 
-    // long units, one per workgroup iteration
+    // long units, one per workgroup iteration: a chunk of rows x a group of column blocks.  Groups are as
+    // large as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
     const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
-    const int n_long = count_chunks(p, n_seg, c0, C::CT, longs) * long_blocks;
-    for (int id = (int)blockIdx.x; id < n_long; id += (int)gridDim.x) {
+    const int n_chunks = count_chunks(p, n_seg, c0, C::CT, longs);
+    const int groups_wanted = n_chunks > 0 ? (4 * (int)gridDim.x + n_chunks - 1) / n_chunks : 1;
+    const int per_group = max(1, long_blocks / max(1, min(long_blocks, groups_wanted)));
+    const int groups = (long_blocks + per_group - 1) / per_group;
+    const int n_long = n_chunks * groups;
+    __shared__ int s_ticket;
+    Tickets tk = tickets_begin(p.tickets + 2, n_long);
+    for (int id; (id = tickets_take(tk, &s_ticket)) >= 0;) {
         Unit u;
-        if (!find_chunk(p, n_seg, c0, id / long_blocks, C::CT, longs, u)) continue;
+        if (!find_chunk(p, n_seg, c0, id / groups, C::CT, longs, u)) continue;
         const SegInfo s = load_adapter(p, u);
         if (!s.ok) continue;
-        expand_long_unit<KSTEPS, PAIRS>(p, u, s, id % long_blocks, lds_raw);
+        const int nb = (id % groups) * per_group;
+        expand_long_unit<KSTEPS, PAIRS>(p, u, s, nb, min(long_blocks, nb + per_group), lds_raw);
     }
+    tickets_end(tk);
 
     // short units, one per wave iteration, dealt round-robin over the workgroups first so that a few
     // hundred units spread over all compute units
@@ -782,6 +860,7 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     p.h_out = h_out; p.h_offsets = reinterpret_cast<const long long*>(h_offsets);
     p.rstride = rstride_for(max_rank);
     p.err = static_cast<int*>(workspace);
+    p.tickets = static_cast<int*>(workspace) + 4;
     p.hpart = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWsHeaderBytes);
 
     int seg_bound = max_segments;

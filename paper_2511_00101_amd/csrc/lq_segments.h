@@ -3,7 +3,7 @@
 // The token rows of segment g are perm[seg_starts[g] .. seg_starts[g+1]).  Work is handed out in
 // chunks of at most `per` consecutive positions of one segment; chunk ids count through the segments
 // of a length class in order.  Every wave resolves chunk ids on its own with one wave scan per 64
-// segments (the first 64 are cached in registers; the tables are small and cache resident), so no
+// segments (the first 128 are cached in registers; the tables are small and cache resident), so no
 // plan buffer or extra launch is needed and the grid can be a fixed number of resident workgroups.
 //
 // P is a kernel parameter block with the members seg_starts, seg_adapter, seg_kind, n_segments,
@@ -30,6 +30,27 @@ __device__ __forceinline__ SegLane load_seg_lane(const P& p, int n_seg, int s)
     return c;
 }
 
+// the first kCachedBatches * 64 segments, one per lane and batch, held in registers by every wave
+constexpr int kCachedBatches = 2;
+struct SegCache { SegLane c[kCachedBatches]; };
+
+template <class P>
+__device__ __forceinline__ SegCache load_seg_cache(const P& p, int n_seg)
+{
+    SegCache sc;
+#pragma unroll
+    for (int b = 0; b < kCachedBatches; ++b) sc.c[b] = load_seg_lane(p, n_seg, b * kWave + lane_id());
+    return sc;
+}
+
+template <class P>
+__device__ __forceinline__ SegLane seg_batch(const P& p, int n_seg, const SegCache& sc, int s0)
+{
+    if (s0 == 0) return sc.c[0];
+    if (s0 == kWave) return sc.c[1];
+    return load_seg_lane(p, n_seg, s0 + lane_id());
+}
+
 struct Unit { int seg, pos, len, first, ad, kd; };
 
 struct LenClass { int lo, hi; };  // segments with lo <= rows < hi
@@ -43,11 +64,11 @@ __device__ __forceinline__ int wave_sum(int v) { return uniform(__shfl(wave_incl
 
 // number of chunks of `per` rows over the segments of a class; wave uniform
 template <class P>
-__device__ __forceinline__ int count_chunks(const P& p, int n_seg, const SegLane& c0, int per, LenClass cls)
+__device__ __forceinline__ int count_chunks(const P& p, int n_seg, const SegCache& sc, int per, LenClass cls)
 {
-    int total = wave_sum(chunks_in(c0.en - c0.st, per, cls));
-    for (int s0 = kWave; s0 < n_seg; s0 += kWave) {
-        const SegLane c = load_seg_lane(p, n_seg, s0 + lane_id());
+    int total = 0;
+    for (int s0 = 0; s0 < n_seg; s0 += kWave) {
+        const SegLane c = seg_batch(p, n_seg, sc, s0);
         total += wave_sum(chunks_in(c.en - c.st, per, cls));
     }
     return total;
@@ -55,12 +76,12 @@ __device__ __forceinline__ int count_chunks(const P& p, int n_seg, const SegLane
 
 // the id-th chunk (ids count through the segments of the class in order); wave uniform result
 template <class P>
-__device__ __forceinline__ bool find_chunk(const P& p, int n_seg, const SegLane& c0, int id, int per, LenClass cls,
+__device__ __forceinline__ bool find_chunk(const P& p, int n_seg, const SegCache& sc, int id, int per, LenClass cls,
                                            Unit& u)
 {
     int base = 0;
     for (int s0 = 0; s0 < n_seg; s0 += kWave) {
-        const SegLane c = s0 == 0 ? c0 : load_seg_lane(p, n_seg, s0 + lane_id());
+        const SegLane c = seg_batch(p, n_seg, sc, s0);
         const int nch = chunks_in(c.en - c.st, per, cls);
         const int incl = wave_inclusive_scan(nch);
         const int total = uniform(__shfl(incl, kWave - 1, kWave));
