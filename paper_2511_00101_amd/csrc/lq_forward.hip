@@ -56,7 +56,7 @@ struct FwdParams {
     int ksplit;
     int rstride;     // 32, 64 or 128
     int* err;
-    int* tickets;    // workspace header words 4..7: ticket counters of the two kernels, zero between launches
+    int* tickets;    // workspace header words 4..9: unit tickets of the two phases and the fused variant's barrier
 };
 
 // ---- unit hand-out --------------------------------------------------------------------------------
@@ -670,17 +670,14 @@ constexpr size_t shrink_lds_bytes()
 }
 
 template <int NT>
-__global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
+__device__ __forceinline__ void shrink_phase(const FwdParams& p, int n_seg, const SegCache& c0, unsigned char* lds_raw,
+                                             int* s_ticket)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
-    const SegCache c0 = load_seg_cache(p, n_seg);
     const LenClass tall{kTallMin, kBig}, small{1, kTallMin};
     const int n_tall = count_chunks(p, n_seg, c0, kTallRows, tall) * p.ksplit;
     const int n_small = count_chunks(p, n_seg, c0, kShortRows, small) * p.ksplit;
-    __shared__ int s_ticket;
     Tickets tk = tickets_begin(p.tickets + 0, n_tall + n_small);
-    for (int id; (id = tickets_take(tk, &s_ticket)) >= 0;) {
+    for (int id; (id = tickets_take(tk, s_ticket)) >= 0;) {
         Unit u;
         const bool is_tall = id < n_tall;
         const int cid = is_tall ? id : id - n_tall;
@@ -706,14 +703,21 @@ __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
     tickets_end(tk);
 }
 
-template <int KSTEPS, int PAIRS>
-__global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
+template <int NT>
+__global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
 {
-    using C = ExpandCfg<KSTEPS, PAIRS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    __shared__ ShortLds sh;
+    __shared__ int s_ticket;
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegCache c0 = load_seg_cache(p, n_seg);
+    shrink_phase<NT>(p, n_seg, c0, lds_raw, &s_ticket);
+}
+
+template <int KSTEPS, int PAIRS>
+__device__ __forceinline__ void expand_phase(const FwdParams& p, int n_seg, const SegCache& c0, unsigned char* lds_raw,
+                                             ShortLds& sh, int* s_ticket)
+{
+    using C = ExpandCfg<KSTEPS, PAIRS>;
     const LenClass longs{kLongMin, kBig}, shorts{1, kLongMin};
 
     // long units, one per workgroup iteration: a chunk of rows x a group of column blocks.  Groups are as
@@ -724,9 +728,8 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
     const int per_group = max(1, long_blocks / max(1, min(long_blocks, groups_wanted)));
     const int groups = (long_blocks + per_group - 1) / per_group;
     const int n_long = n_chunks * groups;
-    __shared__ int s_ticket;
     Tickets tk = tickets_begin(p.tickets + 2, n_long);
-    for (int id; (id = tickets_take(tk, &s_ticket)) >= 0;) {
+    for (int id; (id = tickets_take(tk, s_ticket)) >= 0;) {
         Unit u;
         if (!find_chunk(p, n_seg, c0, id / groups, C::CT, longs, u)) continue;
         const SegInfo s = load_adapter(p, u);
@@ -748,6 +751,69 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
         if (!s.ok) continue;
         expand_short_unit(p, u, s, id % short_blocks, sh);
     }
+}
+
+template <int KSTEPS, int PAIRS>
+__global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    __shared__ ShortLds sh;
+    __shared__ int s_ticket;
+    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
+    const SegCache c0 = load_seg_cache(p, n_seg);
+    expand_phase<KSTEPS, PAIRS>(p, n_seg, c0, lds_raw, sh, &s_ticket);
+}
+
+// =================================================================================================
+// fused single launch: every workgroup runs its shrink units, all workgroups meet at a device-wide
+// barrier (which also makes the h values visible across the XCDs' L2 caches), then every workgroup runs
+// its expand units.  The grid is exactly the number of workgroups that are resident at once, so every
+// workgroup reaches the barrier; the wait is bounded all the same, and a timeout is reported in the
+// workspace error word instead of hanging.
+//   tickets[4] = arrivals (back to zero when the last workgroup arrives), tickets[5] = generation.
+// =================================================================================================
+constexpr int kErrBarrierTimeout = 2;
+constexpr int kBarrierSpinLimit = 1 << 20;
+
+__device__ __forceinline__ void grid_barrier(const FwdParams& p, int gen0)
+{
+    __threadfence();  // release: this workgroup's h stores
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int* arrive = p.tickets + 4;
+        int* gen = p.tickets + 5;
+        const int before = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (before == (int)gridDim.x - 1) {
+            __hip_atomic_store(arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            int spins = 0;
+            while (__hip_atomic_load(gen, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
+                __builtin_amdgcn_s_sleep(8);
+                if (++spins > kBarrierSpinLimit) {
+                    atomicOr(p.err, kErrBarrierTimeout);
+                    break;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    __threadfence();  // acquire: other workgroups' h stores
+}
+
+template <int NT, int KSTEPS, int PAIRS>
+__global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    __shared__ ShortLds sh;
+    __shared__ int s_ticket;
+    // the generation is read before this workgroup arrives, hence before the last arrival can change it
+    const int gen0 = __hip_atomic_load(p.tickets + 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
+    const SegCache c0 = load_seg_cache(p, n_seg);
+    shrink_phase<NT>(p, n_seg, c0, lds_raw, &s_ticket);
+    grid_barrier(p, gen0);
+    expand_phase<KSTEPS, PAIRS>(p, n_seg, c0, lds_raw, sh, &s_ticket);
 }
 
 int rstride_for(int max_rank) { return max_rank <= 32 ? 32 : max_rank <= 64 ? 64 : 128; }  // what the expand kernel reads per row
@@ -806,6 +872,25 @@ hipError_t launch_expand(const FwdParams& p, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int NT, int KSTEPS, int PAIRS>
+int fused_grid()
+{
+    static int grid = 0;
+    const size_t lds = shrink_lds_bytes<NT>() > ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES ? shrink_lds_bytes<NT>()
+                                                                                   : ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
+    if (!grid) grid = resident_grid(fused_kernel<NT, KSTEPS, PAIRS>, lds);
+    return grid;
+}
+
+template <int NT, int KSTEPS, int PAIRS>
+hipError_t launch_fused(const FwdParams& p, hipStream_t st)
+{
+    const size_t lds = shrink_lds_bytes<NT>() > ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES ? shrink_lds_bytes<NT>()
+                                                                                   : ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
+    hipLaunchKernelGGL((fused_kernel<NT, KSTEPS, PAIRS>), dim3(fused_grid<NT, KSTEPS, PAIRS>()), dim3(kThreads), lds, st, p);
+    return hipGetLastError();
+}
+
 }  // namespace
 }  // namespace lq
 
@@ -842,7 +927,6 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     if (x && x == y) return LQ_ERR_INVALID_ARG;
     if (max_rank > LQ_MAX_RANK || n_adapters > LQ_MAX_ADAPTERS) return LQ_ERR_UNSUPPORTED;
     if ((d_in % 8) || (d_out % 8) || (ldx % 8) || (ldy % 8) || !aligned16(x) || !aligned16(y)) return LQ_ERR_UNSUPPORTED;
-    if (variant == LQ_VARIANT_FUSED) return LQ_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) ||
         !aligned16(workspace))
         return LQ_ERR_WORKSPACE;
@@ -869,9 +953,17 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int nt = nt_for(max_rank);
+    hipError_t e = hipSuccess;
+    if (variant == LQ_VARIANT_FUSED) {
+        const int grid_f = nt == 1 ? fused_grid<1, 1, 2>() : nt == 2 ? fused_grid<2, 1, 2>()
+                         : nt == 4 ? fused_grid<4, 2, 2>() : fused_grid<8, 4, 1>();
+        p.ksplit = choose_ksplit(n_tokens, seg_bound, d_in, grid_f);
+        e = nt == 1 ? launch_fused<1, 1, 2>(p, st) : nt == 2 ? launch_fused<2, 1, 2>(p, st)
+          : nt == 4 ? launch_fused<4, 2, 2>(p, st) : launch_fused<8, 4, 1>(p, st);
+        return e == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    }
     const int grid_s = nt == 1 ? shrink_grid<1>() : nt == 2 ? shrink_grid<2>() : nt == 4 ? shrink_grid<4>() : shrink_grid<8>();
     p.ksplit = choose_ksplit(n_tokens, seg_bound, d_in, grid_s);
-    hipError_t e = hipSuccess;
     if (variant != LQ_VARIANT_EXPAND_ONLY) {
         e = nt == 1 ? launch_shrink<1>(p, st) : nt == 2 ? launch_shrink<2>(p, st)
           : nt == 4 ? launch_shrink<4>(p, st) : launch_shrink<8>(p, st);

@@ -10,7 +10,7 @@ from gpu_util import DeviceProblem, assert_close, assert_tables_equal, check_for
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [lq.LQ_VARIANT_SPLIT]
+VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED]
 
 
 # ---------------------------------------------------------------------------------------------------
