@@ -777,28 +777,30 @@ constexpr int kBarrierSpinLimit = 1 << 20;
 
 __device__ __forceinline__ void grid_barrier(const FwdParams& p, int gen0)
 {
-    __threadfence();  // release: this workgroup's h stores
     __syncthreads();
     if (threadIdx.x == 0) {
         int* arrive = p.tickets + 4;
         int* gen = p.tickets + 5;
-        const int before = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // this workgroup's h stores, once per workgroup
+        const int before = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (before == (int)gridDim.x - 1) {
             __hip_atomic_store(arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else {
+            // Poll with relaxed loads: an acquire per poll would invalidate caches that the workgroups
+            // still in the shrink phase are using.
             int spins = 0;
-            while (__hip_atomic_load(gen, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
-                __builtin_amdgcn_s_sleep(8);
+            while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
+                __builtin_amdgcn_s_sleep(16);
                 if (++spins > kBarrierSpinLimit) {
                     atomicOr(p.err, kErrBarrierTimeout);
                     break;
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // other workgroups' h stores
     }
     __syncthreads();
-    __threadfence();  // acquire: other workgroups' h stores
 }
 
 template <int NT, int KSTEPS, int PAIRS>
