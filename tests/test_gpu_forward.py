@@ -136,3 +136,41 @@ def test_repeat_calls_are_bit_identical(variant):
         d.build()
         outs.append(d.forward(variant)[0])
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+# ---------------------------------------------------------------------------------------------------
+# full-size workloads in the launch configuration the benchmark times
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config4_mlp_hetero_ranks(oracle_mod, variant, which):
+    check_forward(oracle_mod, synth.config4(which), variant)
+
+
+def test_config4_lora_term_alone(oracle_mod):
+    """y0 = 0, so the bound applies to the LoRA term itself and not to y0 + term."""
+    check_forward(oracle_mod, synth.config4("up", y0_zero=True), lq.LQ_VARIANT_SPLIT)
+
+
+@pytest.mark.parametrize("layer,projection", [(0, 0), (0, 1), (31, 4), (31, 6)])
+def test_config5_layer_stack_calls(oracle_mod, layer, projection):
+    """Four of the 224 (layer, projection) calls of the layer stack: q and k of layer 0, gate and down of layer 31."""
+    p = synth.config5(layer, projection, with_dy=False)
+    check_forward(oracle_mod, p, lq.LQ_VARIANT_SPLIT if projection % 2 == 0 else lq.LQ_VARIANT_FUSED)
+
+
+def test_large_rank_and_many_segments(oracle_mod):
+    """Ranks up to the maximum and more than 128 segments (beyond the register-cached part of the tables)."""
+    rng = np.random.default_rng(5)
+    n_ad = 150
+    ranks = rng.choice([4, 16, 40, 96, 128], size=n_ad)
+    lens = rng.choice([1, 2, 3, 17, 40, 70, 130], size=n_ad)
+    ta = np.concatenate([np.full(l, a, np.int32) for a, l in enumerate(lens)])
+    tk = np.concatenate([np.full(l, a % 3, np.uint8) for a, l in enumerate(lens)])
+    order = rng.permutation(len(ta))
+    # weights and scales small enough that |y| stays below 8: from there on half a bf16 ulp of the output
+    # alone (2^-5) exceeds the absolute bound
+    p = synth.make_problem("many", synth.Batch(ta[order], tk[order]), 1024, 1536, ranks, rng.uniform(0.5, 1.0, n_ad), 321,
+                           w_std=0.03)
+    for variant in VARIANTS:
+        check_forward(oracle_mod, p, variant)
