@@ -26,7 +26,8 @@
  *     before anything is launched.  Metadata that only the device can see (adapter id out
  *     of range, rank out of range) never causes an out-of-bounds access: the segment is
  *     skipped and bit 0 of the int32 at workspace offset 0 is set (the caller may zero and
- *     read that word; the library only ever ORs into it).
+ *     read that word; the library only ever ORs into it).  Bit 1 reports that the fused
+ *     variant's bounded device-wide wait timed out (its results are then incomplete).
  *   - x and y must not alias.  Rows of y that no segment covers are untouched bit for bit.
  *   - Calls on different streams that share a workspace race; give each stream its own.
  */
@@ -137,13 +138,18 @@ lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ld
  *     dB_a += s_a * h^T dy        dA_a += s_a * g^T x        dx[t, :] += s_a * g[t, :] * A_a
  *
  *   dy       bf16 [n_tokens, d_out] (rows of fine-tune tokens are read)
- *   dx       bf16 [n_tokens, d_in], read-modify-write on fine-tune rows only
+ *   dx       bf16 [n_tokens, d_in], read-modify-write on fine-tune rows only (one rounding per call);
+ *            must not alias x or dy
  *   h_saved  float, the h_out written by the forward (same h_offsets)
  *   dA_ptrs / dB_ptrs  [n_adapters] device arrays of device pointers to float [r_a, d_in] / [r_a, d_out],
- *            accumulated into (caller zeroes); entries of adapters without fine-tune segments may be NULL
- *   workspace lora_backward_workspace_bytes(...) bytes.
+ *            accumulated into (caller zeroes); entries may be NULL (that gradient is skipped), and
+ *            either table may be NULL; with both NULL only dx is computed
+ *   workspace lora_backward_workspace_bytes(...) bytes; its first 256 bytes zero as for the forward.
+ *   Four launches: shrink (g), weight-gradient partials, their reduction, expand (dx).  The order of
+ *   every sum is fixed, so results are reproducible run to run.
  * ------------------------------------------------------------------------------------------- */
-size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out);
+size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in,
+                                     int32_t d_out);
 
 lq_status lora_segmented_backward(const void* x, int64_t ldx, const void* dy, int64_t lddy, void* dx, int64_t lddx,
                                   int32_t d_in, int32_t d_out,

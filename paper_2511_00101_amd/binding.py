@@ -31,7 +31,7 @@ _SIGNATURES = {
     "lora_forward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_segmented_forward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _i32,
                                               _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
-    "lora_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
+    "lora_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_segmented_backward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp,
                                                _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
                                                _vp, _vp, _vp, _sz, _vp]),
@@ -86,8 +86,8 @@ def lora_forward_workspace_bytes(n_tokens: int, max_rank: int, d_in: int, d_out:
     return int(lib().lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant))
 
 
-def lora_backward_workspace_bytes(n_tokens: int, max_rank: int, d_in: int, d_out: int) -> int:
-    return int(lib().lora_backward_workspace_bytes(n_tokens, max_rank, d_in, d_out))
+def lora_backward_workspace_bytes(n_tokens: int, n_adapters: int, max_rank: int, d_in: int, d_out: int) -> int:
+    return int(lib().lora_backward_workspace_bytes(n_tokens, n_adapters, max_rank, d_in, d_out))
 
 
 @dataclass
@@ -191,7 +191,7 @@ def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTa
 
 
 def lora_segmented_backward(x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, adapters: AdapterTable,
-                            dA_ptrs: torch.Tensor, dB_ptrs: torch.Tensor, seg: SegmentTables,
+                            dA_ptrs: Optional[torch.Tensor], dB_ptrs: Optional[torch.Tensor], seg: SegmentTables,
                             h_saved: torch.Tensor, workspace: torch.Tensor, use_perm: bool = True, stream=None) -> None:
     assert x.dtype == torch.bfloat16 and dy.dtype == torch.bfloat16 and dx.dtype == torch.bfloat16
     n_tokens, d_in = int(x.shape[0]), int(x.shape[1])

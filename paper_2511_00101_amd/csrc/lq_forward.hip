@@ -24,7 +24,7 @@
 // contiguous bytes per instruction); on MI355X that streams from HBM within a few percent of a
 // row-contiguous pattern as long as nothing else competes for the address path, which is why A_a, B_a
 // and h reach the MFMA through LDS instead.
-#include "lq_segments.h"
+#include "lq_internal.h"
 
 namespace lq {
 namespace {
@@ -42,22 +42,6 @@ constexpr int kShortN = 512;     // expand, short unit: columns (64 lanes x 8)
 constexpr int kMaxKSplit = 8;
 constexpr int kBig = 0x7fffffff;
 
-struct FwdParams {
-    const u16* x; long long ldx;
-    u16* y; long long ldy;
-    int d_in, d_out;
-    const void* const* A_ptrs; const void* const* B_ptrs;
-    const int32_t* ranks; const float* scales; int n_adapters; int max_rank;
-    const int32_t* perm; int n_tokens;
-    const int32_t* seg_starts; const int32_t* seg_adapter; const uint8_t* seg_kind;
-    const int32_t* n_segments; int max_segments;
-    float* h_out; const long long* h_offsets;
-    float* hpart;    // [ksplit][n_tokens][rstride] h of each slice of d_in by position in segment order (unscaled)
-    int ksplit;
-    int rstride;     // 32, 64 or 128
-    int* err;
-    int* tickets;    // workspace header words 4..9: unit tickets of the two phases and the fused variant's barrier
-};
 
 // ---- unit hand-out --------------------------------------------------------------------------------
 // Units differ in size by more than 10x, so when there are more units than workgroups a workgroup draws
@@ -673,7 +657,7 @@ template <int NT>
 __device__ __forceinline__ void shrink_phase(const FwdParams& p, int n_seg, const SegCache& c0, unsigned char* lds_raw,
                                              int* s_ticket)
 {
-    const LenClass tall{kTallMin, kBig}, small{1, kTallMin};
+    const LenClass tall{kTallMin, kBig, p.kinds}, small{1, kTallMin, p.kinds};
     const int n_tall = count_chunks(p, n_seg, c0, kTallRows, tall) * p.ksplit;
     const int n_small = count_chunks(p, n_seg, c0, kShortRows, small) * p.ksplit;
     Tickets tk = tickets_begin(p.tickets + 0, n_tall + n_small);
@@ -718,7 +702,7 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, int n_seg, cons
                                              ShortLds& sh, int* s_ticket)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
-    const LenClass longs{kLongMin, kBig}, shorts{1, kLongMin};
+    const LenClass longs{kLongMin, kBig, p.kinds}, shorts{1, kLongMin, p.kinds};
 
     // long units, one per workgroup iteration: a chunk of rows x a group of column blocks.  Groups are as
     // large as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
@@ -818,11 +802,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     expand_phase<KSTEPS, PAIRS>(p, n_seg, c0, lds_raw, sh, &s_ticket);
 }
 
-int rstride_for(int max_rank) { return max_rank <= 32 ? 32 : max_rank <= 64 ? 64 : 128; }  // what the expand kernel reads per row
 int ksplit_cap(int n_tokens) { return n_tokens <= 32768 ? kMaxKSplit : 1; }
 int nt_for(int max_rank) { return max_rank <= 16 ? 1 : max_rank <= 32 ? 2 : max_rank <= 64 ? 4 : 8; }
 
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // number of workgroups of `kernel` that are resident at once on the current device
 template <typename K>
@@ -894,6 +876,38 @@ hipError_t launch_fused(const FwdParams& p, hipStream_t st)
 }
 
 }  // namespace
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int rstride_for(int max_rank) { return max_rank <= 32 ? 32 : max_rank <= 64 ? 64 : 128; }  // what the expand kernel reads per row
+
+size_t h_slices_bytes(int n_tokens, int max_rank)
+{
+    return (size_t)ksplit_cap(n_tokens) * (size_t)n_tokens * (size_t)rstride_for(max_rank) * sizeof(float);
+}
+
+hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream_t st)
+{
+    const int nt = nt_for(p.max_rank);
+    hipError_t e = hipSuccess;
+    if (variant == LQ_VARIANT_FUSED) {
+        const int grid_f = nt == 1 ? fused_grid<1, 1, 2>() : nt == 2 ? fused_grid<2, 1, 2>()
+                         : nt == 4 ? fused_grid<4, 2, 2>() : fused_grid<8, 4, 1>();
+        p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, seg_bound, p.d_in, grid_f);
+        return nt == 1 ? launch_fused<1, 1, 2>(p, st) : nt == 2 ? launch_fused<2, 1, 2>(p, st)
+             : nt == 4 ? launch_fused<4, 2, 2>(p, st) : launch_fused<8, 4, 1>(p, st);
+    }
+    const int grid_s = nt == 1 ? shrink_grid<1>() : nt == 2 ? shrink_grid<2>() : nt == 4 ? shrink_grid<4>() : shrink_grid<8>();
+    p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, seg_bound, p.d_in, grid_s);
+    if (variant != LQ_VARIANT_EXPAND_ONLY) {
+        e = nt == 1 ? launch_shrink<1>(p, st) : nt == 2 ? launch_shrink<2>(p, st)
+          : nt == 4 ? launch_shrink<4>(p, st) : launch_shrink<8>(p, st);
+        if (e != hipSuccess || variant == LQ_VARIANT_SHRINK_ONLY) return e;
+    }
+    return p.max_rank <= 32 ? launch_expand<1, 2>(p, st) : p.max_rank <= 64 ? launch_expand<2, 2>(p, st)
+                                                                            : launch_expand<4, 1>(p, st);
+}
+
 }  // namespace lq
 
 // workspace: [header 256 B][hpart: cap x n_tokens x rstride floats]
@@ -902,8 +916,7 @@ extern "C" size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_ran
 {
     (void)d_in; (void)d_out; (void)variant;
     if (n_tokens < 0 || max_rank < 1) return lq::kWsHeaderBytes;
-    const size_t h = (size_t)n_tokens * (size_t)lq::rstride_for(max_rank) * sizeof(float);
-    return (size_t)lq::kWsHeaderBytes + (size_t)lq::ksplit_cap(n_tokens) * h;
+    return (size_t)lq::kWsHeaderBytes + lq::h_slices_bytes(n_tokens, max_rank);
 }
 
 extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
@@ -953,25 +966,7 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     if (seg_bound > n_tokens) seg_bound = n_tokens;
     if ((long long)seg_bound > 3LL * n_adapters) seg_bound = 3 * n_adapters;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int nt = nt_for(max_rank);
-    hipError_t e = hipSuccess;
-    if (variant == LQ_VARIANT_FUSED) {
-        const int grid_f = nt == 1 ? fused_grid<1, 1, 2>() : nt == 2 ? fused_grid<2, 1, 2>()
-                         : nt == 4 ? fused_grid<4, 2, 2>() : fused_grid<8, 4, 1>();
-        p.ksplit = choose_ksplit(n_tokens, seg_bound, d_in, grid_f);
-        e = nt == 1 ? launch_fused<1, 1, 2>(p, st) : nt == 2 ? launch_fused<2, 1, 2>(p, st)
-          : nt == 4 ? launch_fused<4, 2, 2>(p, st) : launch_fused<8, 4, 1>(p, st);
-        return e == hipSuccess ? LQ_OK : LQ_ERR_HIP;
-    }
-    const int grid_s = nt == 1 ? shrink_grid<1>() : nt == 2 ? shrink_grid<2>() : nt == 4 ? shrink_grid<4>() : shrink_grid<8>();
-    p.ksplit = choose_ksplit(n_tokens, seg_bound, d_in, grid_s);
-    if (variant != LQ_VARIANT_EXPAND_ONLY) {
-        e = nt == 1 ? launch_shrink<1>(p, st) : nt == 2 ? launch_shrink<2>(p, st)
-          : nt == 4 ? launch_shrink<4>(p, st) : launch_shrink<8>(p, st);
-        if (e != hipSuccess) return LQ_ERR_HIP;
-        if (variant == LQ_VARIANT_SHRINK_ONLY) return LQ_OK;
-    }
-    e = max_rank <= 32 ? launch_expand<1, 2>(p, st) : max_rank <= 64 ? launch_expand<2, 2>(p, st) : launch_expand<4, 1>(p, st);
-    return e == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    p.ksplit_hint = 0;
+    p.kinds = kAllKinds;
+    return run_shrink_expand(p, variant, seg_bound, static_cast<hipStream_t>(stream)) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }

@@ -1,0 +1,40 @@
+// Declarations shared by the forward and backward translation units (not part of the C ABI).
+#pragma once
+
+#include "lq_segments.h"
+
+namespace lq {
+
+// Parameter block of the shrink / expand / fused kernels.  The backward pass reuses the same kernels
+// with the roles swapped (g = dy B^T is a shrink over d_out, dx += s g A is an expand over d_in).
+struct FwdParams {
+    const u16* x; long long ldx;
+    u16* y; long long ldy;
+    int d_in, d_out;
+    const void* const* A_ptrs; const void* const* B_ptrs;
+    const int32_t* ranks; const float* scales; int n_adapters; int max_rank;
+    const int32_t* perm; int n_tokens;
+    const int32_t* seg_starts; const int32_t* seg_adapter; const uint8_t* seg_kind;
+    const int32_t* n_segments; int max_segments;
+    float* h_out; const long long* h_offsets;
+    float* hpart;    // [ksplit][n_tokens][rstride] h of each slice of d_in by position in segment order (unscaled)
+    int ksplit;
+    int rstride;     // 32, 64 or 128
+    int* err;
+    int ksplit_hint; // host only: > 0 forces this split (the expand half of a pair repeats the shrink half's)
+    int kinds;       // bit k set: segments of kind k take part (forward: all; backward: fine-tune only)
+    int* tickets;    // workspace header words 4..9: unit tickets of the two phases and the fused variant's barrier
+};
+
+constexpr int kAllKinds = 7;
+constexpr int kFinetuneOnly = 1 << LQ_SEG_FINETUNE;
+
+bool aligned16(const void* p);
+int rstride_for(int max_rank);
+size_t h_slices_bytes(int n_tokens, int max_rank);   // bytes of the partial-h region of a workspace
+
+// Fills p.ksplit and enqueues: variant LQ_VARIANT_SPLIT / _FUSED / _SHRINK_ONLY / _EXPAND_ONLY.
+// p.ksplit_hint > 0 forces that split (the expand half of a pair must use the shrink half's value).
+hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream_t stream);
+
+}  // namespace lq

@@ -51,13 +51,13 @@ __device__ __forceinline__ SegLane seg_batch(const P& p, int n_seg, const SegCac
     return load_seg_lane(p, n_seg, s0 + lane_id());
 }
 
-struct Unit { int seg, pos, len, first, ad, kd; };
+struct Unit { int seg, pos, len, first, seg_len, ad, kd; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len)
 
-struct LenClass { int lo, hi; };  // segments with lo <= rows < hi
+struct LenClass { int lo, hi, kinds; };  // segments with lo <= rows < hi whose kind's bit is set in `kinds`
 
-__device__ __forceinline__ int chunks_in(int len, int per, LenClass cls)
+__device__ __forceinline__ int chunks_in(int len, int kind, int per, LenClass cls)
 {
-    return (len >= cls.lo && len < cls.hi && len > 0) ? (len + per - 1) / per : 0;
+    return (len >= cls.lo && len < cls.hi && len > 0 && ((cls.kinds >> kind) & 1)) ? (len + per - 1) / per : 0;
 }
 
 __device__ __forceinline__ int wave_sum(int v) { return uniform(__shfl(wave_inclusive_scan(v), kWave - 1, kWave)); }
@@ -69,7 +69,7 @@ __device__ __forceinline__ int count_chunks(const P& p, int n_seg, const SegCach
     int total = 0;
     for (int s0 = 0; s0 < n_seg; s0 += kWave) {
         const SegLane c = seg_batch(p, n_seg, sc, s0);
-        total += wave_sum(chunks_in(c.en - c.st, per, cls));
+        total += wave_sum(chunks_in(c.en - c.st, c.kd, per, cls));
     }
     return total;
 }
@@ -82,7 +82,7 @@ __device__ __forceinline__ bool find_chunk(const P& p, int n_seg, const SegCache
     int base = 0;
     for (int s0 = 0; s0 < n_seg; s0 += kWave) {
         const SegLane c = seg_batch(p, n_seg, sc, s0);
-        const int nch = chunks_in(c.en - c.st, per, cls);
+        const int nch = chunks_in(c.en - c.st, c.kd, per, cls);
         const int incl = wave_inclusive_scan(nch);
         const int total = uniform(__shfl(incl, kWave - 1, kWave));
         if (id < base + total) {
@@ -92,7 +92,8 @@ __device__ __forceinline__ bool find_chunk(const P& p, int n_seg, const SegCache
             u.seg = s0 + l;
             u.first = uniform(__shfl(c.st, l, kWave));
             u.pos = u.first + local * per;
-            u.len = min(per, uniform(__shfl(c.en, l, kWave)) - u.pos);
+            u.seg_len = uniform(__shfl(c.en, l, kWave)) - u.first;
+            u.len = min(per, u.first + u.seg_len - u.pos);
             u.ad = uniform(__shfl(c.ad, l, kWave));
             u.kd = uniform(__shfl(c.kd, l, kWave));
             return true;

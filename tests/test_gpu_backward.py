@@ -1,0 +1,99 @@
+"""GPU parity of the backward pass (fine-tune segments only) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_00101_amd import binding as lq
+from paper_2511_00101_amd import synth
+
+from gpu_util import DeviceProblem, assert_close, rel_frobenius
+
+pytestmark = pytest.mark.gpu
+
+# Weight gradients are fp32 sums of up to thousands of products of magnitude ~1, so their bound is relative:
+# the bf16 high/low split of h and g carries ~2^-16 per product and the sums are fp32.
+WGRAD_REL_FROBENIUS = 1e-3
+WGRAD_REL_MAX = 2e-3   # of the largest reference magnitude
+
+
+def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_SPLIT, dx0_seed=5):
+    rng = np.random.default_rng(dx0_seed)
+    dx0 = synth.normal_bf16(rng, (p.n_tokens, p.d_in), 1.0)
+    ref_f = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    ref_b = oracle_mod.backward(p.x, p.dy, dx0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+
+    d = DeviceProblem(p)
+    d.build()
+    d.forward(variant, h_elems=ref_f.segments.h_elems)          # writes h_out, which the backward consumes
+    dev = d.x.device
+    dx = lq.bf16_from_bits(dx0, dev)
+    dA = [torch.zeros(int(r), p.d_in, dtype=torch.float32, device=dev) for r in p.ranks]
+    dB = [torch.zeros(int(r), p.d_out, dtype=torch.float32, device=dev) for r in p.ranks]
+    dA_ptrs = torch.tensor([t.data_ptr() for t in dA], dtype=torch.int64, device=dev)
+    dB_ptrs = torch.tensor([t.data_ptr() for t in dB], dtype=torch.int64, device=dev)
+    ws = lq.workspace(lq.lora_backward_workspace_bytes(p.n_tokens, p.n_adapters, d.adapters.max_rank, p.d_in, p.d_out), dev)
+    lq.lora_segmented_backward(d.x, d.dy, dx, d.adapters, dA_ptrs, dB_ptrs, d.seg, d.h_out, ws)
+    torch.cuda.synchronize()
+    assert int(ws[0].item() & 0xffffffff) == 0
+
+    dx_bits = lq.bits_from_bf16(dx)
+    assert_close(synth.bf16_bits_to_f64(dx_bits), ref_b.dx, f"{p.name} dx")
+    ft = (p.batch.token_kind == 0) & (p.batch.token_adapter >= 0)
+    assert np.array_equal(dx_bits[~ft], dx0[~ft]), "rows that are not fine-tune rows must be untouched"
+    for a in range(p.n_adapters):
+        for got, ref, what in ((dA[a].cpu().numpy(), ref_b.dA[a], "dA"), (dB[a].cpu().numpy(), ref_b.dB[a], "dB")):
+            scale = float(np.abs(ref).max())
+            if scale == 0.0:
+                assert not np.any(got), f"{p.name} {what}[{a}] must stay zero"
+                continue
+            assert np.all(np.isfinite(got))
+            assert rel_frobenius(got, ref) <= WGRAD_REL_FROBENIUS, f"{p.name} {what}[{a}]"
+            assert float(np.abs(got - ref).max()) <= WGRAD_REL_MAX * scale, f"{p.name} {what}[{a}]"
+    return dx_bits, dA, dB
+
+
+def test_backward_tiny_config1(oracle_mod):
+    p = synth.config1()
+    rng = np.random.default_rng(77)
+    p.dy = synth.normal_bf16(rng, (p.n_tokens, p.d_out), 1.0)
+    run_backward(oracle_mod, p)
+
+
+@pytest.mark.parametrize("seed,T,d_in,d_out,ranks", [
+    (11, 200, 520, 264, [1, 3, 8, 64]),
+    (12, 700, 1032, 776, [16, 128, 5, 24]),
+    (13, 1300, 2048, 1024, [32, 32]),        # segments longer than one 512-row weight-gradient chunk
+])
+def test_backward_small_mixed(oracle_mod, seed, T, d_in, d_out, ranks):
+    p = synth.small_mixed(seed, T, d_in, d_out, ranks, drop_frac=0.1, with_dy=True, w_std=0.03,
+                          scales=np.linspace(0.5, 1.5, len(ranks)))
+    run_backward(oracle_mod, p)
+
+
+def test_backward_without_weight_gradients(oracle_mod):
+    """Both gradient tables NULL: only dx."""
+    p = synth.small_mixed(21, 150, 256, 512, [8, 16], with_dy=True)
+    dx0 = synth.normal_bf16(np.random.default_rng(1), (p.n_tokens, p.d_in), 1.0)
+    ref = oracle_mod.backward(p.x, p.dy, dx0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    d = DeviceProblem(p)
+    d.build()
+    dx = lq.bf16_from_bits(dx0)
+    ws = lq.workspace(lq.lora_backward_workspace_bytes(p.n_tokens, p.n_adapters, d.adapters.max_rank, p.d_in, p.d_out))
+    lq.lora_segmented_backward(d.x, d.dy, dx, d.adapters, None, None, d.seg, None, ws)
+    torch.cuda.synchronize()
+    assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(dx)), ref.dx, "dx")
+
+
+def test_backward_repeat_is_bit_identical(oracle_mod):
+    p = synth.small_mixed(31, 900, 1024, 1024, [16, 32], with_dy=True)
+    a = run_backward(oracle_mod, p)
+    b = run_backward(oracle_mod, p)
+    assert np.array_equal(a[0], b[0])
+    for x, y in zip(a[1] + a[2], b[1] + b[2]):
+        assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("layer,projection", [(0, 0), (31, 6)])
+def test_backward_config5_calls(oracle_mod, layer, projection):
+    """Two of the 224 (layer, projection) calls of the layer stack with its seeded dy."""
+    run_backward(oracle_mod, synth.config5(layer, projection, with_dy=True))
