@@ -154,6 +154,123 @@ def measure(p, variant, steps, warmup):
     return res
 
 
+class LayerStack:
+    """The 8B-shaped 32-layer stack (benchmark configs[4]): 7 LoRA projections per layer with their own
+    adapter weights, one batch structure for all 224 calls; forward of every call, then backward of the
+    fine-tune rows of every call.  Activations and weights are drawn on the GPU (same distributions as the
+    seeded generators; the parity tests use the seeded ones on sampled calls)."""
+
+    def __init__(self, variant, n_layers=None):
+        import numpy as np
+        import torch
+        from paper_2511_00101_amd import binding as lq
+        from paper_2511_00101_amd import synth
+        self.lq, self.torch, self.variant = lq, torch, variant
+        self.n_layers = n_layers or synth.N_LAYERS
+        dev = "cuda"
+        b = synth.config5_batch()
+        self.batch = b
+        T = b.n_tokens
+        self.T = T
+        n_ad, r = 16, 32
+        self.ranks_np = np.full(n_ad, r, np.int32)
+        gen = torch.Generator(device=dev).manual_seed(5000)
+        bf = torch.bfloat16
+
+        def act(cols, std=1.0):
+            return (torch.randn(T, cols, generator=gen, device=dev, dtype=torch.float32) * std).to(bf)
+
+        self.ta = torch.from_numpy(b.token_adapter).to(dev)
+        self.tk = torch.from_numpy(b.token_kind).to(dev)
+        self.seg = lq.SegmentTables.empty(T, n_ad, dev)
+        self.bws = lq.workspace(lq.lora_build_workspace_bytes(T, n_ad), dev)
+        self.calls = []
+        max_fws = max_bws = 0
+        for layer in range(self.n_layers):
+            xs = {4096: act(4096), 14336: act(14336)}          # q,k,v,(o),gate,up read a 4096-wide x; down a 14336-wide one
+            x_o = act(4096)
+            dxs = {4096: act(4096), 14336: act(14336)}
+            dx_o = act(4096)
+            for pi, (name, d_in, d_out) in enumerate(synth.LAYER_PROJECTIONS):
+                A = [(torch.randn(r, d_in, generator=gen, device=dev) * 0.02).to(bf) for _ in range(n_ad)]
+                B = [(torch.randn(r, d_out, generator=gen, device=dev) * 0.02).to(bf) for _ in range(n_ad)]
+                ad = lq.AdapterTable.from_tensors(A, B, [2.0] * n_ad, dev)
+                y = act(d_out)                                   # y0; after the forward it doubles as dy for the backward
+                dA = [torch.zeros(r, d_in, device=dev) if a < 2 else None for a in range(n_ad)]
+                dB = [torch.zeros(r, d_out, device=dev) if a < 2 else None for a in range(n_ad)]
+                dA_ptrs = torch.tensor([t.data_ptr() if t is not None else 0 for t in dA], dtype=torch.int64, device=dev)
+                dB_ptrs = torch.tensor([t.data_ptr() if t is not None else 0 for t in dB], dtype=torch.int64, device=dev)
+                h_out = torch.zeros(4096 * r, dtype=torch.float32, device=dev)
+                self.calls.append(dict(x=x_o if name == "o" else xs[d_in], dx=dx_o if name == "o" else dxs[d_in], y=y, ad=ad,
+                                       h_out=h_out, dA=dA, dB=dB, dA_ptrs=dA_ptrs, dB_ptrs=dB_ptrs, d_in=d_in, d_out=d_out))
+                max_fws = max(max_fws, lq.lora_forward_workspace_bytes(T, r, d_in, d_out, variant))
+                max_bws = max(max_bws, lq.lora_backward_workspace_bytes(T, n_ad, r, d_in, d_out))
+        self.fws = lq.workspace(max_fws, dev)
+        self.bwd_ws = lq.workspace(max_bws, dev)
+        self.ranks = self.calls[0]["ad"].ranks
+
+    def work(self):
+        """Algorithmic bytes / flops of one step (forward of all calls + backward of the fine-tune rows)."""
+        import numpy as np
+        b = self.batch
+        n_live, n_ft = b.n_tokens, int((b.token_kind == 0).sum())
+        r, used, used_ft = 32, 16, 2
+        fwd_b = bwd_b = fwd_f = bwd_f = 0
+        for c in self.calls:
+            di, do = c["d_in"], c["d_out"]
+            fwd_b += n_live * di * 2 + n_live * do * 4 + used * r * (di + do) * 2 + n_ft * r * 4
+            fwd_f += 2 * r * (di + do) * n_live
+            # backward: dy and x read once each for the weight gradients and once for g / dx's operands are the same
+            # rows, dx read + written, A and B of the fine-tune adapters, dA and dB read + written, h read
+            bwd_b += n_ft * do * 2 + n_ft * di * 2 + n_ft * di * 4 + used_ft * r * (di + do) * 2 + used_ft * r * (di + do) * 8 + n_ft * r * 4
+            bwd_f += 2 * r * (di + do) * n_ft * 2
+        return dict(fwd_bytes=fwd_b, bwd_bytes=bwd_b, fwd_flops=fwd_f, bwd_flops=bwd_f, tokens=n_live)
+
+    def step(self, i=0):
+        lq = self.lq
+        lq.lora_build_segments(self.ta, self.tk, self.ranks, self.seg, self.bws)
+        for c in self.calls:
+            lq.lora_segmented_forward(c["x"], c["y"], c["ad"], self.seg, c["h_out"], self.fws, self.variant)
+        for c in reversed(self.calls):
+            lq.lora_segmented_backward(c["x"], c["y"], c["dx"], c["ad"], c["dA_ptrs"], c["dB_ptrs"], self.seg, c["h_out"],
+                                       self.bwd_ws)
+
+    def forward_only(self):
+        for c in self.calls:
+            self.lq.lora_segmented_forward(c["x"], c["y"], c["ad"], self.seg, c["h_out"], self.fws, self.variant)
+
+    def backward_only(self):
+        for c in reversed(self.calls):
+            self.lq.lora_segmented_backward(c["x"], c["y"], c["dx"], c["ad"], c["dA_ptrs"], c["dB_ptrs"], self.seg, c["h_out"],
+                                            self.bwd_ws)
+
+
+def measure_layer_stack(variant, steps, warmup):
+    import torch
+    st = LayerStack(variant)
+    w = st.work()
+    for i in range(warmup):
+        st.step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        st.step(i)
+    torch.cuda.synchronize()
+    s_per_step = (time.perf_counter() - t0) / steps
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record(); st.forward_only(); ev[1].record(); st.backward_only(); ev[2].record()
+    torch.cuda.synchronize()
+    fwd_ms, bwd_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+    return dict(workload="cfg5_layer_stack (32 layers x 7 projections, forward + backward of the fine-tune rows)",
+                tokens=w["tokens"], calls=len(st.calls), ms_per_step=s_per_step * 1e3, tokens_per_s=w["tokens"] / s_per_step,
+                forward_ms=fwd_ms, backward_ms=bwd_ms,
+                forward_gbps=w["fwd_bytes"] / (fwd_ms * 1e-3) / 1e9, backward_gbps=w["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9,
+                forward_tflops=w["fwd_flops"] / (fwd_ms * 1e-3) / 1e12, backward_tflops=w["bwd_flops"] / (bwd_ms * 1e-3) / 1e12,
+                forward_hbm_frac=w["fwd_bytes"] / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                backward_hbm_frac=w["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                algorithmic_bytes=w["fwd_bytes"] + w["bwd_bytes"], flops=w["fwd_flops"] + w["bwd_flops"])
+
+
 def cpu_baseline(p, budget_s=12.0):
     """The fp64 oracle, as it stands, on the host cores: repeated whole-batch forwards for ~budget_s."""
     import oracle
@@ -176,8 +293,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--variant", choices=["split", "fused"], default="split")
     ap.add_argument("--workload", default="cfg2", help="headline workload: cfg1, cfg2, cfg3, cfg4up, cfg4down")
-    ap.add_argument("--others", default="cfg3,cfg4up,cfg4down", help="comma list of further workloads ('' = none)")
+    ap.add_argument("--others", default="cfg3,cfg4up,cfg4down,cfg5", help="comma list of further workloads ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device copy of known size (256 MiB read + 256 MiB written, 8 times) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's throughput; --gpus must be 1 "
@@ -192,6 +312,14 @@ def main():
         sys.exit(1)
     lq.lib()
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(256 * 2 ** 20, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(copy_bytes_read=src.numel(), copy_bytes_written=dst.numel(), copies=8)))
+        return
     variant = lq.LQ_VARIANT_FUSED if args.variant == "fused" else lq.LQ_VARIANT_SPLIT
     makers = dict(cfg1=synth.config1, cfg2=synth.config2, cfg3=synth.config3,
                   cfg4up=lambda: synth.config4("up"), cfg4down=lambda: synth.config4("down"))
@@ -200,6 +328,9 @@ def main():
     head = measure(p, variant, args.steps, args.warmup)
     others = []
     for name in [n for n in args.others.split(",") if n and n != args.workload]:
+        if name == "cfg5":
+            others.append(measure_layer_stack(variant, 3, 1))
+            continue
         q = makers[name]()
         others.append(measure(q, variant, max(20, args.steps // 4), max(5, args.warmup // 2)))
         del q

@@ -43,6 +43,8 @@ def test_workspace_sizes(lqlib):
     b = lqlib.lora_forward_workspace_bytes(512, 16, 4096, 4096, 0)
     assert 256 <= a < b
     assert lqlib.lora_build_workspace_bytes(100, 64) >= 256
+    c = lqlib.lora_backward_workspace_bytes(1024, 4, 16, 512, 768)
+    assert c > lqlib.lora_forward_workspace_bytes(1024, 16, 512, 768, 0)
 
 
 def test_host_validation_returns_codes_without_launching(lqlib):
@@ -66,6 +68,18 @@ def test_host_validation_returns_codes_without_launching(lqlib):
     assert fwd(ws=None) == lqlib.LQ_ERR_WORKSPACE
     assert fwd(ws_bytes=16) == lqlib.LQ_ERR_WORKSPACE
     assert fwd(T=0) == lqlib.LQ_OK                                # empty batch: nothing to do, nothing launched
+
+    def bwd(x=one, dy=al, dx=ctypes.c_void_p(0x3000), d_in=64, d_out=64, ldx=64, T=4, ws=ctypes.c_void_p(0x4000),
+            ws_bytes=1 << 30, max_rank=8):
+        return L.lora_segmented_backward(x, ldx, dy, 64, dx, 64, d_in, d_out, one, one, None, None, one, one, 2, max_rank,
+                                         one, T, one, one, one, one, 4, None, None, ws, ws_bytes, None)
+
+    assert bwd(d_in=0) == lqlib.LQ_ERR_INVALID_ARG
+    assert bwd(dx=one) == lqlib.LQ_ERR_INVALID_ARG               # dx aliases x
+    assert bwd(ldx=8) == lqlib.LQ_ERR_INVALID_ARG
+    assert bwd(max_rank=200) == lqlib.LQ_ERR_UNSUPPORTED
+    assert bwd(ws_bytes=100) == lqlib.LQ_ERR_WORKSPACE
+    assert bwd(T=0) == lqlib.LQ_OK
 
     def bld(T=4, n_ad=2, max_seg=4, ranks=one):
         return L.lora_build_segments(one, one, T, ranks, n_ad, one, one, one, one, one, one, max_seg, None, 0, None)
