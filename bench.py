@@ -102,27 +102,43 @@ def time_steps(rep, steps, warmup):
 
 
 def time_kernels(rep, steps, warmup):
-    """Average duration of each launch, from events recorded on the launch stream around every call."""
+    """Average duration of each kernel from HIP events on the launch stream, two ways, the smaller one kept:
+    (a) an event pair around every single launch (reads the duration plus a fixed event cost of a few
+    microseconds), (b) `steps` launches of one phase back to back between two events (reads the duration plus
+    the dispatch gap, but not less than the host's launch interval).  Both are upper bounds of the
+    kernel's own duration; rocprofv3's kernel trace of the same command is the reference (profiles/)."""
     torch, lq = rep.torch, rep.lq
     phases = (("build", None),) + ((("forward_fused", lq.LQ_VARIANT_FUSED),) if rep.variant == lq.LQ_VARIANT_FUSED else
                                    (("shrink", lq.LQ_VARIANT_SHRINK_ONLY), ("expand", lq.LQ_VARIANT_EXPAND_ONLY)))
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(steps)]
+
+    def launch(name, variant, i):
+        if name == "build":
+            rep.build(i)
+        else:
+            rep.forward(i, variant)
+
     for i in range(warmup):
         rep.step(i)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(steps)]
     torch.cuda.synchronize()
     for i in range(steps):
         ev[i][0].record()
         for k, (name, variant) in enumerate(phases):
-            if name == "build":
-                rep.build(warmup + i)
-            else:
-                rep.forward(warmup + i, variant)
+            launch(name, variant, warmup + i)
             ev[i][k + 1].record()
     torch.cuda.synchronize()
     out = {}
-    for k, (name, _) in enumerate(phases):
-        ms = sorted(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(steps))
-        out[name] = dict(avg_us=1e3 * sum(ms) / len(ms), median_us=1e3 * ms[len(ms) // 2], min_us=1e3 * ms[0])
+    for k, (name, variant) in enumerate(phases):
+        each = sorted(1e3 * ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(steps))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            launch(name, variant, i)
+        e1.record()
+        torch.cuda.synchronize()
+        train = 1e3 * e0.elapsed_time(e1) / steps
+        out[name] = dict(avg_us=min(sum(each) / len(each), train), per_launch_events_us=sum(each) / len(each),
+                         back_to_back_us=train, min_us=min(each[0], train))
     return out
 
 

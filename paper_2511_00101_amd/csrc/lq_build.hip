@@ -56,12 +56,13 @@ __device__ __forceinline__ int token_key(const int32_t* __restrict__ token_adapt
     return (a >= 0 && a < n_adapters && k <= LQ_SEG_DECODE) ? k * n_adapters + a : -1;
 }
 
+template <bool LDS_HIST>
 __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     const int32_t* __restrict__ token_adapter, const uint8_t* __restrict__ token_kind, int n_tokens,
     const int32_t* __restrict__ ranks, int n_adapters,
     int32_t* __restrict__ perm, int32_t* __restrict__ seg_starts, int32_t* __restrict__ seg_adapter,
     uint8_t* __restrict__ seg_kind, int64_t* __restrict__ h_offsets, int32_t* __restrict__ n_segments,
-    int32_t* ws_hist, int use_lds)
+    int32_t* ws_hist)
 {
     extern __shared__ int32_t lds_hist[];
     __shared__ int s_tot[kBuildWaves];
@@ -72,9 +73,13 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     const int n_entries = n_keys * kBuildWaves;
     // hist[key * 16 + wave]: tokens with that key in that wave's token range; scanned in place into
     // the position in perm where that wave's first such token goes.
-    int32_t* hist = use_lds ? lds_hist : ws_hist;
+    // (a compile-time choice, so that the common case gets LDS atomics instead of flat ones)
+    auto hist_at = [&](int i) -> int32_t* {
+        if constexpr (LDS_HIST) return lds_hist + i;
+        else return ws_hist + i;
+    };
 
-    for (int i = tid; i < n_entries; i += kBuildThreads) hist[i] = 0;
+    for (int i = tid; i < n_entries; i += kBuildThreads) *hist_at(i) = 0;
     __syncthreads();
 
     // each wave owns a contiguous token range (a multiple of 64 long), walked 64 tokens at a time
@@ -86,7 +91,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     for (int base = t_begin; base < t_end; base += kWave) {
         const int t = base + lane;
         const int key = t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1;
-        if (key >= 0) atomicAdd(&hist[key * kBuildWaves + w], 1);
+        if (key >= 0) atomicAdd(hist_at(key * kBuildWaves + w), 1);
     }
     __syncthreads();
 
@@ -95,12 +100,12 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     const int e_begin = min(n_entries, tid * per_thread);
     const int e_end = min(n_entries, e_begin + per_thread);
     int local = 0;
-    for (int i = e_begin; i < e_end; ++i) local += hist[i];
+    for (int i = e_begin; i < e_end; ++i) local += *hist_at(i);
     int n_live = 0;
     int run = block_exclusive_scan(local, s_tot, n_live);
     for (int i = e_begin; i < e_end; ++i) {
-        const int c = hist[i];
-        hist[i] = run;
+        const int c = *hist_at(i);
+        *hist_at(i) = run;
         run += c;
     }
     __syncthreads();
@@ -112,8 +117,8 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     int my_segs = 0;
     long long my_h = 0;
     for (int k = k_begin; k < k_end; ++k) {
-        const int start = hist[k * kBuildWaves];
-        const int next = (k + 1 < n_keys) ? hist[(k + 1) * kBuildWaves] : n_live;
+        const int start = *hist_at(k * kBuildWaves);
+        const int next = (k + 1 < n_keys) ? *hist_at((k + 1) * kBuildWaves) : n_live;
         const int cnt = next - start;
         if (cnt > 0) {
             ++my_segs;
@@ -125,8 +130,8 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     int seg = block_exclusive_scan(my_segs, s_tot, total_segs);
     long long h_run = block_exclusive_scan64(my_h, s_tot64, total_h);
     for (int k = k_begin; k < k_end; ++k) {
-        const int start = hist[k * kBuildWaves];
-        const int next = (k + 1 < n_keys) ? hist[(k + 1) * kBuildWaves] : n_live;
+        const int start = *hist_at(k * kBuildWaves);
+        const int next = (k + 1 < n_keys) ? *hist_at((k + 1) * kBuildWaves) : n_live;
         const int cnt = next - start;
         if (cnt > 0) {
             const int kind = k / n_adapters, a = k - kind * n_adapters;
@@ -155,7 +160,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
             const int k = __shfl(key, leader, kWave);
             const unsigned long long same = __ballot(key == k);
             int slot = 0;
-            if (lane == leader) slot = atomicAdd(&hist[k * kBuildWaves + w], __popcll(same));
+            if (lane == leader) slot = atomicAdd(hist_at(k * kBuildWaves + w), __popcll(same));
             slot = __shfl(slot, leader, kWave);
             if (key == k) perm[slot + __popcll(same & ((1ull << lane) - 1ull))] = t;
             todo &= ~same;
@@ -193,8 +198,13 @@ extern "C" lq_status lora_build_segments(const int32_t* token_adapter, const uin
         if (!workspace || workspace_bytes < lora_build_workspace_bytes(n_tokens, n_adapters)) return LQ_ERR_WORKSPACE;
         ws_hist = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + lq::kWsHeaderBytes);
     }
-    hipLaunchKernelGGL(lq::build_segments_kernel, dim3(1), dim3(lq::kBuildThreads), use_lds ? hist_bytes : 0,
-                       static_cast<hipStream_t>(stream), token_adapter, token_kind, n_tokens, ranks, n_adapters, perm,
-                       seg_starts, seg_adapter, seg_kind, h_offsets, n_segments, ws_hist, use_lds);
+    if (use_lds)
+        hipLaunchKernelGGL(lq::build_segments_kernel<true>, dim3(1), dim3(lq::kBuildThreads), hist_bytes,
+                           static_cast<hipStream_t>(stream), token_adapter, token_kind, n_tokens, ranks, n_adapters, perm,
+                           seg_starts, seg_adapter, seg_kind, h_offsets, n_segments, ws_hist);
+    else
+        hipLaunchKernelGGL(lq::build_segments_kernel<false>, dim3(1), dim3(lq::kBuildThreads), 0,
+                           static_cast<hipStream_t>(stream), token_adapter, token_kind, n_tokens, ranks, n_adapters, perm,
+                           seg_starts, seg_adapter, seg_kind, h_offsets, n_segments, ws_hist);
     return hipGetLastError() == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }
