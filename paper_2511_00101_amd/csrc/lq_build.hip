@@ -30,22 +30,33 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* s_tot, int& tota
     return before + incl - v;
 }
 
-__device__ __forceinline__ long long block_exclusive_scan64(long long v, long long* s_tot, long long& total)
+// two exclusive scans (an int and a 64-bit count) that share their barriers
+__device__ __forceinline__ void block_exclusive_scan_pair(int v, long long h, int* s_tot, long long* s_tot64, int& ex_v,
+                                                          long long& ex_h, int& total_v, long long& total_h)
 {
     const int lane = lane_id(), w = (int)threadIdx.x / kWave;
-    const long long incl = wave_inclusive_scan64(v);
+    const int incl_v = wave_inclusive_scan(v);
+    const long long incl_h = wave_inclusive_scan64(h);
     __syncthreads();
-    if (lane == kWave - 1) s_tot[w] = incl;
+    if (lane == kWave - 1) {
+        s_tot[w] = incl_v;
+        s_tot64[w] = incl_h;
+    }
     __syncthreads();
-    long long before = 0, all = 0;
+    int before_v = 0, all_v = 0;
+    long long before_h = 0, all_h = 0;
 #pragma unroll
     for (int i = 0; i < kBuildWaves; ++i) {
-        const long long t = s_tot[i];
-        if (i < w) before += t;
-        all += t;
+        const int t = s_tot[i];
+        const long long t64 = s_tot64[i];
+        if (i < w) { before_v += t; before_h += t64; }
+        all_v += t;
+        all_h += t64;
     }
-    total = all;
-    return before + incl - v;
+    total_v = all_v;
+    total_h = all_h;
+    ex_v = before_v + incl_v - v;
+    ex_h = before_h + incl_h - h;
 }
 
 __device__ __forceinline__ int token_key(const int32_t* __restrict__ token_adapter,
@@ -79,18 +90,28 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
         else return ws_hist + i;
     };
 
-    for (int i = tid; i < n_entries; i += kBuildThreads) *hist_at(i) = 0;
-    __syncthreads();
-
     // each wave owns a contiguous token range (a multiple of 64 long), walked 64 tokens at a time
     int per_wave = (n_tokens + kBuildWaves - 1) / kBuildWaves;
     per_wave = (per_wave + kWave - 1) / kWave * kWave;
     const int t_begin = min(n_tokens, w * per_wave);
     const int t_end = min(n_tokens, t_begin + per_wave);
 
+    // What the later phases need from memory is requested first, so that these round trips overlap the
+    // clearing of the histograms: the keys of the wave's first 64 tokens (all of them in a small batch)
+    // and the rank of the first key this thread turns into a segment.
+    const int key_first = t_begin + lane < t_end ? token_key(token_adapter, token_kind, t_begin + lane, n_adapters) : -1;
+    const int keys_per_thread = (n_keys + kBuildThreads - 1) / kBuildThreads;
+    const int k_begin = min(n_keys, tid * keys_per_thread);
+    const int k_end = min(n_keys, k_begin + keys_per_thread);
+    const int rank_first = k_begin < n_adapters ? ranks[k_begin] : 0;
+    auto rank_of_key = [&](int k) { return k == k_begin ? rank_first : ranks[k]; };  // k < n_adapters
+
+    for (int i = tid; i < n_entries; i += kBuildThreads) *hist_at(i) = 0;
+    __syncthreads();
+
     for (int base = t_begin; base < t_end; base += kWave) {
         const int t = base + lane;
-        const int key = t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1;
+        const int key = base == t_begin ? key_first : (t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1);
         if (key >= 0) atomicAdd(hist_at(key * kBuildWaves + w), 1);
     }
     __syncthreads();
@@ -111,9 +132,6 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     __syncthreads();
 
     // segments = non-empty keys, in key order
-    const int keys_per_thread = (n_keys + kBuildThreads - 1) / kBuildThreads;
-    const int k_begin = min(n_keys, tid * keys_per_thread);
-    const int k_end = min(n_keys, k_begin + keys_per_thread);
     int my_segs = 0;
     long long my_h = 0;
     for (int k = k_begin; k < k_end; ++k) {
@@ -122,13 +140,12 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
         const int cnt = next - start;
         if (cnt > 0) {
             ++my_segs;
-            if (k < n_adapters) my_h += (long long)cnt * ranks[k];  // kind 0 = fine-tune keeps h
+            if (k < n_adapters) my_h += (long long)cnt * rank_of_key(k);  // kind 0 = fine-tune keeps h
         }
     }
-    int total_segs = 0;
-    long long total_h = 0;
-    int seg = block_exclusive_scan(my_segs, s_tot, total_segs);
-    long long h_run = block_exclusive_scan64(my_h, s_tot64, total_h);
+    int total_segs = 0, seg = 0;
+    long long total_h = 0, h_run = 0;
+    block_exclusive_scan_pair(my_segs, my_h, s_tot, s_tot64, seg, h_run, total_segs, total_h);
     for (int k = k_begin; k < k_end; ++k) {
         const int start = *hist_at(k * kBuildWaves);
         const int next = (k + 1 < n_keys) ? *hist_at((k + 1) * kBuildWaves) : n_live;
@@ -139,7 +156,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
             seg_adapter[seg] = a;
             seg_kind[seg] = (uint8_t)kind;
             h_offsets[seg] = h_run;
-            if (kind == LQ_SEG_FINETUNE) h_run += (long long)cnt * ranks[a];
+            if (kind == LQ_SEG_FINETUNE) h_run += (long long)cnt * rank_of_key(k);
             ++seg;
         }
     }
@@ -150,21 +167,26 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     }
     __syncthreads();  // all reads of the scanned offsets are done before the scatter advances them
 
-    // stable scatter: within a 64-token round, lanes with equal keys are ranked by lane order
+    // Stable scatter.  Within a 64-token round every lane finds the lanes that hold the same key by
+    // voting on the key's bits one at a time; its rank among them is its offset from the slot that the
+    // first of them draws for the whole group.
+    int key_bits = 0;
+    while ((1 << key_bits) < n_keys) ++key_bits;
     for (int base = t_begin; base < t_end; base += kWave) {
         const int t = base + lane;
-        const int key = t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1;
-        unsigned long long todo = __ballot(key >= 0);
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int k = __shfl(key, leader, kWave);
-            const unsigned long long same = __ballot(key == k);
-            int slot = 0;
-            if (lane == leader) slot = atomicAdd(hist_at(k * kBuildWaves + w), __popcll(same));
-            slot = __shfl(slot, leader, kWave);
-            if (key == k) perm[slot + __popcll(same & ((1ull << lane) - 1ull))] = t;
-            todo &= ~same;
+        const int key = base == t_begin ? key_first : (t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1);
+        const bool valid = key >= 0;
+        unsigned long long peers = __ballot(valid);
+        for (int b = 0; b < key_bits; ++b) {
+            const bool bit = valid && ((key >> b) & 1);
+            const unsigned long long vote = __ballot(bit);
+            peers &= bit ? vote : ~vote;
         }
+        const int leader = valid ? __ffsll((long long)peers) - 1 : lane;
+        int slot = 0;
+        if (valid && lane == leader) slot = atomicAdd(hist_at(key * kBuildWaves + w), __popcll(peers));
+        slot = __shfl(slot, leader, kWave);
+        if (valid) perm[slot + __popcll(peers & ((1ull << lane) - 1ull))] = t;
     }
 }
 

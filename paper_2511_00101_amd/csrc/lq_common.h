@@ -46,70 +46,46 @@ __device__ __forceinline__ void unpack8(const u32x4& w, float* f)
 }
 
 // ---- wave primitives ---------------------------------------------------------------------------
+// v + (v of another lane, picked by a DPP control; 0 where that lane lies outside the row or the row is
+// masked off)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_add(int v)
+{
+    return v + __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+// Inclusive prefix sum over the 64 lanes with DPP moves (no LDS traffic): four shifted adds inside every
+// row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
 __device__ __forceinline__ int wave_inclusive_scan(int v)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        int o = __shfl_up(v, d, kWave);
-        if (lane_id() >= d) v += o;
-    }
+    v = dpp_add<0x111, 0xf>(v);  // row_shr:1
+    v = dpp_add<0x112, 0xf>(v);  // row_shr:2
+    v = dpp_add<0x114, 0xf>(v);  // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);  // row_shr:8
+    v = dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
     return v;
 }
+// the same for 64-bit values in [0, 2^54): the low 24 bits and the rest are scanned as two ints (neither
+// sum can overflow) and put together again
 __device__ __forceinline__ long long wave_inclusive_scan64(long long v)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        long long o = __shfl_up(v, d, kWave);
-        if (lane_id() >= d) v += o;
-    }
-    return v;
+    const int lo = wave_inclusive_scan((int)(v & 0xffffff));
+    const int hi = wave_inclusive_scan((int)(v >> 24));
+    return (long long)lo + ((long long)hi << 24);
 }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int lane_value(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }  // lane: wave uniform
 
-// ---- chunk lookup ------------------------------------------------------------------------------
-// The token rows of segment g are perm[seg_starts[g] .. seg_starts[g+1]).  Work is handed out in
-// chunks of at most `tokens_per_chunk` consecutive positions of one segment; chunk ids count
-// through the segments in order.  Every wave resolves its chunk id on its own with one wave scan
-// per 64 segments (the tables are small and cache resident), so no plan buffer or extra launch
-// is needed and the grid can be sized from host-known upper bounds.
-struct Chunk {
-    int seg;   // -1: chunk id beyond the last chunk
-    int pos;   // first position in perm
-    int len;   // rows in this chunk
-    int first; // position of the segment's first row
-};
-
-__device__ __forceinline__ Chunk find_chunk(const int32_t* __restrict__ seg_starts, int n_seg, int chunk_id,
-                                            int tokens_per_chunk)
+// n / d for 0 <= n and 1 <= d, both wave uniform and small: a reciprocal estimate and one correction
+// instead of the ~40-instruction exact sequence
+__device__ __forceinline__ int small_div(int n, int d)
 {
-    Chunk c;
-    c.seg = -1; c.pos = 0; c.len = 0; c.first = 0;
-    const int lane = lane_id();
-    int base = 0;
-    for (int s0 = 0; s0 < n_seg; s0 += kWave) {
-        const int s = s0 + lane;
-        int st = 0, en = 0;
-        if (s < n_seg) { st = seg_starts[s]; en = seg_starts[s + 1]; }
-        const int len = en > st ? en - st : 0;
-        const int nch = (len + tokens_per_chunk - 1) / tokens_per_chunk;
-        const int incl = wave_inclusive_scan(nch);
-        const int total = __shfl(incl, kWave - 1, kWave);
-        if (chunk_id < base + total) {
-            const unsigned long long m = __ballot(base + incl > chunk_id);
-            const int l = __ffsll((long long)m) - 1;
-            const int excl = __shfl(incl - nch, l, kWave);
-            const int sst = __shfl(st, l, kWave);
-            const int sen = __shfl(en, l, kWave);
-            const int local = chunk_id - base - excl;
-            c.seg = s0 + l;
-            c.first = sst;
-            c.pos = sst + local * tokens_per_chunk;
-            c.len = min(tokens_per_chunk, sen - c.pos);
-            return c;
-        }
-        base += total;
-    }
-    return c;
+    if (n >= (1 << 22)) return n / d;
+    int q = (int)((float)n * __builtin_amdgcn_rcpf((float)d));
+    const int r = n - q * d;
+    if (r >= d) ++q;
+    if (r < 0) --q;
+    return q;
 }
 
 }  // namespace lq

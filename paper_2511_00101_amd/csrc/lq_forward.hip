@@ -42,47 +42,57 @@ constexpr int kShortN = 512;     // expand, short unit: columns (64 lanes x 8)
 constexpr int kMaxKSplit = 8;
 constexpr int kBig = 0x7fffffff;
 
+// Optional in-kernel time stamps (a build with -DLQ_TRACE): thread 0 of every workgroup records the
+// 100 MHz wall clock at a few points of its first units; lq_trace_read copies the table out.
+#ifdef LQ_TRACE
+constexpr int kTraceSlots = 40, kTraceGroups = 1024;
+__device__ unsigned long long g_trace[2 * kTraceGroups * kTraceSlots];
+#define LQ_STAMP(k, id)                                                                                   \
+    do {                                                                                                  \
+        if (threadIdx.x == 0 && blockIdx.x < kTraceGroups && (id) < kTraceSlots)                          \
+            g_trace[((k) * kTraceGroups + blockIdx.x) * kTraceSlots + (id)] = wall_clock64();             \
+    } while (0)
+#define LQ_STAMP_WAIT(k, id)                                                                              \
+    do {                                                                                                  \
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                       \
+        LQ_STAMP(k, id);                                                                                  \
+    } while (0)
+#define LQ_UNIT_SLOT(it, j) (4 + 7 * (it) + (j))
+#else
+#define LQ_STAMP(k, id) ((void)0)
+#define LQ_STAMP_WAIT(k, id) ((void)0)
+#define LQ_UNIT_SLOT(it, j) 0
+#endif
+
 
 // ---- unit hand-out --------------------------------------------------------------------------------
-// Units differ in size by more than 10x, so when there are more units than workgroups a workgroup draws
-// its units after the first one from a ticket counter instead of striding; the next ticket is fetched
-// while the current unit runs.  Relaxed device-scope atomics: no data depends on the counters.  The
-// last workgroup to leave puts both counters back to zero, so they are zero between launches.
-struct Tickets {
-    int* ctr;       // [0] next ticket, [1] workgroups that left
-    bool on;
-    int next;
-    int n_units;
-};
-__device__ __forceinline__ Tickets tickets_begin(int* ctr, int n_units)
+// A workgroup's first unit is its own index.  Units differ in size by more than 10x, so when there are
+// more units than workgroups the later ones are drawn from a counter instead of striding; the draw is
+// issued before the current unit runs and read after it.  Relaxed device-scope atomics: no data depends
+// on the counters.  The last workgroup to leave puts both counters back to zero, so they are zero
+// between launches.  One barrier per unit, which also separates the units' uses of the LDS.
+//   ctr[0] next ticket, ctr[1] workgroups that left; slot: two ints of LDS
+template <class Body>
+__device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, Body&& body)
 {
-    Tickets t;
-    t.ctr = ctr;
-    t.on = n_units > (int)gridDim.x;
-    t.next = (int)blockIdx.x;
-    t.n_units = n_units;
-    return t;
-}
-// returns this iteration's unit id (workgroup uniform) or -1; contains two barriers
-__device__ __forceinline__ int tickets_take(Tickets& t, int* lds_slot)
-{
-    __syncthreads();  // everyone has read the previous ticket
-    if (threadIdx.x == 0) *lds_slot = t.next;
-    __syncthreads();
-    const int id = *lds_slot;
-    if (id >= t.n_units) return -1;
-    if (threadIdx.x == 0)
-        t.next = t.on ? (int)gridDim.x + __hip_atomic_fetch_add(t.ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                      : t.n_units;
-    return id;
-}
-__device__ __forceinline__ void tickets_end(const Tickets& t)
-{
-    if (!t.on || threadIdx.x != 0) return;
-    const int left = __hip_atomic_fetch_add(t.ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (left == (int)gridDim.x - 1) {
-        __hip_atomic_store(t.ctr + 0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(t.ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool on = n_units > (int)gridDim.x;
+    int id = (int)blockIdx.x;
+    for (int it = 0; id < n_units; ++it) {
+        int next = n_units;
+        if (on && threadIdx.x == 0)
+            next = (int)gridDim.x + __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        body(id, it);
+        if (!on) break;
+        if (threadIdx.x == 0) slot[it & 1] = next;
+        __syncthreads();
+        id = uniform(slot[it & 1]);
+    }
+    if (on && threadIdx.x == 0) {
+        const int left = __hip_atomic_fetch_add(ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left == (int)gridDim.x - 1) {
+            __hip_atomic_store(ctr + 0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -186,11 +196,13 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
     // its A piece to registers (stored to the other LDS buffer at the top of the next iteration) and all
     // of its x for this wave.  All loads are unconditional (past the end they re-read the last stage), so
     // the count in flight is static.
+    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 3));
     u32x4 ga[NT], xa[NB][2], xb[NB][2];
     if (n_my > 0) {
         stage_load(stage_of(0), ga);
         xload(stage_of(0), xa);
     }
+    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 4));
     for (int i = 0; i < n_my; i += 2) {
         stage_store(0, ga);
         stage_load(stage_of(min(i + 1, n_my - 1)), ga);
@@ -209,6 +221,7 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    LQ_STAMP(0, LQ_UNIT_SLOT(u.it, 5));
     const HDest d = h_dest(p, u, s, ks);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -220,7 +233,7 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
                 if (d.save) d.save[(long long)i * d.save_ld + j] = acc[nt][v];
             }
         }
-    __syncthreads();  // all waves are done with the stage buffers before the next unit writes them
+    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 6));
 }
 
 // =================================================================================================
@@ -260,14 +273,15 @@ __device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit
     auto load = [&](int blk, u32x4 (&xv)[MT][2], u32x4 (&av)[NT][2]) {  // a block that lies fully inside d_in
         blk += rot;
         if (blk >= n_full) blk -= n_full;
+        // A first: its addresses are known before the row indices (which x needs) have arrived
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int k = blk * kBlockK + 32 * q;
+        for (int q = 0; q < 2; ++q)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) xv[mt][q] = *reinterpret_cast<const u32x4*>(xrow[mt] + k);
+            for (int nt = 0; nt < NT; ++nt) av[nt][q] = *(gconst_u32x4)(arow[nt] + blk * kBlockK + 32 * q);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) av[nt][q] = *(gconst_u32x4)(arow[nt] + k);
-        }
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xv[mt][q] = *reinterpret_cast<const u32x4*>(xrow[mt] + blk * kBlockK + 32 * q);
     };
     auto mma = [&](const u32x4 (&xv)[MT][2], const u32x4 (&av)[NT][2]) {
 #pragma unroll
@@ -280,6 +294,7 @@ __device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit
                                                                           acc[mt][nt], 0, 0, 0);
     };
 
+    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 3));
     const int stride = kWaves * p.ksplit;
     int blk = ks * kWaves + w;
     if constexpr (NT <= 4) {
@@ -336,47 +351,37 @@ __device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit
         mma(xa, aa);
     }
 
-    // tree reduction over the 8 waves in a fixed order: slots[4][MT * NT * 4][64 lanes]
+    LQ_STAMP(0, LQ_UNIT_SLOT(u.it, 5));
+    // Sum over the 8 waves in a fixed order: every wave parks its accumulators in LDS ([wave][register]
+    // [lane]); after one barrier the 512 threads share the (register, lane) values, add the eight partial
+    // sums as a balanced tree and store the result.
     constexpr int REGS = MT * NT * 4;
-#pragma unroll
-    for (int half = kWaves / 2; half >= 1; half >>= 1) {
-        if (w >= half && w < 2 * half) {
-            float* slot = lds + (size_t)(w - half) * REGS * kWave + lane;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) slot[((mt * NT + nt) * 4 + v) * kWave] = acc[mt][nt][v];
-        }
-        __syncthreads();
-        if (w < half) {
-            const float* slot = lds + (size_t)w * REGS * kWave + lane;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[mt][nt][v] += slot[((mt * NT + nt) * 4 + v) * kWave];
-        }
-        __syncthreads();
-    }
-
-    if (w == 0) {
-        const HDest d = h_dest(p, u, s, ks);
+    {
+        float* mine = lds + (size_t)w * REGS * kWave + lane;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int i = mt * 16 + kg * 4 + v, j = nt * 16 + c;
-                    if (i < u.len && j < s.rank) {
-                        d.base[(long long)i * p.rstride + j] = acc[mt][nt][v];
-                        if (d.save) d.save[(long long)i * d.save_ld + j] = acc[mt][nt][v];
-                    }
-                }
+                for (int v = 0; v < 4; ++v) mine[((mt * NT + nt) * 4 + v) * kWave] = acc[mt][nt][v];
     }
+    const HDest d = h_dest(p, u, s, ks);
+    __syncthreads();
+#pragma unroll
+    for (int e = (int)threadIdx.x; e < REGS * kWave; e += kThreads) {
+        const int r = e / kWave, l = e % kWave;
+        float t[kWaves];
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) t[ww] = lds[((size_t)ww * REGS + r) * kWave + l];
+        const float sum = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+        const int v = r % 4, nt = (r / 4) % NT, mt = r / (4 * NT);
+        const int i = mt * 16 + (l >> 4) * 4 + v, jj = nt * 16 + (l & 15);
+        if (i < u.len && jj < s.rank) {
+            d.base[(long long)i * p.rstride + jj] = sum;
+            if (d.save) d.save[(long long)i * d.save_ld + jj] = sum;
+        }
+    }
+    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 6));
 }
 
 // =================================================================================================
@@ -425,8 +430,6 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     int* lds_row = reinterpret_cast<int*>(lds + C::B_BYTES + C::H_BYTES);
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, g = lane >> 4;
 
-    __syncthreads();  // the previous unit's LDS reads are done
-
     // 1. the unit's rows and their h: slices added, (fine-tune segments, first column block: stored to
     // h_out,) scaled, split into bf16 high/low, stored as ready-made fragments
     for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
@@ -458,6 +461,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         lds_h[(slot + 1) * kWave + ln] = lo;
     }
 
+    LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 3));
     for (int n_block = nb_begin; n_block < nb_end; ++n_block) {
     const int n_unit = n_block * C::UN;
     // 2. the block of B: coalesced loads -> LDS -> transposed MFMA fragments in registers
@@ -494,6 +498,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                 bfrag[q][m][ks] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
             }
         }
+    if (n_block == nb_begin) LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 4));
     if (n_wave >= p.d_out) continue;
 
     // 3. stream y: 32 rows per step, the next step's loads in flight while this one is computed.  Loads
@@ -568,7 +573,9 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+    if (n_block == nb_begin) LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 5));
     }  // column blocks
+    LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 6));
 }
 
 // =================================================================================================
@@ -583,47 +590,74 @@ struct ShortLds {
 __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
                                                   ShortLds& sh)
 {
+    constexpr int JG = 8;  // rank rows of B in flight per group
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
-    float (*hs)[kTT] = sh.hs[w];
+    float* hs = &sh.hs[w][0][0];  // hs[j][t] at j * kTT + t
     const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && p.ksplit > 1;
     float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
-    for (int i = lane; i < s.rank * kTT; i += kWave) {
-        const int t = i / s.rank, j = i - t * s.rank;
-        const float h = t < u.len ? h_sum(p, u.pos + t, j) : 0.f;
-        if (save && t < u.len) h_dst[(long long)t * s.rank + j] = h;
-        hs[j][t] = h * s.scale;
-    }
+    const int n = n_block * kShortN + lane * 8;
+    const int n_ld = min(n, p.d_out - 8);
+    const int rank_up = (s.rank + JG - 1) / JG * JG;
+
+    // The loads go out in the order rows, h, first group of B, y, so that each wait covers only what is
+    // needed next.  Everything is loaded unconditionally from clamped addresses.
+    int row[kTT];
+#pragma unroll
+    for (int t = 0; t < kTT; ++t) row[t] = t < u.len ? row_of(p, u.pos + t) : -1;
+
+    // item i = lane + 64 q is (row t = i % 4, rank j = i / 4); the first two per lane cover ranks up to 32
+    auto h_item = [&](int i) {
+        const int t = i & (kTT - 1), j = i >> 2;
+        const float h = h_sum(p, u.pos + min(t, u.len - 1), min(j, s.rank - 1));
+        const bool live = t < u.len && j < s.rank;
+        if (save && live) h_dst[(long long)t * s.rank + j] = h;
+        return live ? h * s.scale : 0.f;
+    };
+    const float h0 = h_item(lane), h1 = h_item(lane + kWave);
+
+    u32x4 bn[JG];
+#pragma unroll
+    for (int jj = 0; jj < JG; ++jj) bn[jj] = *(gconst_u32x4)(s.B + (long long)min(jj, s.rank - 1) * p.d_out + n_ld);
+    const int safe_row = max(row[0], 0);
+    u32x4 yv[kTT];
+#pragma unroll
+    for (int t = 0; t < kTT; ++t)
+        yv[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row[t] >= 0 ? row[t] : safe_row) * p.ldy + n_ld);
+
+    hs[lane] = h0;
+    hs[lane + kWave] = h1;
+    for (int i = lane + 2 * kWave; i < rank_up * kTT; i += kWave) hs[i] = h_item(i);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    int row[kTT];
+    float acc[kTT][8];
 #pragma unroll
-    for (int t = 0; t < kTT; ++t) row[t] = t < u.len ? row_of(p, u.pos + t) : -1;
-    const int n = n_block * kShortN + lane * 8;
-    if (n < p.d_out) {
-        const int safe_row = max(row[0], 0);
-        u32x4 yv[kTT];
+    for (int t = 0; t < kTT; ++t)
 #pragma unroll
-        for (int t = 0; t < kTT; ++t)
-            yv[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row[t] >= 0 ? row[t] : safe_row) * p.ldy + n);
-        float acc[kTT][8];
+        for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
+    for (int j0 = 0; j0 < rank_up; j0 += JG) {
+        u32x4 bc[JG];
 #pragma unroll
-        for (int t = 0; t < kTT; ++t)
+        for (int jj = 0; jj < JG; ++jj) bc[jj] = bn[jj];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
-#pragma unroll 8
-        for (int j = 0; j < s.rank; ++j) {
-            const u32x4 v = *(gconst_u32x4)(s.B + (long long)j * p.d_out + n);
-            const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs[j]);
+        for (int jj = 0; jj < JG; ++jj)  // the next group (past the end: the last row again, unused)
+            bn[jj] = *(gconst_u32x4)(s.B + (long long)min(j0 + JG + jj, s.rank - 1) * p.d_out + n_ld);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int jj = 0; jj < JG; ++jj) {
+            const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs + (j0 + jj) * kTT);  // zero beyond the rank
             float bf[8];
-            unpack8(v, bf);
+            unpack8(bc[jj], bf);
             const float h[kTT] = {h4.x, h4.y, h4.z, h4.w};
 #pragma unroll
             for (int t = 0; t < kTT; ++t)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc[t][i] = fmaf(h[t], bf[i], acc[t][i]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (n < p.d_out) {
 #pragma unroll
         for (int t = 0; t < kTT; ++t) {
             if (row[t] >= 0) {
@@ -649,27 +683,31 @@ template <int NT>
 constexpr size_t shrink_lds_bytes()
 {
     const size_t tall = (size_t)2 * NT * 16 * (kStageK + 8) * sizeof(u16);
-    const size_t small = (size_t)(kWaves / 2) * (kShortRows / 16) * NT * 4 * kWave * sizeof(float);
+    const size_t small = (size_t)kWaves * (kShortRows / 16) * NT * 4 * kWave * sizeof(float);
     return tall > small ? tall : small;
 }
 
 template <int NT>
-__device__ __forceinline__ void shrink_phase(const FwdParams& p, int n_seg, const SegCache& c0, unsigned char* lds_raw,
-                                             int* s_ticket)
+__device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdParams>& sg, unsigned char* lds_raw,
+                                             int* s_slot)
 {
     const LenClass tall{kTallMin, kBig, p.kinds}, small{1, kTallMin, p.kinds};
-    const int n_tall = count_chunks(p, n_seg, c0, kTallRows, tall) * p.ksplit;
-    const int n_small = count_chunks(p, n_seg, c0, kShortRows, small) * p.ksplit;
-    Tickets tk = tickets_begin(p.tickets + 0, n_tall + n_small);
-    for (int id; (id = tickets_take(tk, s_ticket)) >= 0;) {
+    const ClassScan ct = scan_class(p, sg, kTallRows, tall), cm = scan_class(p, sg, kShortRows, small);
+    const int n_tall = ct.total << p.ks_log2, n_small = cm.total << p.ks_log2;
+    LQ_STAMP(0, 2);
+    for_each_unit(p.tickets + 0, n_tall + n_small, s_slot, [&](int id, int it) {
         Unit u;
+        SegInfo s;
+        u.it = it;
+        LQ_STAMP(0, LQ_UNIT_SLOT(it, 0));
         const bool is_tall = id < n_tall;
         const int cid = is_tall ? id : id - n_tall;
-        if (!find_chunk(p, n_seg, c0, cid / p.ksplit, is_tall ? kTallRows : kShortRows, is_tall ? tall : small, u)) continue;
-        const SegInfo s = load_adapter(p, u);
-        if (!s.ok) continue;
+        const int chunk = cid >> p.ks_log2, ks = cid & (p.ksplit - 1);
+        const bool ok = is_tall ? find_unit(p, sg, ct, chunk, kTallRows, tall, u, s)
+                                : find_unit(p, sg, cm, chunk, kShortRows, small, u, s);
+        if (!ok) return;
+        LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(it, 2));
         // the unit runs with as many 16-rank tiles as its adapter needs (at most NT, the launch's maximum)
-        const int ks = cid % p.ksplit;
         u16* lds_a = reinterpret_cast<u16*>(lds_raw);
         float* lds_r = reinterpret_cast<float*>(lds_raw);
         if (is_tall) {
@@ -683,58 +721,66 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, int n_seg, cons
             else if (NT >= 2 && s.rank > 16) shrink_short_unit<(NT >= 2 ? 2 : NT)>(p, u, s, ks, lds_r);
             else shrink_short_unit<1>(p, u, s, ks, lds_r);
         }
-    }
-    tickets_end(tk);
+    });
+    LQ_STAMP_WAIT(0, 3);
 }
 
 template <int NT>
 __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    __shared__ int s_ticket;
-    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
-    const SegCache c0 = load_seg_cache(p, n_seg);
-    shrink_phase<NT>(p, n_seg, c0, lds_raw, &s_ticket);
+    __shared__ int s_slot[2];
+    LQ_STAMP(0, 0);
+    const Segs<FwdParams> sg = load_segs(p);
+    LQ_STAMP(0, 1);
+    shrink_phase<NT>(p, sg, lds_raw, s_slot);
 }
 
 template <int KSTEPS, int PAIRS>
-__device__ __forceinline__ void expand_phase(const FwdParams& p, int n_seg, const SegCache& c0, unsigned char* lds_raw,
-                                             ShortLds& sh, int* s_ticket)
+__device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdParams>& sg, unsigned char* lds_raw,
+                                             ShortLds& sh, int* s_slot)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
     const LenClass longs{kLongMin, kBig, p.kinds}, shorts{1, kLongMin, p.kinds};
+    const ClassScan cl = scan_class(p, sg, C::CT, longs), cs = scan_class(p, sg, kTT, shorts);
 
     // long units, one per workgroup iteration: a chunk of rows x a group of column blocks.  Groups are as
     // large as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
-    const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
-    const int n_chunks = count_chunks(p, n_seg, c0, C::CT, longs);
-    const int groups_wanted = n_chunks > 0 ? (4 * (int)gridDim.x + n_chunks - 1) / n_chunks : 1;
-    const int per_group = max(1, long_blocks / max(1, min(long_blocks, groups_wanted)));
-    const int groups = (long_blocks + per_group - 1) / per_group;
-    const int n_long = n_chunks * groups;
-    Tickets tk = tickets_begin(p.tickets + 2, n_long);
-    for (int id; (id = tickets_take(tk, s_ticket)) >= 0;) {
-        Unit u;
-        if (!find_chunk(p, n_seg, c0, id / groups, C::CT, longs, u)) continue;
-        const SegInfo s = load_adapter(p, u);
-        if (!s.ok) continue;
-        const int nb = (id % groups) * per_group;
-        expand_long_unit<KSTEPS, PAIRS>(p, u, s, nb, min(long_blocks, nb + per_group), lds_raw);
+    const int n_chunks = cl.total;
+    if (n_chunks > 0) {
+        const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
+        const int groups_wanted = small_div(4 * (int)gridDim.x + n_chunks - 1, n_chunks);
+        const int per_group = max(1, small_div(long_blocks, max(1, min(long_blocks, groups_wanted))));
+        const int groups = small_div(long_blocks + per_group - 1, per_group);
+        LQ_STAMP(1, 2);
+        for_each_unit(p.tickets + 2, n_chunks * groups, s_slot, [&](int id, int it) {
+            Unit u;
+            SegInfo s;
+            u.it = it;
+            LQ_STAMP(1, LQ_UNIT_SLOT(it, 0));
+            const int chunk = small_div(id, groups);
+            if (!find_unit(p, sg, cl, chunk, C::CT, longs, u, s)) return;
+            LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(it, 2));
+            const int nb = (id - chunk * groups) * per_group;
+            expand_long_unit<KSTEPS, PAIRS>(p, u, s, nb, min(long_blocks, nb + per_group), lds_raw);
+        });
     }
-    tickets_end(tk);
+    LQ_STAMP_WAIT(1, 3);
 
     // short units, one per wave iteration, dealt round-robin over the workgroups first so that a few
     // hundred units spread over all compute units
     const int short_blocks = (p.d_out + kShortN - 1) / kShortN;
-    const int n_short = count_chunks(p, n_seg, c0, kTT, shorts) * short_blocks;
+    const int n_short = cs.total * short_blocks;
     const int w = uniform((int)threadIdx.x / kWave);
     for (int id = w * (int)gridDim.x + (int)blockIdx.x; id < n_short; id += kWaves * (int)gridDim.x) {
         Unit u;
-        if (!find_chunk(p, n_seg, c0, id / short_blocks, kTT, shorts, u)) continue;
-        const SegInfo s = load_adapter(p, u);
-        if (!s.ok) continue;
-        expand_short_unit(p, u, s, id % short_blocks, sh);
+        SegInfo s;
+        u.it = 4;
+        const int chunk = small_div(id, short_blocks);
+        if (!find_unit(p, sg, cs, chunk, kTT, shorts, u, s)) continue;
+        expand_short_unit(p, u, s, id - chunk * short_blocks, sh);
     }
+    LQ_STAMP_WAIT(1, 39);
 }
 
 template <int KSTEPS, int PAIRS>
@@ -742,10 +788,11 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
-    __shared__ int s_ticket;
-    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
-    const SegCache c0 = load_seg_cache(p, n_seg);
-    expand_phase<KSTEPS, PAIRS>(p, n_seg, c0, lds_raw, sh, &s_ticket);
+    __shared__ int s_slot[2];
+    LQ_STAMP(1, 0);
+    const Segs<FwdParams> sg = load_segs(p);
+    LQ_STAMP(1, 1);
+    expand_phase<KSTEPS, PAIRS>(p, sg, lds_raw, sh, s_slot);
 }
 
 // =================================================================================================
@@ -792,16 +839,21 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
-    __shared__ int s_ticket;
+    __shared__ int s_slot[2];
     // the generation is read before this workgroup arrives, hence before the last arrival can change it
     const int gen0 = __hip_atomic_load(p.tickets + 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
-    const SegCache c0 = load_seg_cache(p, n_seg);
-    shrink_phase<NT>(p, n_seg, c0, lds_raw, &s_ticket);
+    const Segs<FwdParams> sg = load_segs(p);
+    shrink_phase<NT>(p, sg, lds_raw, s_slot);
     grid_barrier(p, gen0);
-    expand_phase<KSTEPS, PAIRS>(p, n_seg, c0, lds_raw, sh, &s_ticket);
+    expand_phase<KSTEPS, PAIRS>(p, sg, lds_raw, sh, s_slot);
 }
 
+int log2_of(int v)  // v is a power of two
+{
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
 int ksplit_cap(int n_tokens) { return n_tokens <= 32768 ? kMaxKSplit : 1; }
 int nt_for(int max_rank) { return max_rank <= 16 ? 1 : max_rank <= 32 ? 2 : max_rank <= 64 ? 4 : 8; }
 
@@ -894,11 +946,13 @@ hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream
         const int grid_f = nt == 1 ? fused_grid<1, 1, 2>() : nt == 2 ? fused_grid<2, 1, 2>()
                          : nt == 4 ? fused_grid<4, 2, 2>() : fused_grid<8, 4, 1>();
         p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, seg_bound, p.d_in, grid_f);
+        p.ks_log2 = log2_of(p.ksplit);
         return nt == 1 ? launch_fused<1, 1, 2>(p, st) : nt == 2 ? launch_fused<2, 1, 2>(p, st)
              : nt == 4 ? launch_fused<4, 2, 2>(p, st) : launch_fused<8, 4, 1>(p, st);
     }
     const int grid_s = nt == 1 ? shrink_grid<1>() : nt == 2 ? shrink_grid<2>() : nt == 4 ? shrink_grid<4>() : shrink_grid<8>();
     p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, seg_bound, p.d_in, grid_s);
+    p.ks_log2 = log2_of(p.ksplit);
     if (variant != LQ_VARIANT_EXPAND_ONLY) {
         e = nt == 1 ? launch_shrink<1>(p, st) : nt == 2 ? launch_shrink<2>(p, st)
           : nt == 4 ? launch_shrink<4>(p, st) : launch_shrink<8>(p, st);
@@ -909,6 +963,19 @@ hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream
 }
 
 }  // namespace lq
+
+#ifdef LQ_TRACE
+// copies the stamp table [kernel 0 = shrink, 1 = expand][workgroup][slot] to the host and clears it
+extern "C" int lq_trace_read(unsigned long long* host, int n_words)
+{
+    const size_t bytes = sizeof(unsigned long long) * 2 * lq::kTraceGroups * lq::kTraceSlots;
+    if ((size_t)n_words * sizeof(unsigned long long) < bytes) return -1;
+    void* dev = nullptr;
+    if (hipGetSymbolAddress(&dev, HIP_SYMBOL(lq::g_trace)) != hipSuccess) return -2;
+    if (hipMemcpy(host, dev, bytes, hipMemcpyDeviceToHost) != hipSuccess) return -3;
+    return hipMemset(dev, 0, bytes) == hipSuccess ? 0 : -4;
+}
+#endif
 
 // workspace: [header 256 B][hpart: cap x n_tokens x rstride floats]
 extern "C" size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,

@@ -18,7 +18,8 @@ struct FwdParams {
     const int32_t* n_segments; int max_segments;
     float* h_out; const long long* h_offsets;
     float* hpart;    // [ksplit][n_tokens][rstride] h of each slice of d_in by position in segment order (unscaled)
-    int ksplit;
+    int ksplit;      // a power of two
+    int ks_log2;
     int rstride;     // 32, 64 or 128
     int* err;
     int ksplit_hint; // host only: > 0 forces this split (the expand half of a pair repeats the shrink half's)

@@ -51,7 +51,7 @@ __device__ __forceinline__ SegLane seg_batch(const P& p, int n_seg, const SegCac
     return load_seg_lane(p, n_seg, s0 + lane_id());
 }
 
-struct Unit { int seg, pos, len, first, seg_len, ad, kd; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len)
+struct Unit { int seg, pos, len, first, seg_len, ad, kd, it; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len); it: loop count (tracing)
 
 struct LenClass { int lo, hi, kinds; };  // segments with lo <= rows < hi whose kind's bit is set in `kinds`
 
@@ -60,7 +60,7 @@ __device__ __forceinline__ int chunks_in(int len, int kind, int per, LenClass cl
     return (len >= cls.lo && len < cls.hi && len > 0 && ((cls.kinds >> kind) & 1)) ? (len + per - 1) / per : 0;
 }
 
-__device__ __forceinline__ int wave_sum(int v) { return uniform(__shfl(wave_inclusive_scan(v), kWave - 1, kWave)); }
+__device__ __forceinline__ int wave_sum(int v) { return lane_value(wave_inclusive_scan(v), kWave - 1); }
 
 // number of chunks of `per` rows over the segments of a class; wave uniform
 template <class P>
@@ -131,6 +131,147 @@ __device__ __forceinline__ SegInfo load_adapter(const P& p, const Unit& u)
     }
     if (!s.ok && threadIdx.x == 0) atomicOr(p.err, kErrBadSegment);
     return s;
+}
+
+// ---- unit lookup with the first 128 segments and the first 128 adapters held in registers -----------
+// At kernel start every lane loads the table entries of "its" two segments and the rank, scale and
+// matrix pointers of "its" two adapters, all in one round trip.  A lookup is then prefix sums with DPP
+// moves, a ballot and a few lane reads, and the matrix data can be requested right after it: a cold
+// start costs two dependent round trips (tables, then data) instead of three.  Segments and adapters
+// beyond the first 128 take the slower on-demand path above.
+struct AdLane { unsigned int a_lo, a_hi, b_lo, b_hi; int rank; float scale; };
+
+template <class P>
+struct Segs {
+    int n_seg;
+    SegLane c[kCachedBatches];
+    AdLane a[kCachedBatches];
+};
+
+template <class P>
+__device__ __forceinline__ Segs<P> load_segs(const P& p)
+{
+    Segs<P> sg;
+    const int n_raw = *p.n_segments;
+    SegLane raw[kCachedBatches];
+#pragma unroll
+    for (int b = 0; b < kCachedBatches; ++b) {
+        const int sc = min(b * kWave + lane_id(), p.max_segments - 1);  // the tables hold max_segments entries
+        raw[b].st = p.seg_starts[sc];
+        raw[b].en = p.seg_starts[sc + 1];
+        raw[b].ad = p.seg_adapter[sc];
+        raw[b].kd = p.seg_kind[sc];
+    }
+#pragma unroll
+    for (int b = 0; b < kCachedBatches; ++b) {
+        const int ad = min(b * kWave + lane_id(), p.n_adapters - 1);
+        const unsigned long long pa = reinterpret_cast<unsigned long long>(p.A_ptrs[ad]);
+        const unsigned long long pb = reinterpret_cast<unsigned long long>(p.B_ptrs[ad]);
+        sg.a[b].a_lo = (unsigned int)pa; sg.a[b].a_hi = (unsigned int)(pa >> 32);
+        sg.a[b].b_lo = (unsigned int)pb; sg.a[b].b_hi = (unsigned int)(pb >> 32);
+        sg.a[b].rank = p.ranks[ad];
+        sg.a[b].scale = p.scales[ad];
+    }
+    sg.n_seg = uniform(min(n_raw, p.max_segments));
+#pragma unroll
+    for (int b = 0; b < kCachedBatches; ++b) {
+        sg.c[b] = raw[b];
+        if (b * kWave + lane_id() >= sg.n_seg) sg.c[b].st = sg.c[b].en = sg.c[b].ad = sg.c[b].kd = 0;
+    }
+    return sg;
+}
+
+// the adapter of a unit: from the registers if it is one of the first 128, else loaded
+template <class P>
+__device__ __forceinline__ SegInfo cached_adapter(const P& p, const Segs<P>& sg, const Unit& u)
+{
+    if (u.ad < 0 || u.ad >= kCachedBatches * kWave) return load_adapter(p, u);
+    const bool hi = u.ad >= kWave;  // wave uniform
+    const int l = u.ad & (kWave - 1);
+    const AdLane& a = hi ? sg.a[1] : sg.a[0];
+    const unsigned long long pa =
+        ((unsigned long long)(unsigned int)lane_value((int)a.a_hi, l) << 32) | (unsigned int)lane_value((int)a.a_lo, l);
+    const unsigned long long pb =
+        ((unsigned long long)(unsigned int)lane_value((int)a.b_hi, l) << 32) | (unsigned int)lane_value((int)a.b_lo, l);
+    SegInfo s;
+    s.A = (gconst_u16)reinterpret_cast<const u16*>(pa);
+    s.B = (gconst_u16)reinterpret_cast<const u16*>(pb);
+    s.rank = lane_value(a.rank, l);
+    s.scale = __int_as_float(lane_value(__float_as_int(a.scale), l));
+    s.ok = u.ad < p.n_adapters && s.rank >= 1 && s.rank <= p.max_rank && pa != 0 && pb != 0;
+    if (!s.ok && threadIdx.x == 0) atomicOr(p.err, kErrBadSegment);
+    return s;
+}
+
+// chunk counts of one length class: prefix sums over the cached segments, totals over all
+struct ClassScan { int nch[kCachedBatches], incl[kCachedBatches]; int tot0, tot_cached, total; };
+
+template <class P>
+__device__ __forceinline__ ClassScan scan_class(const P& p, const Segs<P>& sg, int per, LenClass cls)
+{
+    ClassScan cs;
+#pragma unroll
+    for (int b = 0; b < kCachedBatches; ++b) {
+        cs.nch[b] = chunks_in(sg.c[b].en - sg.c[b].st, sg.c[b].kd, per, cls);
+        cs.incl[b] = wave_inclusive_scan(cs.nch[b]);
+    }
+    cs.tot0 = lane_value(cs.incl[0], kWave - 1);
+    cs.tot_cached = cs.tot0 + lane_value(cs.incl[1], kWave - 1);
+    cs.total = cs.tot_cached;
+    for (int s0 = kCachedBatches * kWave; s0 < sg.n_seg; s0 += kWave) {
+        const SegLane c = load_seg_lane(p, sg.n_seg, s0 + lane_id());
+        cs.total += wave_sum(chunks_in(c.en - c.st, c.kd, per, cls));
+    }
+    return cs;
+}
+
+// the id-th chunk of the class and its adapter; false (and the error bit set) if the segment is unusable
+template <class P>
+__device__ __forceinline__ bool find_unit(const P& p, const Segs<P>& sg, const ClassScan& cs, int id, int per,
+                                          LenClass cls, Unit& u, SegInfo& s)
+{
+    if (id < cs.tot_cached) {
+        const bool hi = id >= cs.tot0;  // wave uniform
+        const int base = hi ? cs.tot0 : 0;
+        const int incl = hi ? cs.incl[1] : cs.incl[0], nch = hi ? cs.nch[1] : cs.nch[0];
+        const SegLane& c = hi ? sg.c[1] : sg.c[0];
+        const unsigned long long m = __ballot(base + incl > id);
+        const int l = uniform(__ffsll((long long)m) - 1);
+        const int local = id - base - lane_value(incl - nch, l);
+        u.seg = (hi ? kWave : 0) + l;
+        u.first = lane_value(c.st, l);
+        u.pos = u.first + local * per;
+        u.seg_len = lane_value(c.en, l) - u.first;
+        u.len = min(per, u.first + u.seg_len - u.pos);
+        u.ad = lane_value(c.ad, l);
+        u.kd = lane_value(c.kd, l);
+        s = cached_adapter(p, sg, u);
+        return s.ok;
+    }
+    // beyond the cached segments: walk the tables
+    int base = cs.tot_cached;
+    for (int s0 = kCachedBatches * kWave; s0 < sg.n_seg; s0 += kWave) {
+        const SegLane c = load_seg_lane(p, sg.n_seg, s0 + lane_id());
+        const int nch = chunks_in(c.en - c.st, c.kd, per, cls);
+        const int incl = wave_inclusive_scan(nch);
+        const int total = lane_value(incl, kWave - 1);
+        if (id < base + total) {
+            const unsigned long long m = __ballot(base + incl > id);
+            const int l = uniform(__ffsll((long long)m) - 1);
+            const int local = id - base - lane_value(incl - nch, l);
+            u.seg = s0 + l;
+            u.first = lane_value(c.st, l);
+            u.pos = u.first + local * per;
+            u.seg_len = lane_value(c.en, l) - u.first;
+            u.len = min(per, u.first + u.seg_len - u.pos);
+            u.ad = lane_value(c.ad, l);
+            u.kd = lane_value(c.kd, l);
+            s = load_adapter(p, u);
+            return s.ok;
+        }
+        base += total;
+    }
+    return false;
 }
 
 // row of the activations for a position of the segment order; -1 if the table holds an invalid row
