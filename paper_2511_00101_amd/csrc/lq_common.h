@@ -32,9 +32,13 @@ __device__ __forceinline__ unsigned int f32_to_bf16_bits(float f)
     if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
+// two fp32 -> packed bf16 with the hardware conversion (round to nearest even)
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    const f32x2 v{lo, hi};
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2));
 }
 
 __device__ __forceinline__ void unpack8(const u32x4& w, float* f)

@@ -393,14 +393,14 @@ __device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit
 // =================================================================================================
 __device__ __forceinline__ void split_bf16(const float (&v)[8], u32x4& hi, u32x4& lo)
 {
-    unsigned int h[8], l[8];
+    unsigned int h[4], l[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        h[i] = f32_to_bf16_bits(v[i]);
-        l[i] = f32_to_bf16_bits(v[i] - __uint_as_float(h[i] << 16));
+    for (int i = 0; i < 4; ++i) {
+        h[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+        l[i] = pack_bf16x2(v[2 * i] - bf16_lo(h[i]), v[2 * i + 1] - bf16_hi(h[i]));
     }
-    hi = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-    lo = u32x4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+    hi = u32x4{h[0], h[1], h[2], h[3]};
+    lo = u32x4{l[0], l[1], l[2], l[3]};
 }
 
 template <int KSTEPS, int PAIRS>
@@ -435,54 +435,82 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
     const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && nb_begin == 0 && p.ksplit > 1;
     float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
-    const int n_tiles = (u.len + 15) / 16;
-    for (int id = (int)threadIdx.x; id < n_tiles * 16 * (C::ROWS / 8); id += kThreads) {
-        const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
-        const float* hp = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * jg;
-        f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
-        for (int part = 1; part < p.ksplit; ++part) {
-            const float* hq = hp + (long long)part * p.n_tokens * p.rstride;
-            h0 += *reinterpret_cast<const f32x4*>(hq);
-            h1 += *reinterpret_cast<const f32x4*>(hq + 4);
-        }
-        float v[8];
+    {
+        // item = (row i, 8 ranks); a thread's items are loaded together, slice after slice
+        constexpr int ITEMS = C::CT * (C::ROWS / 8) / kThreads;
+        static_assert(C::CT * (C::ROWS / 8) % kThreads == 0, "h preparation assumes an even split");
+        const int n_items = (u.len + 15) / 16 * 16 * (C::ROWS / 8);
+        f32x4 h0[ITEMS], h1[ITEMS];
+        const float* hp[ITEMS];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float raw = e < 4 ? h0[e & 3] : h1[e & 3];
-            const bool live = i < u.len && 8 * jg + e < s.rank;
-            if (save && live) h_dst[(long long)i * s.rank + 8 * jg + e] = raw;
-            v[e] = live ? raw * s.scale : 0.f;
+        for (int it = 0; it < ITEMS; ++it) {
+            const int id = (int)threadIdx.x + it * kThreads;
+            const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
+            // (rank groups beyond the adapter's re-read its last one; they are zeroed below)
+            hp[it] = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * min(jg, (s.rank - 1) >> 3);
+            h0[it] = *reinterpret_cast<const f32x4*>(hp[it]);
+            h1[it] = *reinterpret_cast<const f32x4*>(hp[it] + 4);
         }
-        u32x4 hi, lo;
-        split_bf16(v, hi, lo);
-        const int slot = ((i / 16) * KSTEPS + jg / 4) * 2;
-        const int ln = (jg % 4) * 16 + (i % 16);
-        lds_h[(slot + 0) * kWave + ln] = hi;
-        lds_h[(slot + 1) * kWave + ln] = lo;
+        for (int part = 1; part < p.ksplit; ++part) {
+            const long long off = (long long)part * p.n_tokens * p.rstride;
+            f32x4 a0[ITEMS], a1[ITEMS];
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it) {
+                a0[it] = *reinterpret_cast<const f32x4*>(hp[it] + off);
+                a1[it] = *reinterpret_cast<const f32x4*>(hp[it] + off + 4);
+            }
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it) {
+                h0[it] += a0[it];
+                h1[it] += a1[it];
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int id = (int)threadIdx.x + it * kThreads;
+            if (id >= n_items) continue;
+            const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float raw = e < 4 ? h0[it][e & 3] : h1[it][e & 3];
+                const bool live = i < u.len && 8 * jg + e < s.rank;
+                if (save && live) h_dst[(long long)i * s.rank + 8 * jg + e] = raw;
+                v[e] = live ? raw * s.scale : 0.f;
+            }
+            u32x4 hi, lo;
+            split_bf16(v, hi, lo);
+            const int slot = ((i / 16) * KSTEPS + jg / 4) * 2;
+            const int ln = (jg % 4) * 16 + (i % 16);
+            lds_h[(slot + 0) * kWave + ln] = hi;
+            lds_h[(slot + 1) * kWave + ln] = lo;
+        }
     }
-
     LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 3));
+    // 2. per column block, the block of B: coalesced loads -> registers -> LDS -> transposed MFMA fragments
+    // in registers.  The loads of the next block are in flight while this block's y streams by.
+    u32x4 bstage[STAGE];
+    auto b_load = [&](int n_block) {
+#pragma unroll
+        for (int i = 0; i < STAGE; ++i) {
+            const int id = (int)threadIdx.x + i * kThreads;
+            const int j = id / (C::UN / 8), n = n_block * C::UN + (id % (C::UN / 8)) * 8;
+            bstage[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
+        }
+    };
+    b_load(nb_begin);
     for (int n_block = nb_begin; n_block < nb_end; ++n_block) {
     const int n_unit = n_block * C::UN;
-    // 2. the block of B: coalesced loads -> LDS -> transposed MFMA fragments in registers
-    {
-        u32x4 v[STAGE];
+    __syncthreads();  // the previous block's fragment reads are done
 #pragma unroll
-        for (int i = 0; i < STAGE; ++i) {
-            const int id = (int)threadIdx.x + i * kThreads;
-            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
-            v[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
-        }
-        __syncthreads();  // the previous block's fragment reads are done
-#pragma unroll
-        for (int i = 0; i < STAGE; ++i) {
-            const int id = (int)threadIdx.x + i * kThreads;
-            const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
-            const bool live = j < s.rank && n < p.d_out;
-            *reinterpret_cast<u32x4*>(lds_b + j * C::BPITCH + (n - n_unit)) = live ? v[i] : u32x4{0u, 0u, 0u, 0u};
-        }
+    for (int i = 0; i < STAGE; ++i) {
+        const int id = (int)threadIdx.x + i * kThreads;
+        const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
+        const bool live = j < s.rank && n < p.d_out;
+        *reinterpret_cast<u32x4*>(lds_b + j * C::BPITCH + (n - n_unit)) = live ? bstage[i] : u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
+    b_load(min(n_block + 1, nb_end - 1));  // unconditional: the last block is simply loaded again
     const int n_wave = n_unit + w * C::WN;
     u32x4 bfrag[PAIRS][2][KSTEPS];
 #pragma unroll
@@ -691,9 +719,11 @@ template <int NT>
 __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdParams>& sg, unsigned char* lds_raw,
                                              int* s_slot)
 {
-    const LenClass tall{kTallMin, kBig, p.kinds}, small{1, kTallMin, p.kinds};
-    const ClassScan ct = scan_class(p, sg, kTallRows, tall), cm = scan_class(p, sg, kShortRows, small);
-    const int n_tall = ct.total << p.ks_log2, n_small = cm.total << p.ks_log2;
+    // hand-out order: full tall chunks, the tall segments' leftovers, then the short segments' chunks
+    const LenClass tall{kTallMin, kBig, p.kinds, 1}, rest{kTallMin, kBig, p.kinds, 2, 1, kTallRows}, small{1, kTallMin, p.kinds};
+    const ClassScan ct = scan_class(p, sg, kTallRows, tall), cr = scan_class(p, sg, kTallRows, rest),
+                    cm = scan_class(p, sg, kShortRows, small);
+    const int n_full = ct.total << p.ks_log2, n_tall = n_full + (cr.total << p.ks_log2), n_small = cm.total << p.ks_log2;
     LQ_STAMP(0, 2);
     for_each_unit(p.tickets + 0, n_tall + n_small, s_slot, [&](int id, int it) {
         Unit u;
@@ -701,10 +731,11 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdP
         u.it = it;
         LQ_STAMP(0, LQ_UNIT_SLOT(it, 0));
         const bool is_tall = id < n_tall;
-        const int cid = is_tall ? id : id - n_tall;
+        const int cid = id < n_full ? id : is_tall ? id - n_full : id - n_tall;
         const int chunk = cid >> p.ks_log2, ks = cid & (p.ksplit - 1);
-        const bool ok = is_tall ? find_unit(p, sg, ct, chunk, kTallRows, tall, u, s)
-                                : find_unit(p, sg, cm, chunk, kShortRows, small, u, s);
+        const bool ok = id < n_full ? find_unit(p, sg, ct, chunk, kTallRows, tall, u, s)
+                        : is_tall   ? find_unit(p, sg, cr, chunk, kTallRows, rest, u, s)
+                                    : find_unit(p, sg, cm, chunk, kShortRows, small, u, s);
         if (!ok) return;
         LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(it, 2));
         // the unit runs with as many 16-rank tiles as its adapter needs (at most NT, the launch's maximum)
@@ -741,46 +772,59 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
                                              ShortLds& sh, int* s_slot)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
-    const LenClass longs{kLongMin, kBig, p.kinds}, shorts{1, kLongMin, p.kinds};
-    const ClassScan cl = scan_class(p, sg, C::CT, longs), cs = scan_class(p, sg, kTT, shorts);
+    const LenClass shorts{1, kLongMin, p.kinds};
+    const LenClass full{kLongMin, kBig, p.kinds, 1}, big{kLongMin, kBig, p.kinds, 2, C::CT / 2, C::CT},
+        little{kLongMin, kBig, p.kinds, 2, 1, C::CT / 2};
 
-    // long units, one per workgroup iteration: a chunk of rows x a group of column blocks.  Groups are as
-    // large as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
-    const int n_chunks = cl.total;
+    // short units first (their cost is mostly latency, which the start of a launch has to spare): one
+    // per wave iteration, dealt round-robin over the workgroups first so that a few hundred units spread
+    // over all compute units
+    {
+        const ClassScan cs = scan_class(p, sg, kTT, shorts);
+        const int short_blocks = (p.d_out + kShortN - 1) / kShortN;
+        const int n_short = cs.total * short_blocks;
+        const int w = uniform((int)threadIdx.x / kWave);
+        for (int id = w * (int)gridDim.x + (int)blockIdx.x; id < n_short; id += kWaves * (int)gridDim.x) {
+            Unit u;
+            SegInfo s;
+            u.it = 4;
+            const int chunk = small_div(id, short_blocks);
+            if (!find_unit(p, sg, cs, chunk, kTT, shorts, u, s)) continue;
+            expand_short_unit(p, u, s, id - chunk * short_blocks, sh);
+        }
+    }
+    LQ_STAMP_WAIT(1, 39);
+
+    // long units, one per workgroup iteration: a chunk of rows x a group of column blocks, the full chunks
+    // first, the leftovers of more than half a chunk next, the small leftovers last.  Groups are as large
+    // as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
+    const ClassScan cf = scan_class(p, sg, C::CT, full), cb = scan_class(p, sg, C::CT, big),
+                    cl = scan_class(p, sg, C::CT, little);
+    const int n_chunks = cf.total + cb.total + cl.total;
     if (n_chunks > 0) {
         const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
         const int groups_wanted = small_div(4 * (int)gridDim.x + n_chunks - 1, n_chunks);
         const int per_group = max(1, small_div(long_blocks, max(1, min(long_blocks, groups_wanted))));
         const int groups = small_div(long_blocks + per_group - 1, per_group);
+        const int n_full = cf.total * groups, n_big = n_full + cb.total * groups;
         LQ_STAMP(1, 2);
         for_each_unit(p.tickets + 2, n_chunks * groups, s_slot, [&](int id, int it) {
             Unit u;
             SegInfo s;
             u.it = it;
             LQ_STAMP(1, LQ_UNIT_SLOT(it, 0));
-            const int chunk = small_div(id, groups);
-            if (!find_unit(p, sg, cl, chunk, C::CT, longs, u, s)) return;
+            const int cid = id < n_full ? id : id < n_big ? id - n_full : id - n_big;
+            const int chunk = small_div(cid, groups);
+            const bool ok = id < n_full ? find_unit(p, sg, cf, chunk, C::CT, full, u, s)
+                            : id < n_big ? find_unit(p, sg, cb, chunk, C::CT, big, u, s)
+                                         : find_unit(p, sg, cl, chunk, C::CT, little, u, s);
+            if (!ok) return;
             LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(it, 2));
-            const int nb = (id - chunk * groups) * per_group;
+            const int nb = (cid - chunk * groups) * per_group;
             expand_long_unit<KSTEPS, PAIRS>(p, u, s, nb, min(long_blocks, nb + per_group), lds_raw);
         });
     }
     LQ_STAMP_WAIT(1, 3);
-
-    // short units, one per wave iteration, dealt round-robin over the workgroups first so that a few
-    // hundred units spread over all compute units
-    const int short_blocks = (p.d_out + kShortN - 1) / kShortN;
-    const int n_short = cs.total * short_blocks;
-    const int w = uniform((int)threadIdx.x / kWave);
-    for (int id = w * (int)gridDim.x + (int)blockIdx.x; id < n_short; id += kWaves * (int)gridDim.x) {
-        Unit u;
-        SegInfo s;
-        u.it = 4;
-        const int chunk = small_div(id, short_blocks);
-        if (!find_unit(p, sg, cs, chunk, kTT, shorts, u, s)) continue;
-        expand_short_unit(p, u, s, id - chunk * short_blocks, sh);
-    }
-    LQ_STAMP_WAIT(1, 39);
 }
 
 template <int KSTEPS, int PAIRS>
@@ -842,9 +886,13 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     __shared__ int s_slot[2];
     // the generation is read before this workgroup arrives, hence before the last arrival can change it
     const int gen0 = __hip_atomic_load(p.tickets + 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    LQ_STAMP(0, 0);
     const Segs<FwdParams> sg = load_segs(p);
+    LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
+    LQ_STAMP(1, 0);
     grid_barrier(p, gen0);
+    LQ_STAMP(1, 1);
     expand_phase<KSTEPS, PAIRS>(p, sg, lds_raw, sh, s_slot);
 }
 

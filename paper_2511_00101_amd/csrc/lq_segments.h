@@ -53,11 +53,30 @@ __device__ __forceinline__ SegLane seg_batch(const P& p, int n_seg, const SegCac
 
 struct Unit { int seg, pos, len, first, seg_len, ad, kd, it; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len); it: loop count (tracing)
 
-struct LenClass { int lo, hi, kinds; };  // segments with lo <= rows < hi whose kind's bit is set in `kinds`
+// A class of chunks: those of the segments with lo <= rows < hi whose kind's bit is set in `kinds`;
+// part 0: all chunks of `per` rows (the last one may be shorter), part 1: only the full ones, part 2: only
+// the shorter last one, and only if it has tlo <= rows < thi.  Handing out the full chunks first and the
+// short leftovers last keeps the end of a launch balanced.
+struct LenClass { int lo, hi, kinds; int part = 0, tlo = 0, thi = 0; };
 
 __device__ __forceinline__ int chunks_in(int len, int kind, int per, LenClass cls)
 {
-    return (len >= cls.lo && len < cls.hi && len > 0 && ((cls.kinds >> kind) & 1)) ? (len + per - 1) / per : 0;
+    if (!(len >= cls.lo && len < cls.hi && len > 0 && ((cls.kinds >> kind) & 1))) return 0;
+    if (cls.part == 0) return (len + per - 1) / per;
+    if (cls.part == 1) return len / per;
+    const int rest = len % per;
+    return (rest > 0 && rest >= cls.tlo && rest < cls.thi) ? 1 : 0;
+}
+// position (relative to the segment's first row) and rows of the local-th chunk of a segment in a class
+__device__ __forceinline__ void chunk_rows(int seg_len, int local, int per, LenClass cls, int& rel, int& rows)
+{
+    if (cls.part == 2) {
+        rel = seg_len / per * per;
+        rows = seg_len - rel;
+    } else {
+        rel = local * per;
+        rows = min(per, seg_len - rel);
+    }
 }
 
 __device__ __forceinline__ int wave_sum(int v) { return lane_value(wave_inclusive_scan(v), kWave - 1); }
@@ -240,9 +259,10 @@ __device__ __forceinline__ bool find_unit(const P& p, const Segs<P>& sg, const C
         const int local = id - base - lane_value(incl - nch, l);
         u.seg = (hi ? kWave : 0) + l;
         u.first = lane_value(c.st, l);
-        u.pos = u.first + local * per;
         u.seg_len = lane_value(c.en, l) - u.first;
-        u.len = min(per, u.first + u.seg_len - u.pos);
+        int rel;
+        chunk_rows(u.seg_len, local, per, cls, rel, u.len);
+        u.pos = u.first + rel;
         u.ad = lane_value(c.ad, l);
         u.kd = lane_value(c.kd, l);
         s = cached_adapter(p, sg, u);
@@ -261,9 +281,10 @@ __device__ __forceinline__ bool find_unit(const P& p, const Segs<P>& sg, const C
             const int local = id - base - lane_value(incl - nch, l);
             u.seg = s0 + l;
             u.first = lane_value(c.st, l);
-            u.pos = u.first + local * per;
             u.seg_len = lane_value(c.en, l) - u.first;
-            u.len = min(per, u.first + u.seg_len - u.pos);
+            int rel;
+            chunk_rows(u.seg_len, local, per, cls, rel, u.len);
+            u.pos = u.first + rel;
             u.ad = lane_value(c.ad, l);
             u.kd = lane_value(c.kd, l);
             s = load_adapter(p, u);
