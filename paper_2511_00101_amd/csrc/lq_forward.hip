@@ -430,6 +430,20 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     int* lds_row = reinterpret_cast<int*>(lds + C::B_BYTES + C::H_BYTES);
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, g = lane >> 4;
 
+    // The block of B of every column block: coalesced loads -> registers -> LDS -> transposed MFMA fragments
+    // in registers.  The first block's loads go out before anything else; those of the next block are in
+    // flight while a block's y streams by.
+    u32x4 bstage[STAGE];
+    auto b_load = [&](int n_block) {
+#pragma unroll
+        for (int i = 0; i < STAGE; ++i) {
+            const int id = (int)threadIdx.x + i * kThreads;
+            const int j = id / (C::UN / 8), n = n_block * C::UN + (id % (C::UN / 8)) * 8;
+            bstage[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
+        }
+    };
+    b_load(nb_begin);
+
     // 1. the unit's rows and their h: slices added, (fine-tune segments, first column block: stored to
     // h_out,) scaled, split into bf16 high/low, stored as ready-made fragments
     for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
@@ -487,18 +501,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         }
     }
     LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 3));
-    // 2. per column block, the block of B: coalesced loads -> registers -> LDS -> transposed MFMA fragments
-    // in registers.  The loads of the next block are in flight while this block's y streams by.
-    u32x4 bstage[STAGE];
-    auto b_load = [&](int n_block) {
-#pragma unroll
-        for (int i = 0; i < STAGE; ++i) {
-            const int id = (int)threadIdx.x + i * kThreads;
-            const int j = id / (C::UN / 8), n = n_block * C::UN + (id % (C::UN / 8)) * 8;
-            bstage[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
-        }
-    };
-    b_load(nb_begin);
+    // 2. per column block: stage B, then stream y
     for (int n_block = nb_begin; n_block < nb_end; ++n_block) {
     const int n_unit = n_block * C::UN;
     __syncthreads();  // the previous block's fragment reads are done
@@ -779,12 +782,19 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
     // short units first (their cost is mostly latency, which the start of a launch has to spare): one
     // per wave iteration, dealt round-robin over the workgroups first so that a few hundred units spread
     // over all compute units
+    const ClassScan cf = scan_class(p, sg, C::CT, full), cb = scan_class(p, sg, C::CT, big),
+                    cl = scan_class(p, sg, C::CT, little);
+    const int n_chunks = cf.total + cb.total + cl.total;
     {
         const ClassScan cs = scan_class(p, sg, kTT, shorts);
         const int short_blocks = (p.d_out + kShortN - 1) / kShortN;
         const int n_short = cs.total * short_blocks;
         const int w = uniform((int)threadIdx.x / kWave);
-        for (int id = w * (int)gridDim.x + (int)blockIdx.x; id < n_short; id += kWaves * (int)gridDim.x) {
+        // without long units the short ones are dealt over the workgroups first (all compute units pull
+        // data); with long units they are packed eight to a workgroup, so that the other workgroups
+        // start streaming at once
+        const int first = n_chunks > 0 ? (int)blockIdx.x * kWaves + w : w * (int)gridDim.x + (int)blockIdx.x;
+        for (int id = first; id < n_short; id += kWaves * (int)gridDim.x) {
             Unit u;
             SegInfo s;
             u.it = 4;
@@ -798,9 +808,6 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
     // long units, one per workgroup iteration: a chunk of rows x a group of column blocks, the full chunks
     // first, the leftovers of more than half a chunk next, the small leftovers last.  Groups are as large
     // as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
-    const ClassScan cf = scan_class(p, sg, C::CT, full), cb = scan_class(p, sg, C::CT, big),
-                    cl = scan_class(p, sg, C::CT, little);
-    const int n_chunks = cf.total + cb.total + cl.total;
     if (n_chunks > 0) {
         const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
         const int groups_wanted = small_div(4 * (int)gridDim.x + n_chunks - 1, n_chunks);
