@@ -6,21 +6,27 @@
 // the forward's expand with (y, B, d_out) := (dx, A, d_in); both reuse those kernels, restricted to
 // fine-tune segments.  The two weight gradients are contractions over the TOKEN axis, which is the
 // strided axis of every operand, so they get a kernel of their own:
-//   weight-gradient unit : 512 rows of a fine-tune segment x 512 columns of dy (for dB, with h) or of x
+//   weight-gradient unit : 512 rows of a fine-tune segment x 256 columns of dy (for dB, with h) or of x
 //                          (for dA, with g).  32 rows at a time are staged in LDS with coalesced loads
-//                          (double buffered) and read back transposed into 16x16x32 bf16 MFMA
-//                          fragments; h and g are split into bf16 high and low parts.  The unit stores
-//                          its [rank x 512] partial to the workspace.
-//   reduce unit          : one segment x 512 columns: adds the segment's partials in chunk order, applies
-//                          the scale and accumulates into dA / dB.  Fixed order, so reproducible.
+//                          (four steps in flight in registers, two LDS buffers) and read back
+//                          transposed into 16x16x32 bf16 MFMA fragments; h and g are split into bf16
+//                          high and low parts.  The unit stores its [rank x 256] partial to the
+//                          workspace.
+//   reduce unit          : one segment x 512 columns x 8 ranks: adds the segment's partials in chunk
+//                          order, applies the scale and accumulates into dA / dB.  Fixed order, so
+//                          reproducible.
 #include "lq_internal.h"
+#include <type_traits>
+#include <utility>
 
 namespace lq {
 namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWgRows = 512;    // token rows per weight-gradient unit
-constexpr int kWgCols = 512;    // columns per unit (8 waves x 64)
+constexpr int kWgCols = 256;    // columns per unit (8 waves x 32)
+constexpr int kWgTiles = kWgCols / (8 * 16);  // 16-column MFMA tiles per wave
+
 constexpr int kStepRows = 32;   // token rows per MFMA k step
 constexpr int kBig = 0x7fffffff;
 
@@ -35,8 +41,8 @@ struct BwdParams {
     const int32_t* seg_starts; const int32_t* seg_adapter; const uint8_t* seg_kind;
     const int32_t* n_segments; int max_segments;
     const float* h_saved; const long long* h_offsets;
-    const float* g;      // [ksplit][n_tokens][rstride] slices of g = dy B^T by position in segment order
-    int ksplit; int rstride;
+    const float* g;      // g = dy B^T of the fine-tune rows, laid out like h_saved
+    int rstride;
     float* wpart;        // [chunk][rstride][d_out + d_in] partial weight gradients
     int* err;
 };
@@ -51,16 +57,24 @@ struct WgCfg {
     static constexpr size_t LDS_BYTES = 2 * BUF_BYTES + kWgRows * sizeof(int);
 };
 
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ...: a loop over register slots that have to be
+// indexed with constants
+template <int... Js, class F>
+__device__ __forceinline__ void for_each_slot(std::integer_sequence<int, Js...>, F&& f)
+{
+    (f(std::integral_constant<int, Js>{}), ...);
+}
+
 __device__ __forceinline__ void split_hi_lo(const float (&v)[8], u32x4& hi, u32x4& lo)
 {
-    unsigned int h[8], l[8];
+    unsigned int h[4], l[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        h[i] = f32_to_bf16_bits(v[i]);
-        l[i] = f32_to_bf16_bits(v[i] - __uint_as_float(h[i] << 16));
+    for (int i = 0; i < 4; ++i) {
+        h[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+        l[i] = pack_bf16x2(v[2 * i] - bf16_lo(h[i]), v[2 * i + 1] - bf16_hi(h[i]));
     }
-    hi = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-    lo = u32x4{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+    hi = u32x4{h[0], h[1], h[2], h[3]};
+    lo = u32x4{l[0], l[1], l[2], l[3]};
 }
 
 // D[rank][col] = sum_t H[t][rank] Y[t][col] over the unit's rows; H = h_saved (for dB, Y = dy) or g (for
@@ -71,6 +85,7 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
                                            int col_block, unsigned char* lds)
 {
     using C = WgCfg<NT>;
+    constexpr int YQ = kWgCols / 128;  // 16-byte pieces of a staged activation row per thread
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, kg = lane >> 4;
     const u16* Y = for_b ? p.dy : p.x;
     const long long ldy = for_b ? p.lddy : p.ldx;
@@ -83,64 +98,53 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
     __syncthreads();
     const int safe_row = max(lds_row[0], 0);
 
-    // staging assignment.  Y: 16 threads cover 128 columns of one row per pass, 4 passes cover 512 columns.
+    // staging assignment: 16 threads cover 128 columns (256 bytes) of one row per pass
     const int y_row = (int)threadIdx.x / 16, y_piece = (int)threadIdx.x % 16;
-    const long long h_base = for_b ? p.h_offsets[u.seg] + (long long)(u.pos - u.first) * rank : 0;
-    u32x4 gy[4];
-    float gh[NT];
-    auto stage_load = [&](int step) {
+    // the unit's rows of h_saved (for dB) or of g (for dA); both are [row][rank] per segment
+    const float* hsrc = (for_b ? p.h_saved : p.g) + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * rank;
+    constexpr int DEPTH = NT <= 2 ? 4 : NT <= 4 ? 2 : 1;  // steps in flight (as many as the registers allow)
+    u32x4 gy[DEPTH][YQ];
+    float gh[DEPTH][NT];
+    // all loads are unconditional (clamped addresses), so the number in flight is static; what lies
+    // outside the unit is zeroed when it is stored to LDS
+    auto stage_load = [&](int step, u32x4 (&y)[YQ], float (&h)[NT]) {
         const int i = step * kStepRows + y_row;
         const int row = lds_row[min(i, kWgRows - 1)];
         const u16* yrow = Y + (long long)(row >= 0 ? row : safe_row) * ldy;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int n = n0 + (y_piece + 16 * q) * 8;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(yrow + min(n, d - 8));
-            gy[q] = (n < d && row >= 0) ? v : u32x4{0u, 0u, 0u, 0u};
-        }
+        for (int q = 0; q < YQ; ++q) y[q] = *reinterpret_cast<const u32x4*>(yrow + min(n0 + (y_piece + 16 * q) * 8, d - 8));
+        const float* hrow = hsrc + (long long)min(i, u.len - 1) * rank;
 #pragma unroll
-        for (int q = 0; q < NT; ++q) {
-            const int j = y_piece + 16 * q;
-            float v = 0.f;
-            if (i < u.len && j < rank) {
-                if (for_b) {
-                    v = p.h_saved[h_base + (long long)i * rank + j];
-                } else {
-                    for (int part = 0; part < p.ksplit; ++part)
-                        v += p.g[((long long)part * p.n_tokens + u.pos + i) * p.rstride + j];
-                }
-            }
-            gh[q] = v;
-        }
+        for (int q = 0; q < NT; ++q) h[q] = hrow[min(y_piece + 16 * q, rank - 1)];
     };
-    auto stage_store = [&](int buf) {
+    auto stage_store = [&](int step, int buf, const u32x4 (&y)[YQ], const float (&h)[NT]) {
         u16* ly = reinterpret_cast<u16*>(lds + buf * C::BUF_BYTES);
         float* lh = reinterpret_cast<float*>(lds + buf * C::BUF_BYTES + C::Y_BYTES);
+        const int i = step * kStepRows + y_row;
+        const bool row_live = i < u.len && lds_row[min(i, kWgRows - 1)] >= 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4*>(ly + y_row * C::YPITCH + (y_piece + 16 * q) * 8) = gy[q];
+        for (int q = 0; q < YQ; ++q) {
+            const bool live = row_live && n0 + (y_piece + 16 * q) * 8 < d;
+            *reinterpret_cast<u32x4*>(ly + y_row * C::YPITCH + (y_piece + 16 * q) * 8) = live ? y[q] : u32x4{0u, 0u, 0u, 0u};
+        }
 #pragma unroll
-        for (int q = 0; q < NT; ++q) lh[y_row * C::HPITCH + y_piece + 16 * q] = gh[q];
+        for (int q = 0; q < NT; ++q)
+            lh[y_row * C::HPITCH + y_piece + 16 * q] = (i < u.len && y_piece + 16 * q < rank) ? h[q] : 0.f;
     };
 
-    f32x4 acc[NT][4];
+    f32x4 acc[NT][kWgTiles];
 #pragma unroll
     for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) acc[jt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int nt = 0; nt < kWgTiles; ++nt) acc[jt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int n_steps = (u.len + kStepRows - 1) / kStepRows;
-    stage_load(0);
-    for (int step = 0; step < n_steps; ++step) {
-        const int buf = step & 1;
-        stage_store(buf);
-        stage_load(min(step + 1, n_steps - 1));  // unconditional; the last one re-reads
-        __syncthreads();  // one barrier per step: the buffer written now was last read two steps ago
+    auto compute = [&](int buf) {
         const u16* ly = reinterpret_cast<const u16*>(lds + buf * C::BUF_BYTES);
         const float* lh = reinterpret_cast<const float*>(lds + buf * C::BUF_BYTES + C::Y_BYTES);
-        u32x4 yf[4];
+        u32x4 yf[kWgTiles];
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const u16* col = ly + w * 64 + nt * 16 + c;
+        for (int nt = 0; nt < kWgTiles; ++nt) {
+            const u16* col = ly + w * (16 * kWgTiles) + nt * 16 + c;
             unsigned int e[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) e[i] = col[(8 * kg + i) * C::YPITCH];
@@ -154,22 +158,42 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
             u32x4 hi, lo;
             split_hi_lo(v, hi, lo);
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
+            for (int nt = 0; nt < kWgTiles; ++nt) {
                 acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(lo), as_bf16x8(yf[nt]), acc[jt][nt], 0, 0, 0);
                 acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(hi), as_bf16x8(yf[nt]), acc[jt][nt], 0, 0, 0);
             }
         }
-    }
+    };
+
+    // Pipeline: the loads of the next DEPTH steps are in flight in registers; a step is stored to one of
+    // two LDS buffers (one barrier per step: the buffer written now was last read two steps ago), its
+    // register slot is refilled with the step DEPTH ahead, and the step is multiplied out of LDS.
+    const int n_steps = (u.len + kStepRows - 1) / kStepRows;
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) stage_load(min(dd, n_steps - 1), gy[dd], gh[dd]);
+    auto step_fn = [&](int step, auto slot) {
+        constexpr int J = decltype(slot)::value;
+        stage_store(step, step & 1, gy[J], gh[J]);
+        stage_load(min(step + DEPTH, n_steps - 1), gy[J], gh[J]);  // unconditional; past the end it re-reads
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        compute(step & 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int step = 0; step < n_steps; step += DEPTH)
+        for_each_slot(std::make_integer_sequence<int, DEPTH>{}, [&](auto slot) {
+            if (step + decltype(slot)::value < n_steps) step_fn(step + decltype(slot)::value, slot);
+        });
 
     const int dsum = p.d_out + p.d_in;
     float* out = p.wpart + (long long)chunk_id * p.rstride * dsum + (for_b ? 0 : p.d_out);
 #pragma unroll
     for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int nt = 0; nt < kWgTiles; ++nt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int j = jt * 16 + 4 * kg + v, n = n0 + w * 64 + nt * 16 + c;
+                const int j = jt * 16 + 4 * kg + v, n = n0 + w * (16 * kWgTiles) + nt * 16 + c;
                 if (j < rank && n < d) out[(long long)j * dsum + n] = acc[jt][nt][v];
             }
 }
@@ -186,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(BwdParams p)
     const int n_units = count_chunks(p, n_seg, c0, kWgRows, ft) * per_chunk;
     for (int id = (int)blockIdx.x; id < n_units; id += (int)gridDim.x) {
         Unit u;
-        const int chunk_id = id / per_chunk, cb = id % per_chunk;
+        const int chunk_id = small_div(id, per_chunk), cb = id - chunk_id * per_chunk;
         if (!find_chunk(p, n_seg, c0, chunk_id, kWgRows, ft, u)) continue;
         if (u.ad < 0 || u.ad >= p.n_adapters) continue;  // flagged by the forward kernels already
         const int rank = p.ranks[u.ad];
@@ -198,7 +222,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(BwdParams p)
     }
 }
 
-// dA / dB += scale * (sum of the segment's chunk partials, in chunk order)
+// dA / dB += scale * (sum of the segment's chunk partials, in chunk order).  One unit = the first chunk of
+// a segment x 512 columns of [dB | dA] x 8 ranks; a thread owns one column and keeps the 8 sums in
+// registers, so the loads of a chunk's partials are independent of each other.
+constexpr int kRedRanks = 8;
 __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
 {
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
@@ -206,10 +233,12 @@ __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
     const LenClass ft{1, kBig, 1 << LQ_SEG_FINETUNE};
     const int dsum = p.d_out + p.d_in;
     const int col_blocks = (dsum + kThreads - 1) / kThreads;
-    const int n_units = count_chunks(p, n_seg, c0, kWgRows, ft) * col_blocks;
+    const int rank_groups = (p.max_rank + kRedRanks - 1) / kRedRanks;
+    const int per_chunk = col_blocks * rank_groups;
+    const int n_units = count_chunks(p, n_seg, c0, kWgRows, ft) * per_chunk;
     for (int id = (int)blockIdx.x; id < n_units; id += (int)gridDim.x) {
         Unit u;
-        const int chunk_id = id / col_blocks;
+        const int chunk_id = small_div(id, per_chunk), sub = id - chunk_id * per_chunk;
         if (!find_chunk(p, n_seg, c0, chunk_id, kWgRows, ft, u)) continue;
         if (u.pos != u.first) continue;  // only the segment's first chunk adds up the segment
         if (u.ad < 0 || u.ad >= p.n_adapters) continue;
@@ -217,20 +246,36 @@ __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
         if (rank < 1 || rank > p.max_rank) continue;
         const float scale = p.scales[u.ad];
         const int n_chunks = (u.seg_len + kWgRows - 1) / kWgRows;
-        const int col = (id % col_blocks) * kThreads + (int)threadIdx.x;
-        if (col >= dsum) continue;
+        const int j0 = (sub / col_blocks) * kRedRanks;
+        const int col = (sub % col_blocks) * kThreads + (int)threadIdx.x;
+        if (col >= dsum || j0 >= rank) continue;
         const bool for_b = col < p.d_out;
-        float* dst = for_b ? (p.dB_ptrs ? p.dB_ptrs[u.ad] : nullptr) : (p.dA_ptrs ? p.dA_ptrs[u.ad] : nullptr);
+        float* __restrict__ dst = for_b ? (p.dB_ptrs ? p.dB_ptrs[u.ad] : nullptr) : (p.dA_ptrs ? p.dA_ptrs[u.ad] : nullptr);
         if (!dst) continue;
         const int d = for_b ? p.d_out : p.d_in, n = for_b ? col : col - p.d_out;
-        for (int j = 0; j < rank; ++j) {
-            float sum = 0.f;
-            for (int cc = 0; cc < n_chunks; ++cc)
-                sum += p.wpart[((long long)(chunk_id + cc) * p.rstride + j) * dsum + col];
-            dst[(long long)j * d + n] += scale * sum;
+        const float* __restrict__ part = p.wpart + ((long long)chunk_id * p.rstride + j0) * dsum + col;
+        float sum[kRedRanks], old[kRedRanks];
+#pragma unroll
+        for (int jj = 0; jj < kRedRanks; ++jj) {
+            sum[jj] = 0.f;
+            old[jj] = dst[(long long)min(j0 + jj, rank - 1) * d + n];
         }
+        for (int cc = 0; cc < n_chunks; ++cc) {
+            float v[kRedRanks];
+#pragma unroll
+            for (int jj = 0; jj < kRedRanks; ++jj)  // rows beyond the rank lie inside the rstride rows of the partial
+                v[jj] = part[((long long)cc * p.rstride + jj) * dsum];
+#pragma unroll
+            for (int jj = 0; jj < kRedRanks; ++jj) sum[jj] += v[jj];
+        }
+#pragma unroll
+        for (int jj = 0; jj < kRedRanks; ++jj)
+            if (j0 + jj < rank) dst[(long long)(j0 + jj) * d + n] = old[jj] + scale * sum[jj];
     }
 }
+
+// finished g of the fine-tune rows: at most n_tokens x max_rank floats (a multiple of 16 bytes)
+size_t gsum_bytes(int n_tokens, int max_rank) { return ((size_t)n_tokens * (size_t)max_rank * sizeof(float) + 15) / 16 * 16; }
 
 size_t wpart_bytes(int n_tokens, int n_adapters, int max_rank, int d_in, int d_out)
 {
@@ -261,12 +306,12 @@ hipError_t launch_wgrad(const BwdParams& p, hipStream_t st)
 }  // namespace
 }  // namespace lq
 
-// workspace: [header 256 B][g slices: like the forward's partial h][partial weight gradients]
+// workspace: [header 256 B][g slices: like the forward's partial h][finished g][partial weight gradients]
 extern "C" size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in,
                                                 int32_t d_out)
 {
     if (n_tokens < 0 || n_adapters < 0 || max_rank < 1 || d_in < 0 || d_out < 0) return lq::kWsHeaderBytes;
-    return (size_t)lq::kWsHeaderBytes + lq::h_slices_bytes(n_tokens, max_rank) +
+    return (size_t)lq::kWsHeaderBytes + lq::h_slices_bytes(n_tokens, max_rank) + lq::gsum_bytes(n_tokens, max_rank) +
            lq::wpart_bytes(n_tokens, n_adapters, max_rank, d_in, d_out);
 }
 
@@ -314,14 +359,22 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     s1.perm = perm; s1.n_tokens = n_tokens;
     s1.seg_starts = seg_starts; s1.seg_adapter = seg_adapter; s1.seg_kind = seg_kind;
     s1.n_segments = n_segments; s1.max_segments = max_segments;
-    s1.h_out = nullptr; s1.h_offsets = nullptr;
+    // the finished g goes where the forward would save h: [segment offset + row x rank + j], for the weight gradients
+    float* gsum = reinterpret_cast<float*>(ws + kWsHeaderBytes + h_slices_bytes(n_tokens, max_rank));
+    const bool want_w = dA_ptrs || dB_ptrs;
+    s1.h_out = want_w ? gsum : nullptr; s1.h_offsets = want_w ? reinterpret_cast<const long long*>(h_offsets) : nullptr;
     s1.hpart = reinterpret_cast<float*>(ws + kWsHeaderBytes);
     s1.ksplit = 1; s1.rstride = rstride_for(max_rank);
     s1.err = reinterpret_cast<int*>(ws); s1.tickets = reinterpret_cast<int*>(ws) + 4;
     s1.ksplit_hint = 0; s1.kinds = kFinetuneOnly;
     if (run_shrink_expand(s1, LQ_VARIANT_SHRINK_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
 
-    // 2. partial weight gradients, then their reduction into dA / dB
+    // 2. dx += s g A on fine-tune rows: the forward's expand over d_in against A, with the same k split.  Whichever
+    // of the two kernels finishes g (the shrink without a split, the expand with one) also stores it to gsum.
+    s1.ksplit_hint = s1.ksplit;
+    if (run_shrink_expand(s1, LQ_VARIANT_EXPAND_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+
+    // 3. partial weight gradients (from x, dy, the saved h and the finished g), then their reduction into dA / dB
     if (dA_ptrs || dB_ptrs) {
         BwdParams b;
         b.x = static_cast<const u16*>(x); b.ldx = ldx;
@@ -333,8 +386,8 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
         b.seg_starts = seg_starts; b.seg_adapter = seg_adapter; b.seg_kind = seg_kind;
         b.n_segments = n_segments; b.max_segments = max_segments;
         b.h_saved = h_saved; b.h_offsets = reinterpret_cast<const long long*>(h_offsets);
-        b.g = s1.hpart; b.ksplit = s1.ksplit; b.rstride = s1.rstride;
-        b.wpart = reinterpret_cast<float*>(ws + kWsHeaderBytes + h_slices_bytes(n_tokens, max_rank));
+        b.g = gsum; b.rstride = s1.rstride;
+        b.wpart = reinterpret_cast<float*>(ws + kWsHeaderBytes + h_slices_bytes(n_tokens, max_rank) + gsum_bytes(n_tokens, max_rank));
         b.err = reinterpret_cast<int*>(ws);
         const hipError_t e = max_rank <= 16 ? launch_wgrad<1>(b, st) : max_rank <= 32 ? launch_wgrad<2>(b, st)
                            : max_rank <= 64 ? launch_wgrad<4>(b, st) : launch_wgrad<8>(b, st);
@@ -342,8 +395,5 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
         hipLaunchKernelGGL(wreduce_kernel, dim3(512), dim3(kThreads), 0, st, b);
         if (hipGetLastError() != hipSuccess) return LQ_ERR_HIP;
     }
-
-    // 3. dx += s g A on fine-tune rows: the forward's expand over d_in against A, with the same k split
-    s1.ksplit_hint = s1.ksplit;
-    return run_shrink_expand(s1, LQ_VARIANT_EXPAND_ONLY, seg_bound, st) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    return LQ_OK;
 }

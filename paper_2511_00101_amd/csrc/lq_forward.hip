@@ -25,13 +25,14 @@
 // row-contiguous pattern as long as nothing else competes for the address path, which is why A_a, B_a
 // and h reach the MFMA through LDS instead.
 #include "lq_internal.h"
+#include <type_traits>
 
 namespace lq {
 namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kTallMin = 64;     // shrink: segments with at least this many rows take the row-split path
+constexpr int kTallMin = 33;     // shrink: segments with at least this many rows take the row-split path
 constexpr int kTallRows = 128;   // shrink, tall unit: rows (8 waves x 16)
 constexpr int kStageK = 256;     // shrink, tall unit: k elements of A staged per step
 constexpr int kShortRows = 32;   // shrink, short unit: rows (two 16-row MFMA tiles)
@@ -66,30 +67,33 @@ __device__ unsigned long long g_trace[2 * kTraceGroups * kTraceSlots];
 
 
 // ---- unit hand-out --------------------------------------------------------------------------------
-// A workgroup's first unit is its own index.  Units differ in size by more than 10x, so when there are
-// more units than workgroups the later ones are drawn from a counter instead of striding; the draw is
-// issued before the current unit runs and read after it.  Relaxed device-scope atomics: no data depends
-// on the counters.  The last workgroup to leave puts both counters back to zero, so they are zero
-// between launches.  One barrier per unit, which also separates the units' uses of the LDS.
-//   ctr[0] next ticket, ctr[1] workgroups that left; slot: two ints of LDS
+// A workgroup's first two units are fixed: its own index and that plus the grid size.  Units differ in
+// size by more than 10x, so the later ones are drawn from a counter instead of striding; the draw is
+// issued when a unit starts and read when it ends.  (Not for the first unit: all workgroups start
+// together, 256 draws on one address take microseconds, and the loads behind a draw cannot be used
+// before it returns.)  Relaxed device-scope atomics: no data depends on the counters.  The last
+// workgroup to leave puts both counters back to zero, so they are zero between launches.  One barrier
+// per unit, which also separates the units' uses of the LDS.
+//   ctr[0] draws so far, ctr[1] workgroups that left; slot: two ints of LDS
 template <class Body>
 __device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, Body&& body)
 {
-    const bool on = n_units > (int)gridDim.x;
+    const int grid = (int)gridDim.x;
+    const bool more = n_units > grid, draws = n_units > 2 * grid;
     int id = (int)blockIdx.x;
     for (int it = 0; id < n_units; ++it) {
-        int next = n_units;
-        if (on && threadIdx.x == 0)
-            next = (int)gridDim.x + __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int next = id + grid;
+        if (it > 0 && threadIdx.x == 0)
+            next = draws ? 2 * grid + __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : n_units;
         body(id, it);
-        if (!on) break;
+        if (!more) break;
         if (threadIdx.x == 0) slot[it & 1] = next;
         __syncthreads();
         id = uniform(slot[it & 1]);
     }
-    if (on && threadIdx.x == 0) {
+    if (draws && threadIdx.x == 0) {
         const int left = __hip_atomic_fetch_add(ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (left == (int)gridDim.x - 1) {
+        if (left == grid - 1) {
             __hip_atomic_store(ctr + 0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -100,21 +104,21 @@ __device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, 
 // the finished h, and fine-tune segments store it to h_out as well; with ksplit > 1 the expand kernel
 // adds the slices in order (and stores h_out), so no workgroup ever waits for another.
 struct HDest { float* base; float* save; int save_ld; };
-__device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const SegInfo& s, int ks)
+__device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, int nsplit)
 {
     HDest d;
     d.base = p.hpart + ((long long)ks * p.n_tokens + u.pos) * p.rstride;
-    const bool save = p.ksplit == 1 && u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets;
+    const bool save = nsplit == 1 && u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets;
     d.save = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     d.save_ld = s.rank;
     return d;
 }
 
 // finished h of one element: the slices added in order
-__device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j)
+__device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j, int parts)
 {
     float sum = p.hpart[pos * p.rstride + j];
-    for (int part = 1; part < p.ksplit; ++part) sum += p.hpart[((long long)part * p.n_tokens + pos) * p.rstride + j];
+    for (int part = 1; part < parts; ++part) sum += p.hpart[((long long)part * p.n_tokens + pos) * p.rstride + j];
     return sum;
 }
 
@@ -192,37 +196,43 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
                 }
     };
 
-    // Pipeline: while stage i is multiplied out of LDS (A) and registers (x), stage i + 1 is in flight:
-    // its A piece to registers (stored to the other LDS buffer at the top of the next iteration) and all
-    // of its x for this wave.  All loads are unconditional (past the end they re-read the last stage), so
-    // the count in flight is static.
+    // Pipeline: while stage i is multiplied out of LDS (A) and registers (x), the A piece of stage i + 1
+    // is in flight to registers (stored to the other LDS buffer at the top of the next iteration), and so
+    // is this wave's x of the next XB - 1 stages: two stages ahead where the registers allow it, which
+    // doubles the bytes a compute unit keeps in flight.  A is requested before x in every iteration, so
+    // the wait for A at the top of an iteration leaves the newest x stage in flight.  All loads are
+    // unconditional (past the end they re-read the last stage), so the count in flight is static.
+    constexpr int XB = NT <= 2 ? 3 : 2;
     LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 3));
-    u32x4 ga[NT], xa[NB][2], xb[NB][2];
+    u32x4 ga[NT], xr[XB][NB][2];
     if (n_my > 0) {
         stage_load(stage_of(0), ga);
-        xload(stage_of(0), xa);
+#pragma unroll
+        for (int b = 0; b < XB - 1; ++b) xload(stage_of(min(b, n_my - 1)), xr[b]);
     }
     LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 4));
-    for (int i = 0; i < n_my; i += 2) {
-        stage_store(0, ga);
+    auto step = [&](int i, auto slot) {
+        constexpr int J = decltype(slot)::value;
+        stage_store(i & 1, ga);
         stage_load(stage_of(min(i + 1, n_my - 1)), ga);
-        xload(stage_of(min(i + 1, n_my - 1)), xb);
+        xload(stage_of(min(i + XB - 1, n_my - 1)), xr[(J + XB - 1) % XB]);
         __syncthreads();  // one barrier per stage: the buffer written now was last read two stages ago
         __builtin_amdgcn_sched_barrier(0);
-        if (wave_live) mma(xa, 0);
+        if (wave_live) mma(xr[J], i & 1);
         __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int i = 0; i < n_my; i += XB) {
+        step(i, std::integral_constant<int, 0>{});
         if (i + 1 >= n_my) break;
-        stage_store(1, ga);
-        stage_load(stage_of(min(i + 2, n_my - 1)), ga);
-        xload(stage_of(min(i + 2, n_my - 1)), xa);
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        if (wave_live) mma(xb, 1);
-        __builtin_amdgcn_sched_barrier(0);
+        step(i + 1, std::integral_constant<int, 1>{});
+        if constexpr (XB == 3) {
+            if (i + 2 >= n_my) break;
+            step(i + 2, std::integral_constant<int, 2>{});
+        }
     }
 
     LQ_STAMP(0, LQ_UNIT_SLOT(u.it, 5));
-    const HDest d = h_dest(p, u, s, ks);
+    const HDest d = h_dest(p, u, s, ks, p.ksplit);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -365,7 +375,7 @@ __device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit
 #pragma unroll
                 for (int v = 0; v < 4; ++v) mine[((mt * NT + nt) * 4 + v) * kWave] = acc[mt][nt][v];
     }
-    const HDest d = h_dest(p, u, s, ks);
+    const HDest d = h_dest(p, u, s, ks, p.ksplit);
     __syncthreads();
 #pragma unroll
     for (int e = (int)threadIdx.x; e < REGS * kWave; e += kThreads) {
@@ -447,7 +457,8 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     // 1. the unit's rows and their h: slices added, (fine-tune segments, first column block: stored to
     // h_out,) scaled, split into bf16 high/low, stored as ready-made fragments
     for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
-    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && nb_begin == 0 && p.ksplit > 1;
+    const int parts = p.ksplit;
+    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && nb_begin == 0 && parts > 1;
     float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     {
         // item = (row i, 8 ranks); a thread's items are loaded together, slice after slice
@@ -465,7 +476,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
             h0[it] = *reinterpret_cast<const f32x4*>(hp[it]);
             h1[it] = *reinterpret_cast<const f32x4*>(hp[it] + 4);
         }
-        for (int part = 1; part < p.ksplit; ++part) {
+        for (int part = 1; part < parts; ++part) {
             const long long off = (long long)part * p.n_tokens * p.rstride;
             f32x4 a0[ITEMS], a1[ITEMS];
 #pragma unroll
@@ -624,7 +635,8 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     constexpr int JG = 8;  // rank rows of B in flight per group
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
     float* hs = &sh.hs[w][0][0];  // hs[j][t] at j * kTT + t
-    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && p.ksplit > 1;
+    const int parts = p.ksplit;
+    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && parts > 1;
     float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     const int n = n_block * kShortN + lane * 8;
     const int n_ld = min(n, p.d_out - 8);
@@ -639,7 +651,7 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     // item i = lane + 64 q is (row t = i % 4, rank j = i / 4); the first two per lane cover ranks up to 32
     auto h_item = [&](int i) {
         const int t = i & (kTT - 1), j = i >> 2;
-        const float h = h_sum(p, u.pos + min(t, u.len - 1), min(j, s.rank - 1));
+        const float h = h_sum(p, u.pos + min(t, u.len - 1), min(j, s.rank - 1), parts);
         const bool live = t < u.len && j < s.rank;
         if (save && live) h_dst[(long long)t * s.rank + j] = h;
         return live ? h * s.scale : 0.f;
@@ -722,8 +734,9 @@ template <int NT>
 __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdParams>& sg, unsigned char* lds_raw,
                                              int* s_slot)
 {
-    // hand-out order: full tall chunks, the tall segments' leftovers, then the short segments' chunks
-    const LenClass tall{kTallMin, kBig, p.kinds, 1}, rest{kTallMin, kBig, p.kinds, 2, 1, kTallRows}, small{1, kTallMin, p.kinds};
+    // hand-out order, large units first so that a launch ends evenly: the even chunks (65 to 128 rows) of
+    // the segments with more than 128 rows, the other tall segments (one chunk each), the short segments
+    const LenClass tall{kTallRows + 1, kBig, p.kinds, true}, rest{kTallMin, kTallRows + 1, p.kinds}, small{1, kTallMin, p.kinds};
     const ClassScan ct = scan_class(p, sg, kTallRows, tall), cr = scan_class(p, sg, kTallRows, rest),
                     cm = scan_class(p, sg, kShortRows, small);
     const int n_full = ct.total << p.ks_log2, n_tall = n_full + (cr.total << p.ks_log2), n_small = cm.total << p.ks_log2;
@@ -776,8 +789,7 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
     const LenClass shorts{1, kLongMin, p.kinds};
-    const LenClass full{kLongMin, kBig, p.kinds, 1}, big{kLongMin, kBig, p.kinds, 2, C::CT / 2, C::CT},
-        little{kLongMin, kBig, p.kinds, 2, 1, C::CT / 2};
+    const LenClass full{C::CT + 1, kBig, p.kinds, true}, big{C::CT / 2, C::CT + 1, p.kinds}, little{kLongMin, C::CT / 2, p.kinds};
 
     // short units first (their cost is mostly latency, which the start of a launch has to spare): one
     // per wave iteration, dealt round-robin over the workgroups first so that a few hundred units spread
@@ -805,8 +817,9 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
     }
     LQ_STAMP_WAIT(1, 39);
 
-    // long units, one per workgroup iteration: a chunk of rows x a group of column blocks, the full chunks
-    // first, the leftovers of more than half a chunk next, the small leftovers last.  Groups are as large
+    // long units, one per workgroup iteration: a chunk of rows x a group of column blocks, large ones first
+    // so that a launch ends evenly: the even chunks of the segments with more than CT rows, the segments
+    // with CT/2 to CT rows, the smaller ones.  Groups are as large
     // as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
     if (n_chunks > 0) {
         const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
@@ -936,13 +949,16 @@ int shrink_grid()
     return grid;
 }
 
-// Few rows: cut d_in into slices so that the shrink units still cover the machine.  A pure function of
-// host arguments.
+// A 128-row shrink unit streams its rows at the rate of one compute unit, so a batch has to be cut into
+// enough units for the launch to draw the full HBM rate and to end evenly: d_in is cut into slices (each
+// at least four stages long) as long as that leaves at most one row chunk x slice per workgroup (more
+// slices cost the expand kernel, which adds them up).  A pure function of host arguments.
 int choose_ksplit(int n_tokens, int seg_bound, int d_in, int grid)
 {
-    const long long units_est = (n_tokens + kTallRows - 1) / kTallRows + seg_bound / 2;
+    (void)seg_bound;
+    const long long chunks = (n_tokens + kTallRows - 1) / kTallRows;
     int ks = 1;
-    while (ks < ksplit_cap(n_tokens) && units_est * ks * 2 <= grid && d_in >= ks * 2 * 2 * kStageK) ks *= 2;
+    while (ks < ksplit_cap(n_tokens) && chunks * ks * 2 <= grid && d_in >= ks * 2 * 4 * kStageK) ks *= 2;
     return ks;
 }
 

@@ -53,30 +53,25 @@ __device__ __forceinline__ SegLane seg_batch(const P& p, int n_seg, const SegCac
 
 struct Unit { int seg, pos, len, first, seg_len, ad, kd, it; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len); it: loop count (tracing)
 
-// A class of chunks: those of the segments with lo <= rows < hi whose kind's bit is set in `kinds`;
-// part 0: all chunks of `per` rows (the last one may be shorter), part 1: only the full ones, part 2: only
-// the shorter last one, and only if it has tlo <= rows < thi.  Handing out the full chunks first and the
-// short leftovers last keeps the end of a launch balanced.
-struct LenClass { int lo, hi, kinds; int part = 0, tlo = 0, thi = 0; };
+// A class of chunks: those of the segments with lo <= rows < hi whose kind's bit is set in `kinds`.  A
+// segment is cut into ceil(rows / per) chunks; with `even` set they all get ceil(rows / chunks) rows
+// (so no chunk is less than half full), otherwise `per` rows each with a shorter last one.
+struct LenClass { int lo, hi, kinds; bool even = false; };
 
 __device__ __forceinline__ int chunks_in(int len, int kind, int per, LenClass cls)
 {
-    if (!(len >= cls.lo && len < cls.hi && len > 0 && ((cls.kinds >> kind) & 1))) return 0;
-    if (cls.part == 0) return (len + per - 1) / per;
-    if (cls.part == 1) return len / per;
-    const int rest = len % per;
-    return (rest > 0 && rest >= cls.tlo && rest < cls.thi) ? 1 : 0;
+    return (len >= cls.lo && len < cls.hi && len > 0 && ((cls.kinds >> kind) & 1)) ? (len + per - 1) / per : 0;
 }
 // position (relative to the segment's first row) and rows of the local-th chunk of a segment in a class
 __device__ __forceinline__ void chunk_rows(int seg_len, int local, int per, LenClass cls, int& rel, int& rows)
 {
-    if (cls.part == 2) {
-        rel = seg_len / per * per;
-        rows = seg_len - rel;
-    } else {
-        rel = local * per;
-        rows = min(per, seg_len - rel);
+    int each = per;
+    if (cls.even) {
+        const int n = (seg_len + per - 1) / per;
+        each = small_div(seg_len + n - 1, n);
     }
+    rel = local * each;
+    rows = min(each, seg_len - rel);
 }
 
 __device__ __forceinline__ int wave_sum(int v) { return lane_value(wave_inclusive_scan(v), kWave - 1); }
