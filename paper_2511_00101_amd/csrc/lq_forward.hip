@@ -43,26 +43,8 @@ constexpr int kShortN = 512;     // expand, short unit: columns (64 lanes x 8)
 constexpr int kMaxKSplit = 8;
 constexpr int kBig = 0x7fffffff;
 
-// Optional in-kernel time stamps (a build with -DLQ_TRACE): thread 0 of every workgroup records the
-// 100 MHz wall clock at a few points of its first units; lq_trace_read copies the table out.
 #ifdef LQ_TRACE
-constexpr int kTraceSlots = 40, kTraceGroups = 1024;
-__device__ unsigned long long g_trace[2 * kTraceGroups * kTraceSlots];
-#define LQ_STAMP(k, id)                                                                                   \
-    do {                                                                                                  \
-        if (threadIdx.x == 0 && blockIdx.x < kTraceGroups && (id) < kTraceSlots)                          \
-            g_trace[((k) * kTraceGroups + blockIdx.x) * kTraceSlots + (id)] = wall_clock64();             \
-    } while (0)
-#define LQ_STAMP_WAIT(k, id)                                                                              \
-    do {                                                                                                  \
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                       \
-        LQ_STAMP(k, id);                                                                                  \
-    } while (0)
-#define LQ_UNIT_SLOT(it, j) (4 + 7 * (it) + (j))
-#else
-#define LQ_STAMP(k, id) ((void)0)
-#define LQ_STAMP_WAIT(k, id) ((void)0)
-#define LQ_UNIT_SLOT(it, j) 0
+__device__ unsigned long long g_trace[2 * kTraceGroups * kTraceSlots];  // this file's stamp table
 #endif
 
 
@@ -469,6 +451,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         const float* hp[ITEMS];
 #pragma unroll
         for (int it = 0; it < ITEMS; ++it) {
+            if (it * kThreads >= n_items) break;  // workgroup uniform
             const int id = (int)threadIdx.x + it * kThreads;
             const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
             // (rank groups beyond the adapter's re-read its last one; they are zeroed below)
@@ -481,11 +464,13 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
             f32x4 a0[ITEMS], a1[ITEMS];
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
+                if (it * kThreads >= n_items) break;
                 a0[it] = *reinterpret_cast<const f32x4*>(hp[it] + off);
                 a1[it] = *reinterpret_cast<const f32x4*>(hp[it] + off + 4);
             }
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
+                if (it * kThreads >= n_items) break;
                 h0[it] += a0[it];
                 h1[it] += a1[it];
             }
@@ -788,14 +773,30 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
                                              ShortLds& sh, int* s_slot)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
-    const LenClass shorts{1, kLongMin, p.kinds};
-    const LenClass full{C::CT + 1, kBig, p.kinds, true}, big{C::CT / 2, C::CT + 1, p.kinds}, little{kLongMin, C::CT / 2, p.kinds};
+    const LenClass shorts{1, kLongMin, p.kinds}, longs{kLongMin, kBig, p.kinds};
+    const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
+
+    // Rows per long unit: CT when that still gives every workgroup a couple of units, else fewer (down to 64:
+    // the B block is staged once per unit), so that a batch with few rows is still spread over the whole machine.
+    int per = C::CT;
+    {
+        int rows = 0, segs = 0;
+#pragma unroll
+        for (int b = 0; b < kCachedBatches; ++b) {
+            const int len = sg.c[b].en - sg.c[b].st;
+            const bool in = chunks_in(len, sg.c[b].kd, 1, longs) > 0;
+            rows += wave_sum(in ? len : 0);
+            segs += wave_sum(in ? 1 : 0);
+        }
+        if (sg.n_seg > kCachedBatches * kWave) rows = kBig / 2;  // many segments: plenty of units anyway
+        while (per > 64 && ((long long)(rows / per + segs) * long_blocks < 2LL * (int)gridDim.x)) per >>= 1;
+    }
+    const LenClass full{per + 1, kBig, p.kinds, true}, big{per / 2, per + 1, p.kinds}, little{kLongMin, per / 2, p.kinds};
 
     // short units first (their cost is mostly latency, which the start of a launch has to spare): one
     // per wave iteration, dealt round-robin over the workgroups first so that a few hundred units spread
     // over all compute units
-    const ClassScan cf = scan_class(p, sg, C::CT, full), cb = scan_class(p, sg, C::CT, big),
-                    cl = scan_class(p, sg, C::CT, little);
+    const ClassScan cf = scan_class(p, sg, per, full), cb = scan_class(p, sg, per, big), cl = scan_class(p, sg, per, little);
     const int n_chunks = cf.total + cb.total + cl.total;
     {
         const ClassScan cs = scan_class(p, sg, kTT, shorts);
@@ -818,11 +819,10 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
     LQ_STAMP_WAIT(1, 39);
 
     // long units, one per workgroup iteration: a chunk of rows x a group of column blocks, large ones first
-    // so that a launch ends evenly: the even chunks of the segments with more than CT rows, the segments
-    // with CT/2 to CT rows, the smaller ones.  Groups are as large
-    // as possible (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
+    // so that a launch ends evenly: the even chunks of the segments with more than `per` rows, the segments
+    // with per/2 to per rows, the smaller ones.  Groups are as large as possible (the rows' h is prepared
+    // once per unit) while leaving about 4 units per workgroup.
     if (n_chunks > 0) {
-        const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
         const int groups_wanted = small_div(4 * (int)gridDim.x + n_chunks - 1, n_chunks);
         const int per_group = max(1, small_div(long_blocks, max(1, min(long_blocks, groups_wanted))));
         const int groups = small_div(long_blocks + per_group - 1, per_group);
@@ -835,9 +835,9 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
             LQ_STAMP(1, LQ_UNIT_SLOT(it, 0));
             const int cid = id < n_full ? id : id < n_big ? id - n_full : id - n_big;
             const int chunk = small_div(cid, groups);
-            const bool ok = id < n_full ? find_unit(p, sg, cf, chunk, C::CT, full, u, s)
-                            : id < n_big ? find_unit(p, sg, cb, chunk, C::CT, big, u, s)
-                                         : find_unit(p, sg, cl, chunk, C::CT, little, u, s);
+            const bool ok = id < n_full ? find_unit(p, sg, cf, chunk, per, full, u, s)
+                            : id < n_big ? find_unit(p, sg, cb, chunk, per, big, u, s)
+                                         : find_unit(p, sg, cl, chunk, per, little, u, s);
             if (!ok) return;
             LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(it, 2));
             const int nb = (cid - chunk * groups) * per_group;
