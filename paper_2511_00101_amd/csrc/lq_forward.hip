@@ -904,10 +904,11 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
     __shared__ int s_slot[2];
-    // the generation is read before this workgroup arrives, hence before the last arrival can change it
-    const int gen0 = __hip_atomic_load(p.tickets + 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     LQ_STAMP(0, 0);
     const Segs<FwdParams> sg = load_segs(p);
+    // The generation is read before this workgroup arrives, hence before the last arrival can change it;
+    // and after the table loads, so that their results need not wait for this slower, uncached load.
+    const int gen0 = __hip_atomic_load(p.tickets + 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
     LQ_STAMP(1, 0);
