@@ -9,7 +9,7 @@ Infinity Cache left there by the previous step.
 
 Prints ONE JSON line (see README/DESIGN for the fields).  `value` is tokens/s of the headline
 workload (the decode-heavy batch, benchmark configs[1]); `roofline` is the HBM roofline of the
-dominant kernel from HIP-event timing of each launch; `cpu_baseline` is the fp64 oracle on the host
+dominant kernel from HIP-event timing of each launch (the dispatch's own start and end time stamps); `cpu_baseline` is the fp64 oracle on the host
 cores; `configs` carries the same measurements for the other single-call workloads.
 """
 from __future__ import annotations
@@ -102,44 +102,39 @@ def time_steps(rep, steps, warmup):
 
 
 def time_kernels(rep, steps, warmup):
-    """Average duration of each kernel from HIP events on the launch stream, two ways, the smaller one kept:
-    (a) an event pair around every single launch (reads the duration plus a fixed event cost of a few
-    microseconds), (b) `steps` launches of one phase back to back between two events (reads the duration plus
-    the dispatch gap, but not less than the host's launch interval).  Both are upper bounds of the
-    kernel's own duration; rocprofv3's kernel trace of the same command is the reference (profiles/)."""
+    """Average duration of each kernel over `steps` steps, from HIP events on the launch stream: the library
+    launches every kernel with a pair of events that receive the dispatch's own start and end time stamps
+    (lora_profile_enable / lora_profile_read), which is the duration rocprofv3's kernel trace reports
+    (profiles/), without the gaps between launches."""
     torch, lq = rep.torch, rep.lq
-    phases = (("build", None),) + ((("forward_fused", lq.LQ_VARIANT_FUSED),) if rep.variant == lq.LQ_VARIANT_FUSED else
-                                   (("shrink", lq.LQ_VARIANT_SHRINK_ONLY), ("expand", lq.LQ_VARIANT_EXPAND_ONLY)))
-
-    def launch(name, variant, i):
-        if name == "build":
-            rep.build(i)
-        else:
-            rep.forward(i, variant)
-
     for i in range(warmup):
         rep.step(i)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(steps)]
     torch.cuda.synchronize()
+    lq.lora_profile_enable(True)
     for i in range(steps):
-        ev[i][0].record()
-        for k, (name, variant) in enumerate(phases):
-            launch(name, variant, warmup + i)
-            ev[i][k + 1].record()
+        rep.step(warmup + i)
     torch.cuda.synchronize()
-    out = {}
-    for k, (name, variant) in enumerate(phases):
-        each = sorted(1e3 * ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(steps))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(steps):
-            launch(name, variant, i)
-        e1.record()
-        torch.cuda.synchronize()
-        train = 1e3 * e0.elapsed_time(e1) / steps
-        out[name] = dict(avg_us=min(sum(each) / len(each), train), per_launch_events_us=sum(each) / len(each),
-                         back_to_back_us=train, min_us=min(each[0], train))
-    return out
+    prof = lq.lora_profile_read()
+    lq.lora_profile_enable(False)
+    return {name: dict(avg_us=total / n, launches=n) for name, (total, n) in prof.items() if n}
+
+
+PROFILE_FILES = dict(cfg2_decode_heavy="forward_cfg2_decode_heavy.txt", cfg3_unified="forward_cfg3_unified.txt",
+                     cfg4_mlp_up="forward_cfg4_mlp_up.txt", cfg4_mlp_down="forward_cfg4_mlp_down.txt")
+
+
+def counter_traffic(workload, phase):
+    """HBM bytes per launch of `phase` from the committed rocprofv3 counter summary of this workload
+    (profiles/, FETCH_SIZE and WRITE_SIZE scaled by the copy calibration), or None."""
+    name = PROFILE_FILES.get(workload)
+    path = os.path.join(ROOT, "profiles", name) if name else None
+    if not path or not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == phase:
+            return int(f[2])
+    return None
 
 
 def measure(p, variant, steps, warmup):
@@ -164,7 +159,7 @@ def measure(p, variant, steps, warmup):
         forward_mfma_frac=work["flops"] / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         algorithmic_bytes=work["total"], flops=work["flops"], kernels=kern,
         roofline=dict(bound="hbm", kernel=dom, achieved=dom_gbps, peak=HBM_PEAK_GBPS, unit="GB/s",
-                      frac=dom_gbps / HBM_PEAK_GBPS, traffic=None, algorithmic_bytes=dom_bytes,
+                      frac=dom_gbps / HBM_PEAK_GBPS, traffic=counter_traffic(p.name, dom), algorithmic_bytes=dom_bytes,
                       avg_launch_us=kern[dom]["avg_us"]))
     del rep
     return res
@@ -277,6 +272,13 @@ def measure_layer_stack(variant, steps, warmup):
     ev[0].record(); st.forward_only(); ev[1].record(); st.backward_only(); ev[2].record()
     torch.cuda.synchronize()
     fwd_ms, bwd_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+    kernels = {}
+    for which, run in (("forward", st.forward_only), ("backward", st.backward_only)):
+        st.lq.lora_profile_enable(True)
+        run()
+        torch.cuda.synchronize()
+        kernels[which] = {name: dict(avg_us=total / n, launches=n) for name, (total, n) in st.lq.lora_profile_read().items() if n}
+        st.lq.lora_profile_enable(False)
     return dict(workload="cfg5_layer_stack (32 layers x 7 projections, forward + backward of the fine-tune rows)",
                 tokens=w["tokens"], calls=len(st.calls), ms_per_step=s_per_step * 1e3, tokens_per_s=w["tokens"] / s_per_step,
                 forward_ms=fwd_ms, backward_ms=bwd_ms,
@@ -284,7 +286,7 @@ def measure_layer_stack(variant, steps, warmup):
                 forward_tflops=w["fwd_flops"] / (fwd_ms * 1e-3) / 1e12, backward_tflops=w["bwd_flops"] / (bwd_ms * 1e-3) / 1e12,
                 forward_hbm_frac=w["fwd_bytes"] / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                 backward_hbm_frac=w["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                algorithmic_bytes=w["fwd_bytes"] + w["bwd_bytes"], flops=w["fwd_flops"] + w["bwd_flops"])
+                algorithmic_bytes=w["fwd_bytes"] + w["bwd_bytes"], flops=w["fwd_flops"] + w["bwd_flops"], kernels=kernels)
 
 
 def cpu_baseline(p, budget_s=12.0):

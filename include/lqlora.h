@@ -162,6 +162,25 @@ lq_status lora_segmented_backward(const void* x, int64_t ldx, const void* dy, in
                                   const float* h_saved, const int64_t* h_offsets,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Timing of the library's own kernel launches, for benchmarks (not part of the paper's method).
+ * While enabled, every launch gets a pair of events that receive the dispatch's start and end time
+ * stamps, i.e. the duration a kernel trace reports, without the gaps between launches.
+ *   lora_profile_enable(on)  on != 0 starts recording, 0 stops; both discard what was recorded.
+ *   lora_profile_read(total_us, launches, n_kernels)  host arrays of n_kernels >= LQ_KERNEL_IDS entries,
+ *       indexed by lq_kernel_id: summed duration in microseconds and number of launches since
+ *       recording started; waits for the recorded launches to finish, then discards the records.
+ * Host-side state shared by all threads of the process: call from one thread at a time.  At most
+ * 65536 launches are recorded between reads; further ones run untimed.
+ * ------------------------------------------------------------------------------------------- */
+typedef enum {
+    LQ_KERNEL_BUILD = 0, LQ_KERNEL_SHRINK = 1, LQ_KERNEL_EXPAND = 2, LQ_KERNEL_FUSED = 3,
+    LQ_KERNEL_WGRAD = 4, LQ_KERNEL_WREDUCE = 5, LQ_KERNEL_IDS = 6
+} lq_kernel_id;
+
+lq_status lora_profile_enable(int32_t on);
+lq_status lora_profile_read(double* total_us, int64_t* launches, int32_t n_kernels);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,7 +35,10 @@ _SIGNATURES = {
     "lora_segmented_backward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp,
                                                _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
                                                _vp, _vp, _vp, _sz, _vp]),
+    "lora_profile_enable": (ctypes.c_int, [_i32]),
+    "lora_profile_read": (ctypes.c_int, [_vp, _vp, _i32]),
 }
+KERNEL_NAMES = ("build", "shrink", "expand", "forward_fused", "wgrad", "wreduce")
 
 
 class LqError(RuntimeError):
@@ -219,3 +222,21 @@ def bits_from_bf16(t: torch.Tensor) -> np.ndarray:
 
 def workspace(n_bytes: int, device="cuda") -> torch.Tensor:
     return torch.zeros((max(n_bytes, 256) + 7) // 8, dtype=torch.int64, device=device)
+
+
+def lora_profile_enable(on: bool) -> None:
+    """Start (or stop) timing the library's own launches; either way what was recorded is discarded."""
+    st = lib().lora_profile_enable(1 if on else 0)
+    if st != LQ_OK:
+        raise LqError(st, "lora_profile_enable")
+
+
+def lora_profile_read() -> dict:
+    """Waits for the recorded launches; {kernel name: (summed microseconds, launches)} since recording started."""
+    n = len(KERNEL_NAMES)
+    total = (ctypes.c_double * n)()
+    count = (ctypes.c_int64 * n)()
+    st = lib().lora_profile_read(ctypes.cast(total, ctypes.c_void_p), ctypes.cast(count, ctypes.c_void_p), n)
+    if st != LQ_OK:
+        raise LqError(st, "lora_profile_read")
+    return {name: (float(total[i]), int(count[i])) for i, name in enumerate(KERNEL_NAMES)}

@@ -309,8 +309,7 @@ hipError_t launch_wgrad(const BwdParams& p, hipStream_t st)
             per_cu = 1;
         grid = cus * per_cu;
     }
-    hipLaunchKernelGGL(wgrad_kernel<NT>, dim3(grid), dim3(kThreads), lds, st, p);
-    return hipGetLastError();
+    return launch_kernel(kKernelWgrad, wgrad_kernel<NT>, dim3(grid), dim3(kThreads), lds, st, p);
 }
 
 }  // namespace
@@ -414,8 +413,7 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
         const hipError_t e = max_rank <= 16 ? launch_wgrad<1>(b, st) : max_rank <= 32 ? launch_wgrad<2>(b, st)
                            : max_rank <= 64 ? launch_wgrad<4>(b, st) : launch_wgrad<8>(b, st);
         if (e != hipSuccess) return LQ_ERR_HIP;
-        hipLaunchKernelGGL(wreduce_kernel, dim3(512), dim3(kThreads), 0, st, b);
-        if (hipGetLastError() != hipSuccess) return LQ_ERR_HIP;
+        if (launch_kernel(kKernelWreduce, wreduce_kernel, dim3(512), dim3(kThreads), 0, st, b) != hipSuccess) return LQ_ERR_HIP;
     }
     return LQ_OK;
 }

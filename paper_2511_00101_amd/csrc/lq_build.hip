@@ -3,13 +3,14 @@
 // kind * n_adapters + adapter (the batch order fine-tune | prefill+evaluation | decode of
 // Algorithm 1, refined by adapter) and run-length encodes the non-empty keys.  Integer only; the
 // result is unique, so it is compared bit for bit with the CPU oracle.
-#include "lq_common.h"
+#include "lq_internal.h"
 
 namespace lq {
 namespace {
 
 constexpr int kBuildThreads = 1024;
 constexpr int kBuildWaves = kBuildThreads / kWave;
+constexpr int kKeyRounds = 8;   // 64-token rounds whose keys a wave holds in registers
 constexpr int kBuildLdsBudget = 60000;  // bytes of dynamic LDS used for the histograms when they fit
 
 __device__ __forceinline__ int block_exclusive_scan(int v, int* s_tot, int& total)
@@ -67,6 +68,43 @@ __device__ __forceinline__ int token_key(const int32_t* __restrict__ token_adapt
     return (a >= 0 && a < n_adapters && k <= LQ_SEG_DECODE) ? k * n_adapters + a : -1;
 }
 
+// Lanes of a 64-token round that hold the same key.  A batch whose tokens arrive grouped has one or two
+// keys per round, found with one ballot each: up to four such passes set `peers` (the lanes with this
+// lane's key) for the lanes they cover and return the lanes still to do.
+__device__ __forceinline__ unsigned long long leader_passes(int key, unsigned long long& peers)
+{
+    const bool valid = key >= 0;
+    unsigned long long todo = __ballot(valid);
+    peers = 0;
+    for (int pass = 0; pass < 4 && todo; ++pass) {
+        const int k = lane_value(key, __ffsll((long long)todo) - 1);
+        const unsigned long long same = __ballot(valid && key == k);
+        if (valid && key == k) peers = same;
+        todo &= ~same;
+    }
+    return todo;
+}
+// The same for every lane, packed as leader | rank among the peers << 8 | their number << 16 (0 for a lane
+// without a key); rounds with more than four keys finish by voting on the key's bits one at a time.
+__device__ __forceinline__ int key_group(int key, int key_bits)
+{
+    const int lane = lane_id();
+    unsigned long long peers;
+    const unsigned long long todo = leader_passes(key, peers);
+    if (todo) {
+        const bool mine = (todo >> lane) & 1;
+        unsigned long long left = todo;
+        for (int b = 0; b < key_bits; ++b) {
+            const bool bit = mine && ((key >> b) & 1);
+            const unsigned long long vote = __ballot(bit);
+            left &= bit ? vote : ~vote;
+        }
+        if (mine) peers = left;
+    }
+    if (key < 0) return 0;
+    return (__ffsll((long long)peers) - 1) | (__popcll(peers & ((1ull << lane) - 1ull)) << 8) | (__popcll(peers) << 16);
+}
+
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     const int32_t* __restrict__ token_adapter, const uint8_t* __restrict__ token_kind, int n_tokens,
@@ -97,9 +135,19 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     const int t_end = min(n_tokens, t_begin + per_wave);
 
     // What the later phases need from memory is requested first, so that these round trips overlap the
-    // clearing of the histograms: the keys of the wave's first 64 tokens (all of them in a small batch)
-    // and the rank of the first key this thread turns into a segment.
-    const int key_first = t_begin + lane < t_end ? token_key(token_adapter, token_kind, t_begin + lane, n_adapters) : -1;
+    // clearing of the histograms: the keys of the wave's first kKeyRounds x 64 tokens (all of them in a
+    // batch of up to 8192 tokens, and then they stay in registers for the scatter) and the rank of the
+    // first key this thread turns into a segment.
+    int keys[kKeyRounds];
+    auto load_keys = [&](int base0) {  // all loads go out before the first one is used
+#pragma unroll
+        for (int r = 0; r < kKeyRounds; ++r) {
+            const int t = base0 + r * kWave + lane;
+            keys[r] = t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1;
+        }
+    };
+    const bool keys_fit = per_wave <= kKeyRounds * kWave;  // workgroup uniform
+    load_keys(t_begin);
     const int keys_per_thread = (n_keys + kBuildThreads - 1) / kBuildThreads;
     const int k_begin = min(n_keys, tid * keys_per_thread);
     const int k_end = min(n_keys, k_begin + keys_per_thread);
@@ -109,10 +157,25 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     for (int i = tid; i < n_entries; i += kBuildThreads) *hist_at(i) = 0;
     __syncthreads();
 
-    for (int base = t_begin; base < t_end; base += kWave) {
-        const int t = base + lane;
-        const int key = base == t_begin ? key_first : (t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1);
-        if (key >= 0) atomicAdd(hist_at(key * kBuildWaves + w), 1);
+    int key_bits = 0;
+    while ((1 << key_bits) < n_keys) ++key_bits;
+    // 64 additions to one LDS word are slow, so in a batch with several rounds per wave the first lane of
+    // every group of equal keys adds for its group (and the grouping is kept for the scatter while the
+    // keys stay in registers).  A small batch (one round per wave) has few tokens per key: it adds lane by
+    // lane and leaves the grouping to the scatter.
+    const bool group_early = per_wave > kWave;  // workgroup uniform
+    int groups[kKeyRounds];
+    for (int base0 = t_begin; base0 < t_end; base0 += kKeyRounds * kWave) {
+        if (base0 != t_begin) load_keys(base0);
+#pragma unroll
+        for (int r = 0; r < kKeyRounds; ++r) {
+            if (group_early) {
+                groups[r] = key_group(keys[r], key_bits);
+                if (keys[r] >= 0 && (groups[r] & 0xff) == lane) atomicAdd(hist_at(keys[r] * kBuildWaves + w), groups[r] >> 16);
+            } else if (keys[r] >= 0) {
+                atomicAdd(hist_at(keys[r] * kBuildWaves + w), 1);
+            }
+        }
     }
     __syncthreads();
 
@@ -167,26 +230,22 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     }
     __syncthreads();  // all reads of the scanned offsets are done before the scatter advances them
 
-    // Stable scatter.  Within a 64-token round every lane finds the lanes that hold the same key by
-    // voting on the key's bits one at a time; its rank among them is its offset from the slot that the
-    // first of them draws for the whole group.
-    int key_bits = 0;
-    while ((1 << key_bits) < n_keys) ++key_bits;
-    for (int base = t_begin; base < t_end; base += kWave) {
-        const int t = base + lane;
-        const int key = base == t_begin ? key_first : (t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1);
-        const bool valid = key >= 0;
-        unsigned long long peers = __ballot(valid);
-        for (int b = 0; b < key_bits; ++b) {
-            const bool bit = valid && ((key >> b) & 1);
-            const unsigned long long vote = __ballot(bit);
-            peers &= bit ? vote : ~vote;
+    // Stable scatter: the first lane of every group of equal keys draws the slots of the whole group, the
+    // others add their rank in the group.
+    for (int base0 = t_begin; base0 < t_end; base0 += kKeyRounds * kWave) {
+        if (!keys_fit) load_keys(base0);
+#pragma unroll
+        for (int r = 0; r < kKeyRounds; ++r) {
+            const int t = base0 + r * kWave + lane;
+            const int key = keys[r];
+            if (__ballot(key >= 0) == 0) continue;  // wave uniform: nothing in this round
+            const int grp = group_early && keys_fit ? groups[r] : key_group(key, key_bits);
+            const int leader = key >= 0 ? (grp & 0xff) : lane;
+            int slot = 0;
+            if (key >= 0 && lane == leader) slot = atomicAdd(hist_at(key * kBuildWaves + w), grp >> 16);
+            slot = __shfl(slot, leader, kWave);
+            if (key >= 0) perm[slot + ((grp >> 8) & 0xff)] = t;
         }
-        const int leader = valid ? __ffsll((long long)peers) - 1 : lane;
-        int slot = 0;
-        if (valid && lane == leader) slot = atomicAdd(hist_at(key * kBuildWaves + w), __popcll(peers));
-        slot = __shfl(slot, leader, kWave);
-        if (valid) perm[slot + __popcll(peers & ((1ull << lane) - 1ull))] = t;
     }
 }
 
@@ -220,13 +279,13 @@ extern "C" lq_status lora_build_segments(const int32_t* token_adapter, const uin
         if (!workspace || workspace_bytes < lora_build_workspace_bytes(n_tokens, n_adapters)) return LQ_ERR_WORKSPACE;
         ws_hist = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + lq::kWsHeaderBytes);
     }
-    if (use_lds)
-        hipLaunchKernelGGL(lq::build_segments_kernel<true>, dim3(1), dim3(lq::kBuildThreads), hist_bytes,
-                           static_cast<hipStream_t>(stream), token_adapter, token_kind, n_tokens, ranks, n_adapters, perm,
-                           seg_starts, seg_adapter, seg_kind, h_offsets, n_segments, ws_hist);
-    else
-        hipLaunchKernelGGL(lq::build_segments_kernel<false>, dim3(1), dim3(lq::kBuildThreads), 0,
-                           static_cast<hipStream_t>(stream), token_adapter, token_kind, n_tokens, ranks, n_adapters, perm,
-                           seg_starts, seg_adapter, seg_kind, h_offsets, n_segments, ws_hist);
-    return hipGetLastError() == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    const hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e =
+        use_lds ? lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<true>, dim3(1), dim3(lq::kBuildThreads), hist_bytes,
+                                    st, token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter,
+                                    seg_kind, h_offsets, n_segments, ws_hist)
+                : lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<false>, dim3(1), dim3(lq::kBuildThreads), 0, st,
+                                    token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter,
+                                    seg_kind, h_offsets, n_segments, ws_hist);
+    return e == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }

@@ -966,8 +966,7 @@ int choose_ksplit(int n_tokens, int seg_bound, int d_in, int grid)
 template <int NT>
 hipError_t launch_shrink(const FwdParams& p, hipStream_t st)
 {
-    hipLaunchKernelGGL(shrink_kernel<NT>, dim3(shrink_grid<NT>()), dim3(kThreads), shrink_lds_bytes<NT>(), st, p);
-    return hipGetLastError();
+    return launch_kernel(kKernelShrink, shrink_kernel<NT>, dim3(shrink_grid<NT>()), dim3(kThreads), shrink_lds_bytes<NT>(), st, p);
 }
 
 template <int KSTEPS, int PAIRS>
@@ -976,8 +975,7 @@ hipError_t launch_expand(const FwdParams& p, hipStream_t st)
     static int grid = 0;
     const size_t lds = ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
     if (!grid) grid = resident_grid(expand_kernel<KSTEPS, PAIRS>, lds);
-    hipLaunchKernelGGL((expand_kernel<KSTEPS, PAIRS>), dim3(grid), dim3(kThreads), lds, st, p);
-    return hipGetLastError();
+    return launch_kernel(kKernelExpand, expand_kernel<KSTEPS, PAIRS>, dim3(grid), dim3(kThreads), lds, st, p);
 }
 
 template <int NT, int KSTEPS, int PAIRS>
@@ -995,8 +993,7 @@ hipError_t launch_fused(const FwdParams& p, hipStream_t st)
 {
     const size_t lds = shrink_lds_bytes<NT>() > ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES ? shrink_lds_bytes<NT>()
                                                                                    : ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
-    hipLaunchKernelGGL((fused_kernel<NT, KSTEPS, PAIRS>), dim3(fused_grid<NT, KSTEPS, PAIRS>()), dim3(kThreads), lds, st, p);
-    return hipGetLastError();
+    return launch_kernel(kKernelFused, fused_kernel<NT, KSTEPS, PAIRS>, dim3(fused_grid<NT, KSTEPS, PAIRS>()), dim3(kThreads), lds, st, p);
 }
 
 }  // namespace

@@ -1,6 +1,8 @@
 // Declarations shared by the forward and backward translation units (not part of the C ABI).
 #pragma once
 
+#include <hip/hip_ext.h>
+
 #include "lq_segments.h"
 
 namespace lq {
@@ -37,5 +39,25 @@ size_t h_slices_bytes(int n_tokens, int max_rank);   // bytes of the partial-h r
 // Fills p.ksplit and enqueues: variant LQ_VARIANT_SPLIT / _FUSED / _SHRINK_ONLY / _EXPAND_ONLY.
 // p.ksplit_hint > 0 forces that split (the expand half of a pair must use the shrink half's value).
 hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream_t stream);
+
+// ---- optional timing of the library's own launches (lora_profile_enable / lora_profile_read) ----------------
+// When enabled, a launch goes through hipExtLaunchKernelGGL with a pair of events that receive the
+// dispatch's own start and end time stamps (what a kernel trace reports), and is filed under its id.
+enum KernelId { kKernelBuild = 0, kKernelShrink, kKernelExpand, kKernelFused, kKernelWgrad, kKernelWreduce, kKernelIds };
+bool profile_on();
+void profile_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);  // a fresh pair (null, null when full)
+
+template <class K, class... Args>
+hipError_t launch_kernel(int kernel_id, K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args)
+{
+    if (profile_on()) {
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        profile_events(kernel_id, &e0, &e1);
+        hipExtLaunchKernelGGL(kernel, grid, block, (unsigned int)lds, st, e0, e1, 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+    }
+    return hipGetLastError();
+}
 
 }  // namespace lq
