@@ -87,3 +87,20 @@ def check_forward(oracle_mod, p: synth.Problem, variant=lq.LQ_VARIANT_SPLIT):
     live[ref.segments.perm] = True
     assert np.array_equal(y_bits[~live], p.y0[~live])
     return y_bits, h, ref
+
+
+def long_batch_problem(seed, with_dy):
+    """40000 tokens (more than one batch of keys per builder wave, no k split, hundreds of chunks): a few long
+    fine-tune and prefill segments, many short ones, narrow layers so that the oracle stays fast."""
+    rng = np.random.default_rng(seed)
+    n_ad = 24
+    lens = [9000, 7000, 5000, 3000] + list(rng.integers(1, 700, size=60))
+    lens = np.asarray(lens)          # more than 40000 rows in all; the batch is cut at 40000
+    ads = rng.integers(0, n_ad, size=len(lens))
+    kinds = np.where(np.arange(len(lens)) < 2, 0, rng.integers(0, 3, size=len(lens))).astype(np.uint8)
+    ta = np.concatenate([np.full(l, a, np.int32) for a, l in zip(ads, lens)])[:40000]
+    tk = np.concatenate([np.full(l, k, np.uint8) for k, l in zip(kinds, lens)])[:40000]
+    order = rng.permutation(len(ta))
+    ranks = rng.choice([8, 16, 32], size=n_ad)
+    return synth.make_problem("long_batch", synth.Batch(ta[order], tk[order]), 512, 384, ranks, rng.uniform(0.5, 1.5, n_ad),
+                              seed + 1, with_dy=with_dy, w_std=0.03)

@@ -6,7 +6,7 @@ import torch
 from paper_2511_00101_amd import binding as lq
 from paper_2511_00101_amd import synth
 
-from gpu_util import DeviceProblem, assert_close, rel_frobenius
+from gpu_util import DeviceProblem, assert_close, long_batch_problem, rel_frobenius
 
 pytestmark = pytest.mark.gpu
 
@@ -97,3 +97,23 @@ def test_backward_repeat_is_bit_identical(oracle_mod):
 def test_backward_config5_calls(oracle_mod, layer, projection):
     """Two of the 224 (layer, projection) calls of the layer stack with its seeded dy."""
     run_backward(oracle_mod, synth.config5(layer, projection, with_dy=True))
+
+
+def test_backward_many_adapters_and_tokens(oracle_mod):
+    """More than 128 adapters and fine-tune segments (beyond the register-cached part of the tables), ranks up to
+    the maximum, and a long batch whose weight gradients span many row chunks."""
+    rng = np.random.default_rng(11)
+    n_ad = 140
+    ranks = rng.choice([4, 16, 40, 96, 128], size=n_ad)
+    lens = rng.choice([1, 3, 17, 40, 70, 600], size=n_ad, p=[0.2, 0.2, 0.2, 0.2, 0.15, 0.05])
+    ta = np.concatenate([np.full(l, a, np.int32) for a, l in enumerate(lens)])
+    tk = np.concatenate([np.full(l, 0 if a % 3 else a % 2 + 1, np.uint8) for a, l in enumerate(lens)])
+    order = rng.permutation(len(ta))
+    p = synth.make_problem("many_ft", synth.Batch(ta[order], tk[order]), 512, 768, ranks, rng.uniform(0.5, 1.0, n_ad), 654,
+                           with_dy=True, w_std=0.03)
+    run_backward(oracle_mod, p)
+
+
+def test_backward_many_tokens(oracle_mod):
+    """40000 tokens, two fine-tune segments of thousands of rows: weight gradients from many row chunks."""
+    run_backward(oracle_mod, long_batch_problem(901, with_dy=True))

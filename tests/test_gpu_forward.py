@@ -6,7 +6,7 @@ import torch
 from paper_2511_00101_amd import binding as lq
 from paper_2511_00101_amd import synth
 
-from gpu_util import DeviceProblem, assert_close, assert_tables_equal, check_forward
+from gpu_util import long_batch_problem, DeviceProblem, assert_close, assert_tables_equal, check_forward
 
 pytestmark = pytest.mark.gpu
 
@@ -174,3 +174,31 @@ def test_large_rank_and_many_segments(oracle_mod):
                            w_std=0.03)
     for variant in VARIANTS:
         check_forward(oracle_mod, p, variant)
+
+
+def test_many_tokens(oracle_mod):
+    p = long_batch_problem(900, with_dy=False)
+    for variant in VARIANTS:
+        check_forward(oracle_mod, p, variant)
+
+
+def test_launch_timing_api():
+    """lora_profile_enable / lora_profile_read: one record per launch, plausible durations, nothing left after a read."""
+    p = synth.config1()
+    d = DeviceProblem(p)
+    lq.lora_profile_enable(True)
+    try:
+        for _ in range(3):
+            d.build()
+            d.forward(lq.LQ_VARIANT_SPLIT)
+        d.forward(lq.LQ_VARIANT_FUSED)
+        prof = lq.lora_profile_read()
+        assert prof["build"][1] == 3 and prof["shrink"][1] == 3 and prof["expand"][1] == 3 and prof["forward_fused"][1] == 1
+        for name in ("build", "shrink", "expand", "forward_fused"):
+            total, n = prof[name]
+            assert 0.5 < total / n < 1000.0, (name, total, n)   # microseconds
+        assert all(n == 0 for _, n in lq.lora_profile_read().values())
+    finally:
+        lq.lora_profile_enable(False)
+    d.forward(lq.LQ_VARIANT_SPLIT)
+    assert all(n == 0 for _, n in lq.lora_profile_read().values())
