@@ -4,20 +4,22 @@
 // Every workgroup (8 waves) reads the segment tables itself, so the grids are a fixed number of
 // resident workgroups that stride over "units"; no plan buffer or extra launch is needed.
 //
-//   shrink, tall unit  : 128 rows of a segment with >= 64 rows x one of `ksplit` interleaved slices of
-//                        d_in.  A GEMM with a skinny output: each wave owns 16 rows and streams its x
-//                        rows straight into MFMA fragments; the 256-wide k stage of A_a is staged in
-//                        LDS once per workgroup (coalesced loads, double buffered) and shared by the
-//                        8 waves, so A_a crosses the L2->L1 path once per 128 rows.
-//   shrink, short unit : <= 32 rows of a segment with < 64 rows x one slice of d_in.  GEMV-like: the 8
-//                        waves take alternate 64-wide k blocks of x and A_a and tree-reduce through LDS
-//                        in a fixed order.  The MFMA does the k reduction even when few rows are live.
+//   shrink, tall unit  : up to 128 rows of a segment with more than 32 rows (longer segments are cut into
+//                        even chunks) x one of `ksplit` slices of d_in.  A GEMM with a skinny output:
+//                        each wave owns 16 rows and streams its x rows straight into MFMA fragments;
+//                        the 256-wide k stage of A_a is staged in LDS once per workgroup (coalesced
+//                        loads, double buffered) and shared by the 8 waves, so A_a crosses the L2->L1
+//                        path once per chunk.
+//   shrink, short unit : a segment of at most 32 rows x one slice of d_in.  GEMV-like: the 8 waves take
+//                        alternate 64-wide k blocks of x and A_a and add their results through LDS in
+//                        a fixed order.  The MFMA does the k reduction even when few rows are live.
 //   (with ksplit > 1 every shrink unit stores the h of its slice and the expand kernel adds the slices
 //    in order, so no workgroup waits for another and the sum does not depend on timing)
-//   expand, long unit  : 256 rows of a segment with >= 16 rows x 512 columns of d_out.  The B_a block is
-//                        staged in LDS and transposed into MFMA fragments that stay in registers; the
-//                        unit's h rows are scaled, split into bf16 high and low parts and laid out as
-//                        fragments in LDS once; then y streams by, 32 rows per step, read-modify-write.
+//   expand, long unit  : up to 256 rows of a segment with >= 16 rows x a group of 512-column blocks of
+//                        d_out.  The B_a block is staged in LDS and transposed into MFMA fragments
+//                        that stay in registers; the unit's h rows are scaled, split into bf16 high and
+//                        low parts and laid out as fragments in LDS once; then y streams by, 32 rows
+//                        per step, read-modify-write.
 //   expand, short unit : one wave: <= 4 rows of a segment with < 16 rows x 512 columns.  B_a rows are
 //                        streamed with 16-byte loads, h is broadcast from LDS, plain FMAs.
 // x and y are accessed with 16-byte loads/stores straight in the MFMA operand layout (16 rows x 64
@@ -107,8 +109,8 @@ __device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j,
 // =================================================================================================
 // shrink, tall unit.  D[row][rank] = sum_k x[row][k] A[rank][k] with 16x16x32 bf16 MFMA: lane
 // (c = lane % 16, kg = lane / 16) supplies x[row c][8 kg ..] and A[rank c][8 kg ..] of a 32-wide k step
-// and receives D[row 4 kg + v][rank c].  d_in is cut into 256-wide stages; stage t belongs to slice
-// t % ksplit.
+// and receives D[row 4 kg + v][rank c].  d_in is cut into 256-wide stages; a slice is a run of
+// consecutive stages.
 // =================================================================================================
 template <int NT>  // 16-rank tiles: ranks up to 16 * NT
 __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, u16* lds)
@@ -128,12 +130,13 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
     // side by side would otherwise sweep the same k range of different rows in step, which (with a
     // power-of-two row pitch) keeps hitting the same few HBM channels.
     const int n_stages = (p.d_in + kStageK - 1) / kStageK;
-    const int n_my = (n_stages - ks + p.ksplit - 1) / p.ksplit;
+    const int n_per = (n_stages + p.ksplit - 1) >> p.ks_log2;  // slice ks = stages [ks n_per, (ks + 1) n_per)
+    const int n_my = max(0, min(n_per, n_stages - ks * n_per));
     const int rot = n_my > 0 ? (int)(((unsigned)u.pos / kTallRows * 5u) % (unsigned)n_my) : 0;
     auto stage_of = [&](int i) {
         i += rot;
         if (i >= n_my) i -= n_my;
-        return ks + i * p.ksplit;
+        return ks * n_per + i;
     };
 
     // staging assignment: 32 threads cover the 512 bytes of one A row, 16 rows per pass
@@ -952,14 +955,14 @@ int shrink_grid()
 
 // A 128-row shrink unit streams its rows at the rate of one compute unit, so a batch has to be cut into
 // enough units for the launch to draw the full HBM rate and to end evenly: d_in is cut into slices (each
-// at least four stages long) as long as that leaves at most one row chunk x slice per workgroup (more
+// at least four stages long) as long as that leaves less than one row chunk x slice per workgroup (more
 // slices cost the expand kernel, which adds them up).  A pure function of host arguments.
 int choose_ksplit(int n_tokens, int seg_bound, int d_in, int grid)
 {
     (void)seg_bound;
     const long long chunks = (n_tokens + kTallRows - 1) / kTallRows;
     int ks = 1;
-    while (ks < ksplit_cap(n_tokens) && chunks * ks * 2 <= grid && d_in >= ks * 2 * 4 * kStageK) ks *= 2;
+    while (ks < ksplit_cap(n_tokens) && chunks * ks * 2 < grid && d_in >= ks * 2 * 4 * kStageK) ks *= 2;
     return ks;
 }
 
