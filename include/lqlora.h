@@ -112,7 +112,7 @@ lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token
  *            nothing is saved (inference-only batches)
  *   variant  one of LQ_VARIANT_*; split and fused give the same y and h_out up to fp32 summation
  *            order; h_out may be written by either half of the split variant
- *   workspace lora_forward_workspace_bytes(...) bytes; its first 256 bytes must be ZERO before the first
+ *   workspace lora_forward_workspace_bytes(...) bytes; its first 4096 bytes must be ZERO before the first
  *            call that uses it (error word, which the library only ORs into, and work counters that
  *            every launch leaves at zero); the rest may hold anything.  n_tokens = 0 returns LQ_OK
  *            with no launch.
@@ -144,7 +144,7 @@ lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ld
  *   dA_ptrs / dB_ptrs  [n_adapters] device arrays of device pointers to float [r_a, d_in] / [r_a, d_out],
  *            accumulated into (caller zeroes); entries may be NULL (that gradient is skipped), and
  *            either table may be NULL; with both NULL only dx is computed
- *   workspace lora_backward_workspace_bytes(...) bytes; its first 256 bytes zero as for the forward.
+ *   workspace lora_backward_workspace_bytes(...) bytes; its first 4096 bytes zero as for the forward.
  *   Four launches: shrink (g), expand (dx), weight-gradient partials, their reduction.  The order of
  *   every sum is fixed, so results are reproducible run to run.
  * ------------------------------------------------------------------------------------------- */

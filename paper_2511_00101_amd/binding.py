@@ -221,7 +221,7 @@ def bits_from_bf16(t: torch.Tensor) -> np.ndarray:
 
 
 def workspace(n_bytes: int, device="cuda") -> torch.Tensor:
-    return torch.zeros((max(n_bytes, 256) + 7) // 8, dtype=torch.int64, device=device)
+    return torch.zeros((max(n_bytes, 4096) + 7) // 8, dtype=torch.int64, device=device)
 
 
 def lora_profile_enable(on: bool) -> None:

@@ -9,7 +9,7 @@
 namespace lq {
 
 constexpr int kWave = 64;
-constexpr int kWsHeaderBytes = 256;   // workspace offset 0: int32 device error flags, rest reserved
+constexpr int kWsHeaderBytes = 4096;  // workspace offset 0: int32 device error flags; ticket and barrier words follow
 constexpr int kErrBadSegment = 1;     // adapter id or rank outside the supported range
 
 typedef unsigned short u16;

@@ -84,6 +84,33 @@ __device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, 
     }
 }
 
+// In the fused variant the h slices cross the barrier between workgroups on different XCDs, whose L2
+// caches are not coherent with each other.  There they are written and read with device-scope accesses,
+// which go past the L2's non-coherent lines, so that the barrier needs no cache write-back or
+// invalidation (measured: those cost ~9 us per barrier with 256 workgroups).
+__device__ __forceinline__ void h_store(float* ptr, float v, bool coherent)
+{
+    if (coherent) __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *ptr = v;
+}
+__device__ __forceinline__ float h_load(const float* ptr, bool coherent)
+{
+    return coherent ? __hip_atomic_load(const_cast<float*>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *ptr;
+}
+__device__ __forceinline__ void h_load8(const float* ptr, bool coherent, f32x4& a, f32x4& b)
+{
+    if (!coherent) {
+        a = *reinterpret_cast<const f32x4*>(ptr);
+        b = *reinterpret_cast<const f32x4*>(ptr + 4);
+    } else {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = h_load(ptr + e, true);
+        a = f32x4{v[0], v[1], v[2], v[3]};
+        b = f32x4{v[4], v[5], v[6], v[7]};
+    }
+}
+
 // Where a shrink unit stores its h values: slice ks of the partial-h buffer.  With ksplit == 1 that is
 // the finished h, and fine-tune segments store it to h_out as well; with ksplit > 1 the expand kernel
 // adds the slices in order (and stores h_out), so no workgroup ever waits for another.
@@ -101,8 +128,9 @@ __device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const
 // finished h of one element: the slices added in order
 __device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j, int parts)
 {
-    float sum = p.hpart[pos * p.rstride + j];
-    for (int part = 1; part < parts; ++part) sum += p.hpart[((long long)part * p.n_tokens + pos) * p.rstride + j];
+    float sum = h_load(p.hpart + pos * p.rstride + j, p.coherent);
+    for (int part = 1; part < parts; ++part)
+        sum += h_load(p.hpart + ((long long)part * p.n_tokens + pos) * p.rstride + j, p.coherent);
     return sum;
 }
 
@@ -224,7 +252,7 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
         for (int v = 0; v < 4; ++v) {
             const int i = w * 16 + kg * 4 + v, j = nt * 16 + c;
             if (i < u.len && j < s.rank) {
-                d.base[(long long)i * p.rstride + j] = acc[nt][v];
+                h_store(d.base + (long long)i * p.rstride + j, acc[nt][v], p.coherent);
                 if (d.save) d.save[(long long)i * d.save_ld + j] = acc[nt][v];
             }
         }
@@ -372,7 +400,7 @@ __device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit
         const int v = r % 4, nt = (r / 4) % NT, mt = r / (4 * NT);
         const int i = mt * 16 + (l >> 4) * 4 + v, jj = nt * 16 + (l & 15);
         if (i < u.len && jj < s.rank) {
-            d.base[(long long)i * p.rstride + jj] = sum;
+            h_store(d.base + (long long)i * p.rstride + jj, sum, p.coherent);
             if (d.save) d.save[(long long)i * d.save_ld + jj] = sum;
         }
     }
@@ -459,8 +487,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
             const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
             // (rank groups beyond the adapter's re-read its last one; they are zeroed below)
             hp[it] = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * min(jg, (s.rank - 1) >> 3);
-            h0[it] = *reinterpret_cast<const f32x4*>(hp[it]);
-            h1[it] = *reinterpret_cast<const f32x4*>(hp[it] + 4);
+            h_load8(hp[it], p.coherent, h0[it], h1[it]);
         }
         for (int part = 1; part < parts; ++part) {
             const long long off = (long long)part * p.n_tokens * p.rstride;
@@ -468,8 +495,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
                 if (it * kThreads >= n_items) break;
-                a0[it] = *reinterpret_cast<const f32x4*>(hp[it] + off);
-                a1[it] = *reinterpret_cast<const f32x4*>(hp[it] + off + 4);
+                h_load8(hp[it] + off, p.coherent, a0[it], a1[it]);
             }
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
@@ -771,13 +797,22 @@ __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
 }
 
+// What the expand phase works out from the segment tables before it touches any data: the rows per long
+// unit, the classes of units and their prefix sums.  (The fused kernel does this before its barrier.)
+struct ExpandPlan {
+    int per, long_blocks, n_chunks, short_blocks, n_short;
+    LenClass shorts, full, big, little;
+    ClassScan cf, cb, cl, cs;
+};
+
 template <int KSTEPS, int PAIRS>
-__device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdParams>& sg, unsigned char* lds_raw,
-                                             ShortLds& sh, int* s_slot)
+__device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs<FwdParams>& sg)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
-    const LenClass shorts{1, kLongMin, p.kinds}, longs{kLongMin, kBig, p.kinds};
-    const int long_blocks = (p.d_out + C::UN - 1) / C::UN;
+    ExpandPlan e;
+    const LenClass longs{kLongMin, kBig, p.kinds};
+    e.shorts = LenClass{1, kLongMin, p.kinds};
+    e.long_blocks = (p.d_out + C::UN - 1) / C::UN;
 
     // Rows per long unit: CT when that still gives every workgroup a couple of units, else fewer (down to 64:
     // the B block is staged once per unit), so that a batch with few rows is still spread over the whole machine.
@@ -792,31 +827,60 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
             segs += wave_sum(in ? 1 : 0);
         }
         if (sg.n_seg > kCachedBatches * kWave) rows = kBig / 2;  // many segments: plenty of units anyway
-        while (per > 64 && ((long long)(rows / per + segs) * long_blocks < 2LL * (int)gridDim.x)) per >>= 1;
+        while (per > 64 && ((long long)(rows / per + segs) * e.long_blocks < 2LL * (int)gridDim.x)) per >>= 1;
     }
-    const LenClass full{per + 1, kBig, p.kinds, true}, big{per / 2, per + 1, p.kinds}, little{kLongMin, per / 2, p.kinds};
+    e.per = per;
+    e.full = LenClass{per + 1, kBig, p.kinds, true};
+    e.big = LenClass{per / 2, per + 1, p.kinds};
+    e.little = LenClass{kLongMin, per / 2, p.kinds};
+    e.cf = scan_class(p, sg, per, e.full);
+    e.cb = scan_class(p, sg, per, e.big);
+    e.cl = scan_class(p, sg, per, e.little);
+    e.n_chunks = e.cf.total + e.cb.total + e.cl.total;
+    e.cs = scan_class(p, sg, kTT, e.shorts);
+    e.short_blocks = (p.d_out + kShortN - 1) / kShortN;
+    e.n_short = e.cs.total * e.short_blocks;
+    return e;
+}
 
-    // short units first (their cost is mostly latency, which the start of a launch has to spare): one
-    // per wave iteration, dealt round-robin over the workgroups first so that a few hundred units spread
-    // over all compute units
-    const ClassScan cf = scan_class(p, sg, per, full), cb = scan_class(p, sg, per, big), cl = scan_class(p, sg, per, little);
-    const int n_chunks = cf.total + cb.total + cl.total;
+// Short units: one per wave iteration.  Without long units they are dealt over the workgroups first (all
+// compute units pull data); with long units they are packed eight to a workgroup, so that the other
+// workgroups start streaming at once.
+__device__ __forceinline__ int first_short_unit(const ExpandPlan& e)
+{
+    const int w = uniform((int)threadIdx.x / kWave);
+    return e.n_chunks > 0 ? (int)blockIdx.x * kWaves + w : w * (int)gridDim.x + (int)blockIdx.x;
+}
+__device__ __forceinline__ bool find_short_unit(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e, int id,
+                                                Unit& u, SegInfo& s, int& n_block)
+{
+    const int chunk = small_div(id, e.short_blocks);
+    n_block = id - chunk * e.short_blocks;
+    return find_unit(p, sg, e.cs, chunk, kTT, e.shorts, u, s);
+}
+
+template <int KSTEPS, int PAIRS>
+__device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e,
+                                             unsigned char* lds_raw, ShortLds& sh, int* s_slot)
+{
+    const int per = e.per, long_blocks = e.long_blocks, n_chunks = e.n_chunks;
+    const LenClass& full = e.full;
+    const LenClass& big = e.big;
+    const LenClass& little = e.little;
+    const ClassScan& cf = e.cf;
+    const ClassScan& cb = e.cb;
+    const ClassScan& cl = e.cl;
+
+    // short units first (their cost is mostly latency, which the start of a launch has to spare)
     {
-        const ClassScan cs = scan_class(p, sg, kTT, shorts);
-        const int short_blocks = (p.d_out + kShortN - 1) / kShortN;
-        const int n_short = cs.total * short_blocks;
-        const int w = uniform((int)threadIdx.x / kWave);
-        // without long units the short ones are dealt over the workgroups first (all compute units pull
-        // data); with long units they are packed eight to a workgroup, so that the other workgroups
-        // start streaming at once
-        const int first = n_chunks > 0 ? (int)blockIdx.x * kWaves + w : w * (int)gridDim.x + (int)blockIdx.x;
-        for (int id = first; id < n_short; id += kWaves * (int)gridDim.x) {
+        const int first = first_short_unit(e);
+        for (int id = first; id < e.n_short; id += kWaves * (int)gridDim.x) {
             Unit u;
             SegInfo s;
+            int n_block;
             u.it = 4;
-            const int chunk = small_div(id, short_blocks);
-            if (!find_unit(p, sg, cs, chunk, kTT, shorts, u, s)) continue;
-            expand_short_unit(p, u, s, id - chunk * short_blocks, sh);
+            if (!find_short_unit(p, sg, e, id, u, s, n_block)) continue;
+            expand_short_unit(p, u, s, n_block, sh);
         }
     }
     LQ_STAMP_WAIT(1, 39);
@@ -859,7 +923,8 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
     LQ_STAMP(1, 0);
     const Segs<FwdParams> sg = load_segs(p);
     LQ_STAMP(1, 1);
-    expand_phase<KSTEPS, PAIRS>(p, sg, lds_raw, sh, s_slot);
+    const ExpandPlan plan = plan_expand<KSTEPS, PAIRS>(p, sg);
+    expand_phase<KSTEPS, PAIRS>(p, sg, plan, lds_raw, sh, s_slot);
 }
 
 // =================================================================================================
@@ -868,37 +933,52 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
 // its expand units.  The grid is exactly the number of workgroups that are resident at once, so every
 // workgroup reaches the barrier; the wait is bounded all the same, and a timeout is reported in the
 // workspace error word instead of hanging.
-//   tickets[4] = arrivals (back to zero when the last workgroup arrives), tickets[5] = generation.
+//   (header words: see kBarGen, kBarTop, kBarSub)
 // =================================================================================================
 constexpr int kErrBarrierTimeout = 2;
 constexpr int kBarrierSpinLimit = 1 << 20;
 
-__device__ __forceinline__ void grid_barrier(const FwdParams& p, int gen0)
+// Words of the workspace header used by the barrier, every counter on a 128-byte line of its own: 256
+// arrivals on one word take ~5 us (additions to one address are served one after the other), so a
+// workgroup arrives at one of 16 counters, and the last one at each of those arrives at the top counter.
+// All counters are back at zero when the barrier opens.
+constexpr int kBarGen = 32, kBarTop = 64, kBarSub = 96, kBarLine = 32, kBarFan = 16;  // int offsets from the header
+
+// `overlap` runs in every thread between the workgroup's arrival and its wait for the others.
+template <class Overlap>
+__device__ __forceinline__ void grid_barrier(const FwdParams& p, int gen0, Overlap&& overlap)
 {
+    // every thread's h stores (device-scope, written through) are acknowledged before its workgroup arrives
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        int* arrive = p.tickets + 4;
-        int* gen = p.tickets + 5;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // this workgroup's h stores, once per workgroup
-        const int before = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (before == (int)gridDim.x - 1) {
-            __hip_atomic_store(arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            // Poll with relaxed loads: an acquire per poll would invalidate caches that the workgroups
-            // still in the shrink phase are using.
-            int spins = 0;
-            while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
-                __builtin_amdgcn_s_sleep(16);
-                if (++spins > kBarrierSpinLimit) {
-                    atomicOr(p.err, kErrBarrierTimeout);
-                    break;
-                }
+        int* gen = p.err + kBarGen;
+        const int grid = (int)gridDim.x, k = (int)blockIdx.x % kBarFan;
+        const int n_k = (grid - k + kBarFan - 1) / kBarFan, n_sub = min(grid, kBarFan);
+        int* sub = p.err + kBarSub + k * kBarLine;
+        if (__hip_atomic_fetch_add(sub, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_k - 1) {
+            __hip_atomic_store(sub, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int* top = p.err + kBarTop;
+            if (__hip_atomic_fetch_add(top, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_sub - 1) {
+                __hip_atomic_store(top, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // other workgroups' h stores
+    }
+    overlap();
+    if (threadIdx.x == 0) {
+        int* gen = p.err + kBarGen;
+        int spins = 0;
+        while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
+            __builtin_amdgcn_s_sleep(8);
+            if (++spins > kBarrierSpinLimit) {
+                atomicOr(p.err, kErrBarrierTimeout);
+                break;
+            }
+        }
     }
     __syncthreads();
+    asm volatile("" ::: "memory");  // the h loads of the expand phase stay behind the barrier
 }
 
 template <int NT, int KSTEPS, int PAIRS>
@@ -911,13 +991,15 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     const Segs<FwdParams> sg = load_segs(p);
     // The generation is read before this workgroup arrives, hence before the last arrival can change it;
     // and after the table loads, so that their results need not wait for this slower, uncached load.
-    const int gen0 = __hip_atomic_load(p.tickets + 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int gen0 = __hip_atomic_load(p.err + kBarGen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
     LQ_STAMP(1, 0);
-    grid_barrier(p, gen0);
+    // the expand phase's plan depends only on the tables: it is worked out while the workgroup waits
+    ExpandPlan plan;
+    grid_barrier(p, gen0, [&]() { plan = plan_expand<KSTEPS, PAIRS>(p, sg); });
     LQ_STAMP(1, 1);
-    expand_phase<KSTEPS, PAIRS>(p, sg, lds_raw, sh, s_slot);
+    expand_phase<KSTEPS, PAIRS>(p, sg, plan, lds_raw, sh, s_slot);
 }
 
 int log2_of(int v)  // v is a power of two
@@ -1049,7 +1131,7 @@ extern "C" int lq_trace_read(unsigned long long* host, int n_words)
 }
 #endif
 
-// workspace: [header 256 B][hpart: cap x n_tokens x rstride floats]
+// workspace: [header 4096 B][hpart: cap x n_tokens x rstride floats]
 extern "C" size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,
                                                int32_t variant)
 {
@@ -1107,5 +1189,6 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
 
     p.ksplit_hint = 0;
     p.kinds = kAllKinds;
+    p.coherent = variant == LQ_VARIANT_FUSED;
     return run_shrink_expand(p, variant, seg_bound, static_cast<hipStream_t>(stream)) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }
