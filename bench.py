@@ -309,7 +309,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--variant", choices=["split", "fused"], default="split")
+    ap.add_argument("--variant", choices=["auto", "split", "fused"], default="auto",
+                    help="auto: the single-launch variant for batches of up to 1024 tokens (one launch less is worth "
+                         "more than its barrier costs there), two launches above")
     ap.add_argument("--workload", default="cfg2", help="headline workload: cfg1, cfg2, cfg3, cfg4up, cfg4down")
     ap.add_argument("--others", default="cfg3,cfg4up,cfg4down,cfg5", help="comma list of further workloads ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -338,19 +340,23 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps(dict(copy_bytes_read=src.numel(), copy_bytes_written=dst.numel(), copies=8)))
         return
-    variant = lq.LQ_VARIANT_FUSED if args.variant == "fused" else lq.LQ_VARIANT_SPLIT
+    def variant_for(problem):
+        if args.variant == "auto":
+            return lq.LQ_VARIANT_FUSED if problem.n_tokens <= 1024 else lq.LQ_VARIANT_SPLIT
+        return lq.LQ_VARIANT_FUSED if args.variant == "fused" else lq.LQ_VARIANT_SPLIT
     makers = dict(cfg1=synth.config1, cfg2=synth.config2, cfg3=synth.config3,
                   cfg4up=lambda: synth.config4("up"), cfg4down=lambda: synth.config4("down"))
 
     p = makers[args.workload]()
+    variant = variant_for(p)
     head = measure(p, variant, args.steps, args.warmup)
     others = []
     for name in [n for n in args.others.split(",") if n and n != args.workload]:
         if name == "cfg5":
-            others.append(measure_layer_stack(variant, 3, 1))
+            others.append(measure_layer_stack(lq.LQ_VARIANT_SPLIT if args.variant != "fused" else lq.LQ_VARIANT_FUSED, 3, 1))
             continue
         q = makers[name]()
-        others.append(measure(q, variant, max(20, args.steps // 4), max(5, args.warmup // 2)))
+        others.append(measure(q, variant_for(q), max(20, args.steps // 4), max(5, args.warmup // 2)))
         del q
     cpu = None if args.no_cpu_baseline else cpu_baseline(p)
 
@@ -359,7 +365,8 @@ def main():
         ms_per_step=head["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
         data="synthetic",
         config=dict(workload=f"{head['workload']}: {head['tokens']} tokens, {head['d_in']}->{head['d_out']}, "
-                             f"{p.n_adapters} adapters rank {int(p.ranks.max())}", variant=args.variant,
+                             f"{p.n_adapters} adapters rank {int(p.ranks.max())}",
+                    variant="fused" if variant == lq.LQ_VARIANT_FUSED else "split",
                     replicas=head["replicas"], step="segment builder + forward"),
         roofline=head["roofline"], cpu_baseline=cpu,
         forward=dict(us=head["forward_us"], gbps=head["forward_gbps"], tflops=head["forward_tflops"],
