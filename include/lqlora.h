@@ -112,6 +112,8 @@ lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token
  *            nothing is saved (inference-only batches)
  *   variant  one of LQ_VARIANT_*; split and fused give the same y and h_out up to fp32 summation
  *            order; h_out may be written by either half of the split variant
+ *            (LQ_VARIANT_FUSED: LQ_ERR_UNSUPPORTED if the workspace's partial-h region would reach 2 GiB,
+ *            i.e. beyond about 4 million tokens at rank 128)
  *   workspace lora_forward_workspace_bytes(...) bytes; its first 4096 bytes must be ZERO before the first
  *            call that uses it (error word, which the library only ORs into, and work counters that
  *            every launch leaves at zero); the rest may hold anything.  n_tokens = 0 returns LQ_OK

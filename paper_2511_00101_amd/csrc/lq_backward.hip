@@ -387,7 +387,7 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     s1.hpart = reinterpret_cast<float*>(ws + kWsHeaderBytes);
     s1.ksplit = 1; s1.rstride = rstride_for(max_rank);
     s1.err = reinterpret_cast<int*>(ws); s1.tickets = reinterpret_cast<int*>(ws) + 4;
-    s1.ksplit_hint = 0; s1.kinds = kFinetuneOnly; s1.coherent = 0;
+    s1.ksplit_hint = 0; s1.kinds = kFinetuneOnly; s1.coherent = 0; s1.hpart_bytes = 0;
     if (run_shrink_expand(s1, LQ_VARIANT_SHRINK_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
 
     // 2. dx += s g A on fine-tune rows: the forward's expand over d_in against A, with the same k split.  Whichever

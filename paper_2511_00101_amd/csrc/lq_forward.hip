@@ -97,17 +97,19 @@ __device__ __forceinline__ float h_load(const float* ptr, bool coherent)
 {
     return coherent ? __hip_atomic_load(const_cast<float*>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *ptr;
 }
-__device__ __forceinline__ void h_load8(const float* ptr, bool coherent, f32x4& a, f32x4& b)
+// eight consecutive floats of hpart (16-byte aligned).  The device-scope form is a buffer load with the sc1
+// cache policy: plain C++ has no 16-byte atomic load.
+__device__ __forceinline__ void h_load8(const FwdParams& p, const float* ptr, f32x4& a, f32x4& b)
 {
-    if (!coherent) {
+    if (!p.coherent) {
         a = *reinterpret_cast<const f32x4*>(ptr);
         b = *reinterpret_cast<const f32x4*>(ptr + 4);
     } else {
-        float v[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = h_load(ptr + e, true);
-        a = f32x4{v[0], v[1], v[2], v[3]};
-        b = f32x4{v[4], v[5], v[6], v[7]};
+        constexpr int kRawBuffer = 0x00020000, kSc1 = 16;  // descriptor word 3 (raw 32-bit data); cache policy bit
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(p.hpart, 0, (int)p.hpart_bytes, kRawBuffer);
+        const int off = (int)(reinterpret_cast<const char*>(ptr) - reinterpret_cast<const char*>(p.hpart));
+        a = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kSc1));
+        b = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + 16, 0, kSc1));
     }
 }
 
@@ -487,7 +489,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
             const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
             // (rank groups beyond the adapter's re-read its last one; they are zeroed below)
             hp[it] = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * min(jg, (s.rank - 1) >> 3);
-            h_load8(hp[it], p.coherent, h0[it], h1[it]);
+            h_load8(p, hp[it], h0[it], h1[it]);
         }
         for (int part = 1; part < parts; ++part) {
             const long long off = (long long)part * p.n_tokens * p.rstride;
@@ -495,7 +497,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
                 if (it * kThreads >= n_items) break;
-                h_load8(hp[it] + off, p.coherent, a0[it], a1[it]);
+                h_load8(p, hp[it] + off, a0[it], a1[it]);
             }
 #pragma unroll
             for (int it = 0; it < ITEMS; ++it) {
@@ -1166,6 +1168,8 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     if (!workspace || workspace_bytes < lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) ||
         !aligned16(workspace))
         return LQ_ERR_WORKSPACE;
+    // the fused variant addresses the partial-h region through a buffer descriptor with 32-bit offsets
+    if (variant == LQ_VARIANT_FUSED && h_slices_bytes(n_tokens, max_rank) > 0x7fffffffull) return LQ_ERR_UNSUPPORTED;
     if (n_tokens == 0 || max_segments == 0) return LQ_OK;
 
     FwdParams p;
@@ -1190,5 +1194,6 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     p.ksplit_hint = 0;
     p.kinds = kAllKinds;
     p.coherent = variant == LQ_VARIANT_FUSED;
+    p.hpart_bytes = (unsigned int)h_slices_bytes(n_tokens, max_rank);
     return run_shrink_expand(p, variant, seg_bound, static_cast<hipStream_t>(stream)) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }

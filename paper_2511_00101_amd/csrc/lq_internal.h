@@ -27,6 +27,7 @@ struct FwdParams {
     int ksplit_hint; // host only: > 0 forces this split (the expand half of a pair repeats the shrink half's)
     int kinds;       // bit k set: segments of kind k take part (forward: all; backward: fine-tune only)
     int coherent;    // fused variant: the h slices are written and read with device-scope accesses
+    unsigned int hpart_bytes;  // size of hpart (for the buffer descriptor of the device-scope 16-byte loads)
     int* tickets;    // workspace header words 4..9: unit tickets of the two phases and the fused variant's barrier
 };
 

@@ -301,22 +301,6 @@ __device__ __forceinline__ int row_of(const P& p, int pos)
     return (row >= 0 && row < p.n_tokens) ? row : -1;
 }
 
-// Workgroup b runs on XCD b % 8 (round-robin dispatch).  Giving each XCD one contiguous eighth of the
-// unit ids keeps units that share an adapter (or a row range) on one L2 instead of eight.
-constexpr int kXcds = 8;
-struct UnitRange { int first, last, step, start; };
-__device__ __forceinline__ UnitRange xcd_unit_range(int n_units)
-{
-    const int n_xcd = (int)gridDim.x % kXcds == 0 ? kXcds : 1;
-    const int per_xcd = (n_units + n_xcd - 1) / n_xcd;
-    UnitRange r;
-    r.first = ((int)blockIdx.x % n_xcd) * per_xcd;
-    r.last = min(n_units, r.first + per_xcd);
-    r.step = (int)gridDim.x / n_xcd;
-    r.start = r.first + (int)blockIdx.x / n_xcd;
-    return r;
-}
-
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
 
 }  // namespace lq
