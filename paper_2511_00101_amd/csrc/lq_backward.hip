@@ -108,7 +108,7 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
     const int y_row = (int)threadIdx.x / 16, y_piece = (int)threadIdx.x % 16;
     // the unit's rows of h_saved (for dB) or of g (for dA); both are [row][rank] per segment
     const float* hsrc = (for_b ? p.h_saved : p.g) + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * rank;
-    constexpr int DEPTH = NT <= 2 ? 4 : NT == 4 ? 2 : 1;  // steps in flight (as many as the registers allow)
+    constexpr int DEPTH = NT == 1 ? 4 : NT == 2 ? 3 : NT == 4 ? 2 : 1;  // steps in flight (as many as the registers allow)
     u32x4 gy[DEPTH][YQ];
     float gh[DEPTH][NT];
     // all loads are unconditional (clamped addresses), so the number in flight is static; what lies
@@ -207,8 +207,10 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
             }
 }
 
+// (ranks up to 32: at most 128 registers, so that two workgroups share a compute unit and one's loads
+// overlap the other's barriers)
 template <int NT>
-__global__ __launch_bounds__(kThreads) void wgrad_kernel(BwdParams p)
+__global__ __launch_bounds__(kThreads, NT <= 2 ? 4 : 2) void wgrad_kernel(BwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     LQ_STAMP(0, 0);
