@@ -142,10 +142,14 @@ __device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j,
 // and receives D[row 4 kg + v][rank c].  d_in is cut into 256-wide stages; a slice is a run of
 // consecutive stages.
 // =================================================================================================
-template <int NT>  // 16-rank tiles: ranks up to 16 * NT
-__device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, u16* lds)
+// ROWWISE: x is loaded row-wise (an instruction covers 2 rows x 512 contiguous bytes, which streams from HBM
+// up to a quarter faster than the MFMA layout's 16 rows x 64 bytes when few units share a compute unit) and
+// reaches the MFMA layout through a slab of LDS that belongs to the wave (`slabs`: 8 x 16 rows).
+template <int NT, bool ROWWISE>  // 16-rank tiles: ranks up to 16 * NT
+__device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, u16* lds,
+                                                 u16* slabs)
 {
-    constexpr int PITCH = kStageK + 8;           // elements per staged A row (16-byte aligned, bank spread)
+    constexpr int PITCH = kStageK + 8;           // elements per staged A row or slab row (16-byte aligned, bank spread)
     constexpr int BUF = NT * 16 * PITCH;         // elements per stage buffer
     constexpr int NB = kStageK / kBlockK;        // x blocks per stage
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, kg = lane >> 4;
@@ -155,6 +159,16 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
     const int row = i_row < u.len ? row_of(p, u.pos + i_row) : -1;
     const int safe_row = max(row_of(p, u.pos), 0);
     const u16* xrow = p.x + (long long)(row >= 0 ? row : safe_row) * p.ldx;
+    // row-wise: instruction i of a stage covers rows 2 i and 2 i + 1 of the wave's 16, 32 lanes each
+    const u16* xrw[ROWWISE ? 8 : 1];
+    u16* slab = slabs + w * 16 * PITCH;
+    if constexpr (ROWWISE) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = __shfl(row, 2 * i + (lane >> 5), kWave);  // lane c of the wave holds the wave's row c
+            xrw[i] = p.x + (long long)(r >= 0 ? r : safe_row) * p.ldx + (lane & 31) * 8;
+        }
+    }
 
     // Stages of this slice, visited from a tile-dependent start with wrap-around: workgroups that run
     // side by side would otherwise sweep the same k range of different rows in step, which (with a
@@ -188,27 +202,49 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
     // x of a whole stage (4 blocks of 64 k) for this wave's 16 rows.  Past d_in the address is clamped
     // into the row; the staged A is zero there, so those products vanish.
     auto xload = [&](int stage, u32x4 (&xv)[NB][2]) {
-        const int k0 = stage * kStageK + kg * 8;
+        if constexpr (ROWWISE) {
+            // (a lane's 8 columns lie wholly inside or wholly beyond d_in; beyond, it re-reads column 0)
+            const int k0 = stage * kStageK + (lane & 31) * 8 < p.d_in ? stage * kStageK : -(lane & 31) * 8;
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+            for (int i = 0; i < 8; ++i) xv[i >> 1][i & 1] = *reinterpret_cast<const u32x4*>(xrw[i] + k0);
+        } else {
+            const int k0 = stage * kStageK + kg * 8;
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
-                xv[b][q] = *reinterpret_cast<const u32x4*>(xrow + min(k0 + b * kBlockK + 32 * q, p.d_in - 8));
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    xv[b][q] = *reinterpret_cast<const u32x4*>(xrow + min(k0 + b * kBlockK + 32 * q, p.d_in - 8));
+        }
     };
     f32x4 acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     auto mma = [&](const u32x4 (&xv)[NB][2], int buf) {
+        if constexpr (ROWWISE) {  // the stage's x into the wave's slab as it was loaded: row 2 i + lane / 32
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                *reinterpret_cast<u32x4*>(slab + (2 * i + (lane >> 5)) * PITCH + (lane & 31) * 8) = xv[i >> 1][i & 1];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+            for (int q = 0; q < 2; ++q) {
+                u32x4 xf = xv[b][q];
+                if constexpr (ROWWISE) xf = *reinterpret_cast<const u32x4*>(slab + c * PITCH + b * kBlockK + 32 * q + kg * 8);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     const u32x4 af = *reinterpret_cast<const u32x4*>(lds + buf * BUF + (nt * 16 + c) * PITCH +
                                                                      b * kBlockK + 32 * q + kg * 8);
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(xv[b][q]), as_bf16x8(af), acc[nt], 0, 0, 0);
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(xf), as_bf16x8(af), acc[nt], 0, 0, 0);
                 }
+            }
+        if constexpr (ROWWISE) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();  // the slab is rewritten at the next stage
+        }
     };
 
     // Pipeline: while stage i is multiplied out of LDS (A) and registers (x), the A piece of stage i + 1
@@ -822,7 +858,9 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
 template <int NT>
 constexpr size_t shrink_lds_bytes()
 {
-    const size_t tall = (size_t)2 * NT * 16 * (kStageK + 8) * sizeof(u16);
+    // two stage buffers of A, and (kernels for ranks up to 64) the eight waves' x slabs
+    const size_t tall = (size_t)2 * NT * 16 * (kStageK + 8) * sizeof(u16) +
+                        (NT <= 4 ? (size_t)kWaves * 16 * (kStageK + 8) * sizeof(u16) : 0);
     const size_t small = (size_t)kWaves * (kShortRows / 16) * NT * 4 * kWave * sizeof(float);
     return tall > small ? tall : small;
 }
@@ -855,10 +893,13 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdP
         u16* lds_a = reinterpret_cast<u16*>(lds_raw);
         float* lds_r = reinterpret_cast<float*>(lds_raw);
         if (is_tall) {
-            if (NT >= 8 && s.rank > 64) shrink_tall_unit<(NT >= 8 ? 8 : NT)>(p, u, s, ks, lds_a);
-            else if (NT >= 4 && s.rank > 32) shrink_tall_unit<(NT >= 4 ? 4 : NT)>(p, u, s, ks, lds_a);
-            else if (NT >= 2 && s.rank > 16) shrink_tall_unit<(NT >= 2 ? 2 : NT)>(p, u, s, ks, lds_a);
-            else shrink_tall_unit<1>(p, u, s, ks, lds_a);
+            // row-wise x for ranks up to 32, in the kernels whose LDS has room for the slabs
+            constexpr bool RW = NT <= 4;
+            u16* slabs = lds_a + 2 * NT * 16 * (kStageK + 8);
+            if (NT >= 8 && s.rank > 64) shrink_tall_unit<(NT >= 8 ? 8 : NT), false>(p, u, s, ks, lds_a, slabs);
+            else if (NT >= 4 && s.rank > 32) shrink_tall_unit<(NT >= 4 ? 4 : NT), RW>(p, u, s, ks, lds_a, slabs);
+            else if (NT >= 2 && s.rank > 16) shrink_tall_unit<(NT >= 2 ? 2 : NT), RW>(p, u, s, ks, lds_a, slabs);
+            else shrink_tall_unit<1, RW>(p, u, s, ks, lds_a, slabs);
         } else {
             if (NT >= 8 && s.rank > 64) shrink_short_unit<(NT >= 8 ? 8 : NT)>(p, u, s, ks, lds_r);
             else if (NT >= 4 && s.rank > 32) shrink_short_unit<(NT >= 4 ? 4 : NT)>(p, u, s, ks, lds_r);
