@@ -147,8 +147,8 @@ lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ld
  *            accumulated into (caller zeroes); entries may be NULL (that gradient is skipped), and
  *            either table may be NULL; with both NULL only dx is computed
  *   workspace lora_backward_workspace_bytes(...) bytes; its first 4096 bytes zero as for the forward.
- *   Four launches: shrink (g), expand (dx), weight-gradient partials, their reduction.  The order of
- *   every sum is fixed, so results are reproducible run to run.
+ *   Three launches: g and dx (shrink and expand in one launch), weight-gradient partials, their reduction.
+ *   The order of every sum is fixed, so results are reproducible run to run.
  * ------------------------------------------------------------------------------------------- */
 size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in,
                                      int32_t d_out);

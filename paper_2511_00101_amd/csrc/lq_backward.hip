@@ -389,13 +389,19 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     s1.hpart = reinterpret_cast<float*>(ws + kWsHeaderBytes);
     s1.ksplit = 1; s1.rstride = rstride_for(max_rank);
     s1.err = reinterpret_cast<int*>(ws); s1.tickets = reinterpret_cast<int*>(ws) + 4;
-    s1.ksplit_hint = 0; s1.kinds = kFinetuneOnly; s1.coherent = 0; s1.hpart_bytes = 0;
-    if (run_shrink_expand(s1, LQ_VARIANT_SHRINK_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
-
-    // 2. dx += s g A on fine-tune rows: the forward's expand over d_in against A, with the same k split.  Whichever
-    // of the two kernels finishes g (the shrink without a split, the expand with one) also stores it to gsum.
-    s1.ksplit_hint = s1.ksplit;
-    if (run_shrink_expand(s1, LQ_VARIANT_EXPAND_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+    s1.ksplit_hint = 0; s1.kinds = kFinetuneOnly;
+    // 2. dx += s g A on fine-tune rows: the forward's expand over d_in against A.  Both in the single-launch
+    // variant when its buffer descriptor can address the slices (else two launches with the same k split).
+    // Whichever phase finishes g (the shrink without a split, the expand with one) also stores it to gsum.
+    const bool one_launch = h_slices_bytes(n_tokens, max_rank) <= 0x7fffffffull;
+    s1.coherent = one_launch; s1.hpart_bytes = one_launch ? (unsigned int)h_slices_bytes(n_tokens, max_rank) : 0;
+    if (one_launch) {
+        if (run_shrink_expand(s1, LQ_VARIANT_FUSED, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+    } else {
+        if (run_shrink_expand(s1, LQ_VARIANT_SHRINK_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+        s1.ksplit_hint = s1.ksplit;
+        if (run_shrink_expand(s1, LQ_VARIANT_EXPAND_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+    }
 
     // 3. partial weight gradients (from x, dy, the saved h and the finished g), then their reduction into dA / dB
     if (dA_ptrs || dB_ptrs) {

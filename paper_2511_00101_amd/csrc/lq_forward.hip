@@ -1059,52 +1059,6 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
 // workspace error word instead of hanging.
 //   (header words: see kBarGen, kBarTop, kBarSub)
 // =================================================================================================
-constexpr int kErrBarrierTimeout = 2;
-constexpr int kBarrierSpinLimit = 1 << 20;
-
-// Words of the workspace header used by the barrier, every counter on a 128-byte line of its own: 256
-// arrivals on one word take ~5 us (additions to one address are served one after the other), so a
-// workgroup arrives at one of 16 counters, and the last one at each of those arrives at the top counter.
-// All counters are back at zero when the barrier opens.
-constexpr int kBarGen = 32, kBarTop = 64, kBarSub = 96, kBarLine = 32, kBarFan = 16;  // int offsets from the header
-
-// `overlap` runs in every thread between the workgroup's arrival and its wait for the others.
-template <class Overlap>
-__device__ __forceinline__ void grid_barrier(const FwdParams& p, int gen0, Overlap&& overlap)
-{
-    // every thread's h stores (device-scope, written through) are acknowledged before its workgroup arrives
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int* gen = p.err + kBarGen;
-        const int grid = (int)gridDim.x, k = (int)blockIdx.x % kBarFan;
-        const int n_k = (grid - k + kBarFan - 1) / kBarFan, n_sub = min(grid, kBarFan);
-        int* sub = p.err + kBarSub + k * kBarLine;
-        if (__hip_atomic_fetch_add(sub, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_k - 1) {
-            __hip_atomic_store(sub, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            int* top = p.err + kBarTop;
-            if (__hip_atomic_fetch_add(top, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_sub - 1) {
-                __hip_atomic_store(top, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-    }
-    overlap();
-    if (threadIdx.x == 0) {
-        int* gen = p.err + kBarGen;
-        int spins = 0;
-        while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
-            __builtin_amdgcn_s_sleep(8);
-            if (++spins > kBarrierSpinLimit) {
-                atomicOr(p.err, kErrBarrierTimeout);
-                break;
-            }
-        }
-    }
-    __syncthreads();
-    asm volatile("" ::: "memory");  // the h loads of the expand phase stay behind the barrier
-}
-
 template <int NT, int KSTEPS, int PAIRS>
 __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
 {
@@ -1121,7 +1075,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     LQ_STAMP(1, 0);
     // the expand phase's plan depends only on the tables: it is worked out while the workgroup waits
     ExpandPlan plan;
-    grid_barrier(p, gen0, [&]() { plan = plan_expand<KSTEPS, PAIRS>(p, sg); });
+    grid_barrier(p.err, gen0, [&]() { plan = plan_expand<KSTEPS, PAIRS>(p, sg); });
     LQ_STAMP(1, 1);
     expand_phase<KSTEPS, PAIRS>(p, sg, plan, lds_raw, sh, s_slot);
 }

@@ -42,6 +42,57 @@ size_t h_slices_bytes(int n_tokens, int max_rank);   // bytes of the partial-h r
 // p.ksplit_hint > 0 forces that split (the expand half of a pair must use the shrink half's value).
 hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream_t stream);
 
+// ---- device-wide barrier of a launch whose workgroups are all resident (grid = occupancy x compute units) ----
+// Data that crosses it must be written and read with device-scope accesses (the XCDs' L2 caches are not
+// coherent with each other); the barrier itself uses no cache write-back or invalidation.  header: the
+// workspace header (error word at 0); gen0: the generation word read before this workgroup arrives.  The
+// wait is bounded; a timeout sets bit 1 of the error word.
+constexpr int kErrBarrierTimeout = 2;
+constexpr int kBarrierSpinLimit = 1 << 20;
+
+// Words of the workspace header used by the barrier, every counter on a 128-byte line of its own: 256
+// arrivals on one word take ~5 us (additions to one address are served one after the other), so a
+// workgroup arrives at one of 16 counters, and the last one at each of those arrives at the top counter.
+// All counters are back at zero when the barrier opens.
+constexpr int kBarGen = 32, kBarTop = 64, kBarSub = 96, kBarLine = 32, kBarFan = 16;  // int offsets from the header
+
+// `overlap` runs in every thread between the workgroup's arrival and its wait for the others.
+template <class Overlap>
+__device__ __forceinline__ void grid_barrier(int* header, int gen0, Overlap&& overlap)
+{
+    // every thread's device-scope (written-through) stores are acknowledged before its workgroup arrives
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int* gen = header + kBarGen;
+        const int grid = (int)gridDim.x, k = (int)blockIdx.x % kBarFan;
+        const int n_k = (grid - k + kBarFan - 1) / kBarFan, n_sub = min(grid, kBarFan);
+        int* sub = header + kBarSub + k * kBarLine;
+        if (__hip_atomic_fetch_add(sub, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_k - 1) {
+            __hip_atomic_store(sub, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int* top = header + kBarTop;
+            if (__hip_atomic_fetch_add(top, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_sub - 1) {
+                __hip_atomic_store(top, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    overlap();
+    if (threadIdx.x == 0) {
+        int* gen = header + kBarGen;
+        int spins = 0;
+        while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
+            __builtin_amdgcn_s_sleep(8);
+            if (++spins > kBarrierSpinLimit) {
+                atomicOr(header, kErrBarrierTimeout);
+                break;
+            }
+        }
+    }
+    __syncthreads();
+    asm volatile("" ::: "memory");  // loads of the next phase stay behind the barrier
+}
+
 // ---- optional timing of the library's own launches (lora_profile_enable / lora_profile_read) ----------------
 // When enabled, a launch goes through hipExtLaunchKernelGGL with a pair of events that receive the
 // dispatch's own start and end time stamps (what a kernel trace reports), and is filed under its id.
