@@ -102,11 +102,15 @@ constexpr int kTraceSlots = 40, kTraceGroups = 1024;
         if (threadIdx.x == 0 && blockIdx.x < kTraceGroups && (id) < kTraceSlots)                          \
             g_trace[((k) * kTraceGroups + blockIdx.x) * kTraceSlots + (id)] = wall_clock64();             \
     } while (0)
+#ifdef LQ_TRACE_NOWAIT  // stamps never wait for outstanding memory operations: the flow as it is
+#define LQ_STAMP_WAIT(k, id) LQ_STAMP(k, id)
+#else
 #define LQ_STAMP_WAIT(k, id)                                                                              \
     do {                                                                                                  \
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                       \
         LQ_STAMP(k, id);                                                                                  \
     } while (0)
+#endif
 #define LQ_UNIT_SLOT(it, j) (4 + 7 * (it) + (j))
 #else
 #define LQ_STAMP(k, id) ((void)0)

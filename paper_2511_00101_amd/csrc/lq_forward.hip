@@ -508,6 +508,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     // 1. the unit's rows and their h: slices added, (fine-tune segments, first column block: stored to
     // h_out,) scaled, split into bf16 high/low, stored as ready-made fragments
     for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
+    LQ_STAMP(1, LQ_UNIT_SLOT(u.it, 1));
     const int parts = p.ksplit;
     const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && nb_begin == 0 && parts > 1;
     float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
