@@ -568,7 +568,19 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     // 2. per column block: stage B, then stream y
     for (int n_block = nb_begin; n_block < nb_end; ++n_block) {
     const int n_unit = n_block * C::UN;
-    __syncthreads();  // the previous block's fragment reads are done
+    __syncthreads();  // the previous block's fragment reads are done; the unit's rows are in LDS
+    // (row-wise layout) the first streaming step of y is requested here already: it arrives while B is staged
+    int row_f[4];
+    u32x4 y_f[4];
+    if constexpr (PAIRS == 2) {
+        const int n_ld = min(n_unit + w * C::WN + 8 * (lane & 7), p.d_out - 8);
+        const int safe = max(lds_row[0], 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            row_f[j] = lds_row[min(8 * j + (lane >> 3), C::CT - 1)];
+            y_f[j] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row_f[j] >= 0 ? row_f[j] : safe) * p.ldy + n_ld);
+        }
+    }
 #pragma unroll
     for (int i = 0; i < STAGE; ++i) {
         const int id = (int)threadIdx.x + i * kThreads;
@@ -619,7 +631,11 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                 y_n[j] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row_n[j] >= 0 ? row_n[j] : safe_row) * p.ldy + n_ld);
             }
         };
-        fetch(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            row_n[j] = row_f[j];
+            y_n[j] = y_f[j];
+        }
         for (int step = 0; step < n_steps; ++step) {
             int row[4];
             u32x4 yv[4];
