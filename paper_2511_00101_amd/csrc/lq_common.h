@@ -112,7 +112,13 @@ constexpr int kTraceSlots = 40, kTraceGroups = 1024;
     } while (0)
 #endif
 #define LQ_UNIT_SLOT(it, j) (4 + 7 * (it) + (j))
+#define LQ_STAMP_VALUE(k, id, value)                                                                      \
+    do {                                                                                                  \
+        if (threadIdx.x == 0 && blockIdx.x < kTraceGroups && (id) < kTraceSlots)                          \
+            g_trace[((k) * kTraceGroups + blockIdx.x) * kTraceSlots + (id)] = (unsigned long long)(value); \
+    } while (0)
 #else
+#define LQ_STAMP_VALUE(k, id, value) ((void)0)
 #define LQ_STAMP(k, id) ((void)0)
 #define LQ_STAMP_WAIT(k, id) ((void)0)
 #define LQ_UNIT_SLOT(it, j) 0

@@ -905,6 +905,7 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdP
                         : is_tall   ? find_unit(p, sg, cr, chunk, kTallRows, rest, u, s)
                                     : find_unit(p, sg, cm, chunk, kShortRows, small, u, s);
         if (!ok) return;
+        LQ_STAMP_VALUE(0, LQ_UNIT_SLOT(it, 1), 1ull << 40 | (unsigned long long)(id < n_full ? 2 : is_tall ? 1 : 0) << 32 | (unsigned)u.len << 16 | (unsigned)s.rank);
         LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(it, 2));
         // the unit runs with as many 16-rank tiles as its adapter needs (at most NT, the launch's maximum)
         u16* lds_a = reinterpret_cast<u16*>(lds_raw);
