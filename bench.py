@@ -310,8 +310,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--variant", choices=["auto", "split", "fused"], default="auto",
-                    help="auto: the single-launch variant for batches of up to 1024 tokens (one launch less is worth "
-                         "more than its barrier costs there), two launches above")
+                    help="auto: the single-launch (fused) variant, which is at least as fast as two launches on every "
+                         "workload here; split: two launches, with the shrink / expand breakdown")
     ap.add_argument("--workload", default="cfg2", help="headline workload: cfg1, cfg2, cfg3, cfg4up, cfg4down")
     ap.add_argument("--others", default="cfg3,cfg4up,cfg4down,cfg5", help="comma list of further workloads ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -341,9 +341,7 @@ def main():
         print(json.dumps(dict(copy_bytes_read=src.numel(), copy_bytes_written=dst.numel(), copies=8)))
         return
     def variant_for(problem):
-        if args.variant == "auto":
-            return lq.LQ_VARIANT_FUSED if problem.n_tokens <= 1024 else lq.LQ_VARIANT_SPLIT
-        return lq.LQ_VARIANT_FUSED if args.variant == "fused" else lq.LQ_VARIANT_SPLIT
+        return lq.LQ_VARIANT_SPLIT if args.variant == "split" else lq.LQ_VARIANT_FUSED
     makers = dict(cfg1=synth.config1, cfg2=synth.config2, cfg3=synth.config3,
                   cfg4up=lambda: synth.config4("up"), cfg4down=lambda: synth.config4("down"))
 
@@ -353,7 +351,7 @@ def main():
     others = []
     for name in [n for n in args.others.split(",") if n and n != args.workload]:
         if name == "cfg5":
-            others.append(measure_layer_stack(lq.LQ_VARIANT_SPLIT if args.variant != "fused" else lq.LQ_VARIANT_FUSED, 3, 1))
+            others.append(measure_layer_stack(lq.LQ_VARIANT_SPLIT if args.variant == "split" else lq.LQ_VARIANT_FUSED, 3, 1))
             continue
         q = makers[name]()
         others.append(measure(q, variant_for(q), max(20, args.steps // 4), max(5, args.warmup // 2)))

@@ -779,10 +779,25 @@ struct ShortLds {
     __attribute__((aligned(16))) float hs[kWaves][LQ_MAX_RANK][kTT];  // per wave: hs[rank][row], scaled
 };
 
+constexpr int kShortGroup = 8;  // rank rows of B in flight per group
+
+// A wave's first short unit and those of its loads that do not depend on h (row indices, y, the first 16
+// rows of B): the fused kernel requests them while it waits at its barrier, so that only h is left to
+// fetch behind it.
+struct ShortAhead {
+    bool live;  // wave uniform
+    Unit u;
+    SegInfo s;
+    int n_block;
+    int row[kTT];
+    u32x4 y[kTT], b[2 * kShortGroup];
+};
+
+template <bool AHEAD>  // AHEAD: rows, y and the first 16 rows of B come from `pre`
 __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
-                                                  ShortLds& sh)
+                                                  ShortLds& sh, const ShortAhead& pre)
 {
-    constexpr int JG = 8;  // rank rows of B in flight per group
+    constexpr int JG = kShortGroup;
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
     float* hs = &sh.hs[w][0][0];  // hs[j][t] at j * kTT + t
     const int parts = p.ksplit;
@@ -796,7 +811,10 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     // needed next.  Everything is loaded unconditionally from clamped addresses.
     int row[kTT];
 #pragma unroll
-    for (int t = 0; t < kTT; ++t) row[t] = t < u.len ? row_of(p, u.pos + t) : -1;
+    for (int t = 0; t < kTT; ++t) {
+        if constexpr (AHEAD) row[t] = pre.row[t];
+        else row[t] = t < u.len ? row_of(p, u.pos + t) : -1;
+    }
 
     // item i = lane + 64 q is (row t = i % 4, rank j = i / 4); the first two per lane cover ranks up to 32
     auto h_item = [&](int i) {
@@ -808,14 +826,19 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     };
     const float h0 = h_item(lane), h1 = h_item(lane + kWave);
 
+    // (AHEAD: the ring starts with the third group; the first two are in `pre`)
+    constexpr int J_RING = AHEAD ? 2 * JG : 0;
     u32x4 bn[JG];
 #pragma unroll
-    for (int jj = 0; jj < JG; ++jj) bn[jj] = *(gconst_u32x4)(s.B + (long long)min(jj, s.rank - 1) * p.d_out + n_ld);
+    for (int jj = 0; jj < JG; ++jj)
+        bn[jj] = *(gconst_u32x4)(s.B + (long long)min(J_RING + jj, s.rank - 1) * p.d_out + n_ld);
     const int safe_row = max(row[0], 0);
     u32x4 yv[kTT];
 #pragma unroll
-    for (int t = 0; t < kTT; ++t)
-        yv[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row[t] >= 0 ? row[t] : safe_row) * p.ldy + n_ld);
+    for (int t = 0; t < kTT; ++t) {
+        if constexpr (AHEAD) yv[t] = pre.y[t];
+        else yv[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row[t] >= 0 ? row[t] : safe_row) * p.ldy + n_ld);
+    }
 
     hs[lane] = h0;
     hs[lane + kWave] = h1;
@@ -829,14 +852,7 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     for (int t = 0; t < kTT; ++t)
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
-    for (int j0 = 0; j0 < rank_up; j0 += JG) {
-        u32x4 bc[JG];
-#pragma unroll
-        for (int jj = 0; jj < JG; ++jj) bc[jj] = bn[jj];
-#pragma unroll
-        for (int jj = 0; jj < JG; ++jj)  // the next group (past the end: the last row again, unused)
-            bn[jj] = *(gconst_u32x4)(s.B + (long long)min(j0 + JG + jj, s.rank - 1) * p.d_out + n_ld);
-        __builtin_amdgcn_sched_barrier(0);
+    auto fma_group = [&](const u32x4* bc, int j0) {
 #pragma unroll
         for (int jj = 0; jj < JG; ++jj) {
             const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs + (j0 + jj) * kTT);  // zero beyond the rank
@@ -848,6 +864,20 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc[t][i] = fmaf(h[t], bf[i], acc[t][i]);
         }
+    };
+    if constexpr (AHEAD) {
+        fma_group(pre.b, 0);
+        if (rank_up > JG) fma_group(pre.b + JG, JG);
+    }
+    for (int j0 = J_RING; j0 < rank_up; j0 += JG) {
+        u32x4 bc[JG];
+#pragma unroll
+        for (int jj = 0; jj < JG; ++jj) bc[jj] = bn[jj];
+#pragma unroll
+        for (int jj = 0; jj < JG; ++jj)  // the next group (past the end: the last row again, unused)
+            bn[jj] = *(gconst_u32x4)(s.B + (long long)min(j0 + JG + jj, s.rank - 1) * p.d_out + n_ld);
+        __builtin_amdgcn_sched_barrier(0);
+        fma_group(bc, j0);
         __builtin_amdgcn_sched_barrier(0);
     }
     if (n < p.d_out) {
@@ -1001,9 +1031,32 @@ __device__ __forceinline__ bool find_short_unit(const FwdParams& p, const Segs<F
     return find_unit(p, sg, e.cs, chunk, kTT, e.shorts, u, s);
 }
 
-template <int KSTEPS, int PAIRS>
+// requests the loads of this wave's first short unit that do not depend on h
+__device__ __forceinline__ ShortAhead short_request(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e)
+{
+    ShortAhead a;
+    a.live = false;
+    const int id = first_short_unit(e);
+    if (id >= e.n_short) return a;
+    a.u.it = 4;
+    a.live = find_short_unit(p, sg, e, id, a.u, a.s, a.n_block);
+    if (!a.live) return a;
+    const int n_ld = min(a.n_block * kShortN + lane_id() * 8, p.d_out - 8);
+#pragma unroll
+    for (int t = 0; t < kTT; ++t) a.row[t] = t < a.u.len ? row_of(p, a.u.pos + t) : -1;
+#pragma unroll
+    for (int jj = 0; jj < 2 * kShortGroup; ++jj)
+        a.b[jj] = *(gconst_u32x4)(a.s.B + (long long)min(jj, a.s.rank - 1) * p.d_out + n_ld);
+    const int safe_row = max(a.row[0], 0);
+#pragma unroll
+    for (int t = 0; t < kTT; ++t)
+        a.y[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(a.row[t] >= 0 ? a.row[t] : safe_row) * p.ldy + n_ld);
+    return a;
+}
+
+template <int KSTEPS, int PAIRS, bool AHEAD>  // AHEAD: this wave's first short unit was requested into `ahead`
 __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e,
-                                             unsigned char* lds_raw, ShortLds& sh, int* s_slot)
+                                             unsigned char* lds_raw, ShortLds& sh, int* s_slot, const ShortAhead ahead)
 {
     const int per = e.per, long_blocks = e.long_blocks, n_chunks = e.n_chunks;
     const LenClass& full = e.full;
@@ -1015,14 +1068,20 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
 
     // short units first (their cost is mostly latency, which the start of a launch has to spare)
     {
-        const int first = first_short_unit(e);
+        int first = first_short_unit(e);
+        if constexpr (AHEAD) {  // this wave's first unit was requested ahead; the loop below takes the others
+            if (first < e.n_short && ahead.live) expand_short_unit<true>(p, ahead.u, ahead.s, ahead.n_block, sh, ahead);
+            first += kWaves * (int)gridDim.x;
+        }
+        ShortAhead unused;
+        unused.live = false;
         for (int id = first; id < e.n_short; id += kWaves * (int)gridDim.x) {
             Unit u;
             SegInfo s;
             int n_block;
             u.it = 4;
             if (!find_short_unit(p, sg, e, id, u, s, n_block)) continue;
-            expand_short_unit(p, u, s, n_block, sh);
+            expand_short_unit<false>(p, u, s, n_block, sh, unused);
         }
     }
     LQ_STAMP_WAIT(1, 39);
@@ -1066,7 +1125,9 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
     const Segs<FwdParams> sg = load_segs(p);
     LQ_STAMP(1, 1);
     const ExpandPlan plan = plan_expand<KSTEPS, PAIRS>(p, sg);
-    expand_phase<KSTEPS, PAIRS>(p, sg, plan, lds_raw, sh, s_slot);
+    ShortAhead none;
+    none.live = false;
+    expand_phase<KSTEPS, PAIRS, false>(p, sg, plan, lds_raw, sh, s_slot, none);
 }
 
 // =================================================================================================
@@ -1091,11 +1152,16 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
     LQ_STAMP(1, 0);
-    // the expand phase's plan depends only on the tables: it is worked out while the workgroup waits
+    // What the expand phase needs and h does not: worked out, and requested, while the workgroup waits: the plan
+    // and, for every wave's first short unit, its row indices, y and the first rows of B.
     ExpandPlan plan;
-    grid_barrier(p.err, gen0, [&]() { plan = plan_expand<KSTEPS, PAIRS>(p, sg); });
+    ShortAhead ahead;
+    grid_barrier(p.err, gen0, [&]() {
+        plan = plan_expand<KSTEPS, PAIRS>(p, sg);
+        ahead = short_request(p, sg, plan);
+    });
     LQ_STAMP(1, 1);
-    expand_phase<KSTEPS, PAIRS>(p, sg, plan, lds_raw, sh, s_slot);
+    expand_phase<KSTEPS, PAIRS, true>(p, sg, plan, lds_raw, sh, s_slot, ahead);
 }
 
 int log2_of(int v)  // v is a power of two
