@@ -54,7 +54,11 @@ typedef enum {
  * order of Algorithm 1: fine-tune | prefill+evaluation | decode. */
 enum { LQ_SEG_FINETUNE = 0, LQ_SEG_PREFILL = 1, LQ_SEG_DECODE = 2 };
 
-/* LQ_VARIANT_SPLIT: shrink kernel then expand kernel.  LQ_VARIANT_FUSED: one launch.
+/* LQ_VARIANT_SPLIT: shrink kernel then expand kernel.  LQ_VARIANT_FUSED: one launch whose workgroups
+ * meet at a device-wide barrier between the two phases: it needs all of them resident at once, so the
+ * device must not be shared with other kernels while it runs (on another stream, say); if they are not,
+ * the bounded wait times out, bit 1 of the workspace error word is set and y is incomplete.  The backward
+ * call uses the same kind of launch for its first two steps.
  * LQ_VARIANT_SHRINK_ONLY / LQ_VARIANT_EXPAND_ONLY: the two halves of the split variant as separate
  * calls (same arguments, same workspace, shrink first), for callers that put other work between
  * them and for timing each kernel on its own. */
