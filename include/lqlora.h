@@ -88,7 +88,11 @@ const char* lora_status_string(lq_status status);
  *                                          running sum of len * rank over fine-tune segments
  *        n_segments  int32[1]              device scalar
  *   max_segments must be >= min(n_tokens, 3 * n_adapters).  n_tokens = 0 is valid (n_segments = 0).
- *   workspace: lora_build_workspace_bytes(n_tokens, n_adapters) bytes, contents irrelevant.
+ *   workspace: lora_build_workspace_bytes(n_tokens, n_adapters) bytes; its first 4096 bytes must be ZERO
+ *            before the first call that uses it (batches of 2048 tokens and more are built by several
+ *            workgroups that meet at a device-wide barrier, see LQ_VARIANT_FUSED for what that needs; its
+ *            words are left at zero); the rest may hold anything.  May be NULL for up to 312 adapters:
+ *            then one workgroup builds the tables, whatever the batch size.
  * ------------------------------------------------------------------------------------------- */
 size_t lora_build_workspace_bytes(int32_t n_tokens, int32_t n_adapters);
 

@@ -249,6 +249,136 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     }
 }
 
+// =================================================================================================
+// The same with several workgroups, for batches of thousands of tokens (one workgroup is bound by the
+// instruction rate of its compute unit: about 1.6 us per 1024 tokens).  Every workgroup counts and later
+// scatters its own slice of the tokens; in between the per-key counts of all workgroups meet in the
+// workspace ([key][workgroup], device-scope stores and loads) behind one device-wide barrier, and every
+// workgroup works out for itself where its tokens of every key go.  Workgroup 0 writes the segment
+// tables.  Needs at most 1024 keys' histograms in LDS (one key per thread), else the kernel above is used.
+// =================================================================================================
+constexpr int kMultiMinTokens = 2048;  // below this one workgroup is as fast
+constexpr int kMultiMaxGroups = 16;
+
+__global__ __launch_bounds__(kBuildThreads) void build_segments_multi_kernel(
+    const int32_t* __restrict__ token_adapter, const uint8_t* __restrict__ token_kind, int n_tokens,
+    const int32_t* __restrict__ ranks, int n_adapters,
+    int32_t* __restrict__ perm, int32_t* __restrict__ seg_starts, int32_t* __restrict__ seg_adapter,
+    uint8_t* __restrict__ seg_kind, int64_t* __restrict__ h_offsets, int32_t* __restrict__ n_segments,
+    int32_t* header, int32_t* counts)
+{
+    extern __shared__ int32_t lds_hist[];  // [key][16 waves]
+    __shared__ int s_tot[kBuildWaves];
+    __shared__ long long s_tot64[kBuildWaves];
+
+    const int tid = (int)threadIdx.x, lane = lane_id(), w = tid / kWave;
+    const int g = (int)blockIdx.x, n_groups = (int)gridDim.x;
+    const int n_keys = 3 * n_adapters;  // <= 1024: thread k owns key k
+
+    // every wave of the grid owns a contiguous token range (a multiple of 64 long)
+    int per_wave = (n_tokens + n_groups * kBuildWaves - 1) / (n_groups * kBuildWaves);
+    per_wave = (per_wave + kWave - 1) / kWave * kWave;
+    const int t_begin = (int)min((long long)n_tokens, (long long)(g * kBuildWaves + w) * per_wave);
+    const int t_end = min(n_tokens, t_begin + per_wave);
+
+    int keys[kKeyRounds];
+    auto load_keys = [&](int base0) {
+#pragma unroll
+        for (int r = 0; r < kKeyRounds; ++r) {
+            const int t = base0 + r * kWave + lane;
+            keys[r] = t < t_end ? token_key(token_adapter, token_kind, t, n_adapters) : -1;
+        }
+    };
+    const bool keys_fit = per_wave <= kKeyRounds * kWave;  // grid uniform
+    load_keys(t_begin);
+    const int my_rank = tid < n_adapters ? ranks[tid] : 0;
+    const int gen0 = __hip_atomic_load(header + kBarGen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // before arriving
+
+    for (int i = tid; i < n_keys * kBuildWaves; i += kBuildThreads) lds_hist[i] = 0;
+    __syncthreads();
+
+    int key_bits = 0;
+    while ((1 << key_bits) < n_keys) ++key_bits;
+    int groups[kKeyRounds];
+    for (int base0 = t_begin; base0 < t_end; base0 += kKeyRounds * kWave) {
+        if (base0 != t_begin) load_keys(base0);
+#pragma unroll
+        for (int r = 0; r < kKeyRounds; ++r) {
+            groups[r] = key_group(keys[r], key_bits);
+            if (keys[r] >= 0 && (groups[r] & 0xff) == lane) atomicAdd(lds_hist + keys[r] * kBuildWaves + w, groups[r] >> 16);
+        }
+    }
+    __syncthreads();
+
+    // this workgroup's count of every key goes to the workspace; then all workgroups meet
+    if (tid < n_keys) {
+        int mine = 0;
+#pragma unroll
+        for (int i = 0; i < kBuildWaves; ++i) mine += lds_hist[tid * kBuildWaves + i];
+        __hip_atomic_store(counts + tid * n_groups + g, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    grid_barrier(header, gen0, [] {});
+
+    // key k: tokens in all workgroups, and in the workgroups before this one
+    int total = 0, before = 0;
+    if (tid < n_keys) {
+        for (int i = 0; i < n_groups; ++i) {
+            const int c = __hip_atomic_load(counts + tid * n_groups + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            total += c;
+            if (i < g) before += c;
+        }
+    }
+    int n_live = 0;
+    const int key_start = block_exclusive_scan(total, s_tot, n_live);  // position in perm of the key's first token
+    if (tid < n_keys) {  // where each of this workgroup's waves puts its first token of the key
+        int run = key_start + before;
+#pragma unroll
+        for (int i = 0; i < kBuildWaves; ++i) {
+            const int c = lds_hist[tid * kBuildWaves + i];
+            lds_hist[tid * kBuildWaves + i] = run;
+            run += c;
+        }
+    }
+
+    // segments = non-empty keys, in key order (every workgroup runs the scans, workgroup 0 writes)
+    const bool seg_here = tid < n_keys && total > 0;
+    const long long my_h = seg_here && tid < n_adapters ? (long long)total * my_rank : 0;  // kind 0 = fine-tune keeps h
+    int total_segs = 0, seg = 0;
+    long long total_h = 0, h_run = 0;
+    block_exclusive_scan_pair(seg_here ? 1 : 0, my_h, s_tot, s_tot64, seg, h_run, total_segs, total_h);
+    if (g == 0) {
+        if (seg_here) {
+            const int kind = tid / n_adapters, a = tid - kind * n_adapters;
+            seg_starts[seg] = key_start;
+            seg_adapter[seg] = a;
+            seg_kind[seg] = (uint8_t)kind;
+            h_offsets[seg] = h_run;
+        }
+        if (tid == 0) {
+            seg_starts[total_segs] = n_live;
+            h_offsets[total_segs] = total_h;
+            *n_segments = total_segs;
+        }
+    }
+    __syncthreads();  // the offsets are in LDS before the scatter advances them
+
+    for (int base0 = t_begin; base0 < t_end; base0 += kKeyRounds * kWave) {
+        if (!keys_fit) load_keys(base0);
+#pragma unroll
+        for (int r = 0; r < kKeyRounds; ++r) {
+            const int t = base0 + r * kWave + lane;
+            const int key = keys[r];
+            if (__ballot(key >= 0) == 0) continue;  // wave uniform: nothing in this round
+            const int grp = keys_fit ? groups[r] : key_group(key, key_bits);
+            const int leader = key >= 0 ? (grp & 0xff) : lane;
+            int slot = 0;
+            if (key >= 0 && lane == leader) slot = atomicAdd(lds_hist + key * kBuildWaves + w, grp >> 16);
+            slot = __shfl(slot, leader, kWave);
+            if (key >= 0) perm[slot + ((grp >> 8) & 0xff)] = t;
+        }
+    }
+}
+
 }  // namespace
 }  // namespace lq
 
@@ -280,6 +410,19 @@ extern "C" lq_status lora_build_segments(const int32_t* token_adapter, const uin
         ws_hist = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + lq::kWsHeaderBytes);
     }
     const hipStream_t st = static_cast<hipStream_t>(stream);
+    // thousands of tokens: several workgroups, if the workspace is there for their counts and barrier
+    if (n_tokens >= lq::kMultiMinTokens && n_keys <= lq::kBuildThreads && use_lds && workspace &&
+        workspace_bytes >= lora_build_workspace_bytes(n_tokens, n_adapters)) {
+        int n_groups = (n_tokens + 1023) / 1024;
+        if (n_groups > lq::kMultiMaxGroups) n_groups = lq::kMultiMaxGroups;
+        int32_t* header = static_cast<int32_t*>(workspace);
+        int32_t* counts = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + lq::kWsHeaderBytes);
+        const hipError_t e = lq::launch_kernel(lq::kKernelBuild, lq::build_segments_multi_kernel, dim3(n_groups),
+                                               dim3(lq::kBuildThreads), hist_bytes, st, token_adapter, token_kind, n_tokens, ranks,
+                                               n_adapters, perm, seg_starts, seg_adapter, seg_kind, h_offsets, n_segments, header,
+                                               counts);
+        return e == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    }
     const hipError_t e =
         use_lds ? lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<true>, dim3(1), dim3(lq::kBuildThreads), hist_bytes,
                                     st, token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter,

@@ -34,6 +34,27 @@ def test_build_segments_bit_exact(oracle_mod, T, n_ad):
     assert_tables_equal(seg.to_host(), ref)
 
 
+def test_build_segments_one_and_many_workgroups_agree(oracle_mod):
+    """Batches of 2048 tokens and more are built by several workgroups when a workspace is given and by one
+    without; both must give the oracle's tables, also when the same workspace is used again and again."""
+    rng = np.random.default_rng(77)
+    T, n_ad = 8192 + 37, 48
+    ranks = rng.integers(1, 65, size=n_ad).astype(np.int32)
+    ws = lq.workspace(lq.lora_build_workspace_bytes(T, n_ad))
+    for rep in range(3):
+        ta = rng.integers(-1, n_ad + 1, size=T).astype(np.int32)
+        tk = rng.integers(0, 4, size=T).astype(np.uint8)
+        ta[rep * 1000: rep * 1000 + 3000] = rep       # a long run that straddles workgroup boundaries
+        tk[rep * 1000: rep * 1000 + 3000] = rep % 3
+        ref = oracle_mod.build_segments(ta, tk, ranks)
+        d_ta, d_tk, d_r = torch.from_numpy(ta).cuda(), torch.from_numpy(tk).cuda(), torch.from_numpy(ranks).cuda()
+        for workspace in (ws, None):
+            seg = lq.SegmentTables.empty(T, n_ad)
+            lq.lora_build_segments(d_ta, d_tk, d_r, seg, workspace)
+            assert_tables_equal(seg.to_host(), ref)
+    assert int(ws[0].item() & 0xffffffff) == 0
+
+
 def test_build_segments_configs(oracle_mod):
     for p in (synth.config1(), synth.config2()):
         d = DeviceProblem(p)
