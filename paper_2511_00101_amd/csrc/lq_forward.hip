@@ -59,13 +59,14 @@ __device__ unsigned long long g_trace[2 * kTraceGroups * kTraceSlots];  // this 
 // workgroup to leave puts both counters back to zero, so they are zero between launches.  One barrier
 // per unit, which also separates the units' uses of the LDS.
 //   ctr[0] draws so far, ctr[1] workgroups that left; slot: two ints of LDS
+//   it0 = 1: the workgroup's first unit has been run already; start with the second
 template <class Body>
-__device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, Body&& body)
+__device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, Body&& body, int it0 = 0)
 {
     const int grid = (int)gridDim.x;
     const bool more = n_units > grid, draws = n_units > 2 * grid;
-    int id = (int)blockIdx.x;
-    for (int it = 0; id < n_units; ++it) {
+    int id = (int)blockIdx.x + it0 * grid;
+    for (int it = it0; id < n_units; ++it) {
         int next = id + grid;
         if (it > 0 && threadIdx.x == 0)
             next = draws ? 2 * grid + __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : n_units;
@@ -479,9 +480,22 @@ struct ExpandCfg {
 
 // One unit = up to CT rows of one segment x the column blocks [nb_begin, nb_end).  The rows' h (and row
 // indices) are prepared once and reused for every column block of the unit.
-template <int KSTEPS, int PAIRS>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, a block 8 waves
+// A workgroup's first long unit and those of its loads that do not depend on h (its first block of B, its row
+// indices): the fused kernel requests them while it waits at its barrier.
+template <int KSTEPS, int PAIRS>
+struct LongAhead {
+    using C = ExpandCfg<KSTEPS, PAIRS>;
+    bool live;  // workgroup uniform
+    Unit u;
+    SegInfo s;
+    int nb_begin, nb_end;
+    int row;    // row index of position u.pos + threadIdx.x
+    u32x4 b[C::ROWS * (C::UN / 8) / kThreads];
+};
+
+template <int KSTEPS, int PAIRS, bool AHEAD>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, a block 8 waves
 __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int nb_begin,
-                                                 int nb_end, unsigned char* lds)
+                                                 int nb_end, unsigned char* lds, const LongAhead<KSTEPS, PAIRS>& pre)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
     constexpr int STAGE = C::ROWS * (C::UN / 8) / kThreads;  // 16-byte pieces of the B block per thread
@@ -503,11 +517,21 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
             bstage[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
         }
     };
-    b_load(nb_begin);
+    if constexpr (AHEAD) {
+#pragma unroll
+        for (int i = 0; i < STAGE; ++i) bstage[i] = pre.b[i];
+    } else {
+        b_load(nb_begin);
+    }
 
     // 1. the unit's rows and their h: slices added, (fine-tune segments, first column block: stored to
     // h_out,) scaled, split into bf16 high/low, stored as ready-made fragments
-    for (int i = (int)threadIdx.x; i < C::CT; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
+    static_assert(C::CT <= kThreads, "one row index per thread");
+    if constexpr (AHEAD) {
+        if ((int)threadIdx.x < C::CT) lds_row[threadIdx.x] = pre.row;
+    } else {
+        if ((int)threadIdx.x < C::CT) lds_row[threadIdx.x] = (int)threadIdx.x < u.len ? row_of(p, u.pos + (int)threadIdx.x) : -1;
+    }
     LQ_STAMP(1, LQ_UNIT_SLOT(u.it, 1));
     const int parts = p.ksplit;
     const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && nb_begin == 0 && parts > 1;
@@ -973,6 +997,7 @@ __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
 // unit, the classes of units and their prefix sums.  (The fused kernel does this before its barrier.)
 struct ExpandPlan {
     int per, long_blocks, n_chunks, short_blocks, n_short;
+    int groups, per_group, n_full, n_big, n_long;  // long units: column groups per chunk, numbering of the classes
     LenClass shorts, full, big, little;
     ClassScan cf, cb, cl, cs;
 };
@@ -1009,6 +1034,17 @@ __device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs
     e.cb = scan_class(p, sg, per, e.big);
     e.cl = scan_class(p, sg, per, e.little);
     e.n_chunks = e.cf.total + e.cb.total + e.cl.total;
+    // Long units: a chunk of rows x a group of column blocks.  Groups are as large as possible (the rows' h is
+    // prepared once per unit) while leaving about 4 units per workgroup.
+    e.groups = e.per_group = 1;
+    if (e.n_chunks > 0) {
+        const int groups_wanted = small_div(4 * (int)gridDim.x + e.n_chunks - 1, e.n_chunks);
+        e.per_group = max(1, small_div(e.long_blocks, max(1, min(e.long_blocks, groups_wanted))));
+        e.groups = small_div(e.long_blocks + e.per_group - 1, e.per_group);
+    }
+    e.n_full = e.cf.total * e.groups;
+    e.n_big = e.n_full + e.cb.total * e.groups;
+    e.n_long = e.n_chunks * e.groups;
     e.cs = scan_class(p, sg, kTT, e.shorts);
     e.short_blocks = (p.d_out + kShortN - 1) / kShortN;
     e.n_short = e.cs.total * e.short_blocks;
@@ -1054,17 +1090,49 @@ __device__ __forceinline__ ShortAhead short_request(const FwdParams& p, const Se
     return a;
 }
 
-template <int KSTEPS, int PAIRS, bool AHEAD>  // AHEAD: this wave's first short unit was requested into `ahead`
-__device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e,
-                                             unsigned char* lds_raw, ShortLds& sh, int* s_slot, const ShortAhead ahead)
+// long unit `id`: large ones first so that a launch ends evenly: the even chunks of the segments with more
+// than `per` rows, the segments with per/2 to per rows, the smaller ones
+__device__ __forceinline__ bool find_long_unit(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e, int id,
+                                               Unit& u, SegInfo& s, int& nb_begin, int& nb_end)
 {
-    const int per = e.per, long_blocks = e.long_blocks, n_chunks = e.n_chunks;
-    const LenClass& full = e.full;
-    const LenClass& big = e.big;
-    const LenClass& little = e.little;
-    const ClassScan& cf = e.cf;
-    const ClassScan& cb = e.cb;
-    const ClassScan& cl = e.cl;
+    const int cid = id < e.n_full ? id : id < e.n_big ? id - e.n_full : id - e.n_big;
+    const int chunk = small_div(cid, e.groups);
+    nb_begin = (cid - chunk * e.groups) * e.per_group;
+    nb_end = min(e.long_blocks, nb_begin + e.per_group);
+    return id < e.n_full ? find_unit(p, sg, e.cf, chunk, e.per, e.full, u, s)
+           : id < e.n_big ? find_unit(p, sg, e.cb, chunk, e.per, e.big, u, s)
+                          : find_unit(p, sg, e.cl, chunk, e.per, e.little, u, s);
+}
+
+// requests the loads of this workgroup's first long unit that do not depend on h
+template <int KSTEPS, int PAIRS>
+__device__ __forceinline__ LongAhead<KSTEPS, PAIRS> long_request(const FwdParams& p, const Segs<FwdParams>& sg,
+                                                                  const ExpandPlan& e)
+{
+    using C = ExpandCfg<KSTEPS, PAIRS>;
+    constexpr int STAGE = C::ROWS * (C::UN / 8) / kThreads;
+    LongAhead<KSTEPS, PAIRS> a;
+    a.live = false;
+    if ((int)blockIdx.x >= e.n_long) return a;
+    a.u.it = 0;
+    a.live = find_long_unit(p, sg, e, (int)blockIdx.x, a.u, a.s, a.nb_begin, a.nb_end);
+    if (!a.live) return a;
+#pragma unroll
+    for (int i = 0; i < STAGE; ++i) {
+        const int id = (int)threadIdx.x + i * kThreads;
+        const int j = id / (C::UN / 8), n = a.nb_begin * C::UN + (id % (C::UN / 8)) * 8;
+        a.b[i] = *(gconst_u32x4)(a.s.B + (long long)min(j, a.s.rank - 1) * p.d_out + min(n, p.d_out - 8));
+    }
+    a.row = (int)threadIdx.x < a.u.len ? row_of(p, a.u.pos + (int)threadIdx.x) : -1;
+    return a;
+}
+
+// AHEAD: this wave's first short unit and this workgroup's first long unit were requested into `ahead`, `lahead`
+template <int KSTEPS, int PAIRS, bool AHEAD>
+__device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e,
+                                             unsigned char* lds_raw, ShortLds& sh, int* s_slot, const ShortAhead ahead,
+                                             const LongAhead<KSTEPS, PAIRS> lahead)
+{
 
     // short units first (their cost is mostly latency, which the start of a launch has to spare)
     {
@@ -1072,6 +1140,11 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
         if constexpr (AHEAD) {  // this wave's first unit was requested ahead; the loop below takes the others
             if (first < e.n_short && ahead.live) expand_short_unit<true>(p, ahead.u, ahead.s, ahead.n_block, sh, ahead);
             first += kWaves * (int)gridDim.x;
+        }
+        if constexpr (AHEAD) {  // then the workgroup's first long unit (by now the short unit's registers are free)
+            if (lahead.live)
+                expand_long_unit<KSTEPS, PAIRS, true>(p, lahead.u, lahead.s, lahead.nb_begin, lahead.nb_end, lds_raw, lahead);
+            __syncthreads();  // before the next long unit reuses the LDS
         }
         ShortAhead unused;
         unused.live = false;
@@ -1086,31 +1159,21 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
     }
     LQ_STAMP_WAIT(1, 39);
 
-    // long units, one per workgroup iteration: a chunk of rows x a group of column blocks, large ones first
-    // so that a launch ends evenly: the even chunks of the segments with more than `per` rows, the segments
-    // with per/2 to per rows, the smaller ones.  Groups are as large as possible (the rows' h is prepared
-    // once per unit) while leaving about 4 units per workgroup.
-    if (n_chunks > 0) {
-        const int groups_wanted = small_div(4 * (int)gridDim.x + n_chunks - 1, n_chunks);
-        const int per_group = max(1, small_div(long_blocks, max(1, min(long_blocks, groups_wanted))));
-        const int groups = small_div(long_blocks + per_group - 1, per_group);
-        const int n_full = cf.total * groups, n_big = n_full + cb.total * groups;
+    // long units, one per workgroup iteration
+    if (e.n_chunks > 0) {
         LQ_STAMP(1, 2);
-        for_each_unit(p.tickets + 2, n_chunks * groups, s_slot, [&](int id, int it) {
+        LongAhead<KSTEPS, PAIRS> none;
+        none.live = false;
+        for_each_unit(p.tickets + 2, e.n_long, s_slot, [&](int id, int it) {
             Unit u;
             SegInfo s;
+            int nb_begin, nb_end;
             u.it = it;
             LQ_STAMP(1, LQ_UNIT_SLOT(it, 0));
-            const int cid = id < n_full ? id : id < n_big ? id - n_full : id - n_big;
-            const int chunk = small_div(cid, groups);
-            const bool ok = id < n_full ? find_unit(p, sg, cf, chunk, per, full, u, s)
-                            : id < n_big ? find_unit(p, sg, cb, chunk, per, big, u, s)
-                                         : find_unit(p, sg, cl, chunk, per, little, u, s);
-            if (!ok) return;
+            if (!find_long_unit(p, sg, e, id, u, s, nb_begin, nb_end)) return;
             LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(it, 2));
-            const int nb = (cid - chunk * groups) * per_group;
-            expand_long_unit<KSTEPS, PAIRS>(p, u, s, nb, min(long_blocks, nb + per_group), lds_raw);
-        });
+            expand_long_unit<KSTEPS, PAIRS, false>(p, u, s, nb_begin, nb_end, lds_raw, none);
+        }, AHEAD ? 1 : 0);
     }
     LQ_STAMP_WAIT(1, 3);
 }
@@ -1127,7 +1190,9 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
     const ExpandPlan plan = plan_expand<KSTEPS, PAIRS>(p, sg);
     ShortAhead none;
     none.live = false;
-    expand_phase<KSTEPS, PAIRS, false>(p, sg, plan, lds_raw, sh, s_slot, none);
+    LongAhead<KSTEPS, PAIRS> lnone;
+    lnone.live = false;
+    expand_phase<KSTEPS, PAIRS, false>(p, sg, plan, lds_raw, sh, s_slot, none, lnone);
 }
 
 // =================================================================================================
@@ -1156,12 +1221,14 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     // and, for every wave's first short unit, its row indices, y and the first rows of B.
     ExpandPlan plan;
     ShortAhead ahead;
+    LongAhead<KSTEPS, PAIRS> lahead;
     grid_barrier(p.err, gen0, [&]() {
         plan = plan_expand<KSTEPS, PAIRS>(p, sg);
         ahead = short_request(p, sg, plan);
+        lahead = long_request<KSTEPS, PAIRS>(p, sg, plan);
     });
     LQ_STAMP(1, 1);
-    expand_phase<KSTEPS, PAIRS, true>(p, sg, plan, lds_raw, sh, s_slot, ahead);
+    expand_phase<KSTEPS, PAIRS, true>(p, sg, plan, lds_raw, sh, s_slot, ahead, lahead);
 }
 
 int log2_of(int v)  // v is a power of two
