@@ -54,9 +54,9 @@ struct BwdParams {
 template <int NT>
 struct WgCfg {
     static constexpr int YPITCH = kWgCols + 8;                 // u16 elements per staged activation row
-    static constexpr int HPITCH = 16 * NT + 1;                 // floats per staged h / g row
+    static constexpr int HPITCH = 16 * NT + 8;                 // u16 elements per staged row of h / g (high or low parts)
     static constexpr size_t Y_BYTES = (size_t)kStepRows * YPITCH * sizeof(u16);
-    static constexpr size_t H_BYTES = ((size_t)kStepRows * HPITCH * sizeof(float) + 15) / 16 * 16;
+    static constexpr size_t H_BYTES = ((size_t)2 * kStepRows * HPITCH * sizeof(u16) + 15) / 16 * 16;  // high, then low
     static constexpr size_t BUF_BYTES = Y_BYTES + H_BYTES;
     static constexpr size_t LDS_BYTES = 2 * BUF_BYTES + kWgRows * sizeof(int);
 };
@@ -67,18 +67,6 @@ template <int... Js, class F>
 __device__ __forceinline__ void for_each_slot(std::integer_sequence<int, Js...>, F&& f)
 {
     (f(std::integral_constant<int, Js>{}), ...);
-}
-
-__device__ __forceinline__ void split_hi_lo(const float (&v)[8], u32x4& hi, u32x4& lo)
-{
-    unsigned int h[4], l[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        h[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
-        l[i] = pack_bf16x2(v[2 * i] - bf16_lo(h[i]), v[2 * i + 1] - bf16_hi(h[i]));
-    }
-    hi = u32x4{h[0], h[1], h[2], h[3]};
-    lo = u32x4{l[0], l[1], l[2], l[3]};
 }
 
 // D[rank][col] = sum_t H[t][rank] Y[t][col] over the unit's rows; H = h_saved (for dB, Y = dy) or g (for
@@ -125,7 +113,7 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
     };
     auto stage_store = [&](int step, int buf, const u32x4 (&y)[YQ], const float (&h)[NT]) {
         u16* ly = reinterpret_cast<u16*>(lds + buf * C::BUF_BYTES);
-        float* lh = reinterpret_cast<float*>(lds + buf * C::BUF_BYTES + C::Y_BYTES);
+        u16* lh = reinterpret_cast<u16*>(lds + buf * C::BUF_BYTES + C::Y_BYTES);
         const int i = step * kStepRows + y_row;
         const bool row_live = i < u.len && lds_row[min(i, kWgRows - 1)] >= 0;
 #pragma unroll
@@ -133,9 +121,15 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
             const bool live = row_live && n0 + (y_piece + 16 * q) * 8 < d;
             *reinterpret_cast<u32x4*>(ly + y_row * C::YPITCH + (y_piece + 16 * q) * 8) = live ? y[q] : u32x4{0u, 0u, 0u, 0u};
         }
+        // h / g as bf16 high and low parts (together ~16 mantissa bits), split here once instead of in every wave
 #pragma unroll
-        for (int q = 0; q < NT; ++q)
-            lh[y_row * C::HPITCH + y_piece + 16 * q] = (i < u.len && y_piece + 16 * q < rank) ? h[q] : 0.f;
+        for (int q = 0; q < NT; ++q) {
+            const float v = (i < u.len && y_piece + 16 * q < rank) ? h[q] : 0.f;
+            const unsigned int hi = pack_bf16x2(v, 0.f) & 0xffffu;
+            const unsigned int lo = pack_bf16x2(v - bf16_lo(hi), 0.f) & 0xffffu;
+            lh[y_row * C::HPITCH + y_piece + 16 * q] = (u16)hi;
+            lh[(kStepRows + y_row) * C::HPITCH + y_piece + 16 * q] = (u16)lo;
+        }
     };
 
     f32x4 acc[NT][kWgTiles];
@@ -146,23 +140,15 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
 
     auto compute = [&](int buf) {
         const u16* ly = reinterpret_cast<const u16*>(lds + buf * C::BUF_BYTES);
-        const float* lh = reinterpret_cast<const float*>(lds + buf * C::BUF_BYTES + C::Y_BYTES);
+        const u16* lh = reinterpret_cast<const u16*>(lds + buf * C::BUF_BYTES + C::Y_BYTES);
+        // the staged rows are the MFMA's k axis: both operands are read back transposed
         u32x4 yf[kWgTiles];
 #pragma unroll
-        for (int nt = 0; nt < kWgTiles; ++nt) {
-            const u16* col = ly + w * (16 * kWgTiles) + nt * 16 + c;
-            unsigned int e[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) e[i] = col[(8 * kg + i) * C::YPITCH];
-            yf[nt] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-        }
+        for (int nt = 0; nt < kWgTiles; ++nt) yf[nt] = lds_read_transposed_16x32(ly + w * (16 * kWgTiles) + nt * 16, C::YPITCH);
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt) {
-            float v[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = lh[(8 * kg + i) * C::HPITCH + jt * 16 + c];
-            u32x4 hi, lo;
-            split_hi_lo(v, hi, lo);
+            const u32x4 hi = lds_read_transposed_16x32(lh + jt * 16, C::HPITCH);
+            const u32x4 lo = lds_read_transposed_16x32(lh + kStepRows * C::HPITCH + jt * 16, C::HPITCH);
 #pragma unroll
             for (int nt = 0; nt < kWgTiles; ++nt) {
                 acc[jt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(lo), as_bf16x8(yf[nt]), acc[jt][nt], 0, 0, 0);

@@ -49,6 +49,28 @@ __device__ __forceinline__ void unpack8(const u32x4& w, float* f)
     f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
 }
 
+// ---- transposing LDS read (gfx950 ds_read_b64_tr_b16) ------------------------------------------
+// A 16 x 32 block of 16-bit elements that lies row-major in LDS ([k row][column], `pitch` elements per row)
+// as the 16x16x32 MFMA wants it: lane (c = lane % 16, kg = lane / 16) gets column c, rows 8 kg .. 8 kg + 7.
+// Within every group of 16 lanes the instruction gathers the 8-byte pieces the lanes point at and hands lane
+// i the i%4-th element of the pieces of lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12; so lane q of a group points
+// at row q / 4 of the group's four rows, columns 4 (q % 4) .. + 3, and two reads cover the 8 rows.
+// block: element (k row 0, column 0) of the block; 8-byte aligned, pitch a multiple of 4.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+// The four 4-column pieces need not be adjacent: piece i starts at column piece_stride * i (lane c then gets
+// column piece_stride * (c / 4) + c % 4).
+__device__ __forceinline__ u32x4 lds_read_transposed_16x32(const u16* block, int pitch, int piece_stride = 4)
+{
+    typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+    const int lane = lane_id(), q = lane & 15, kg = lane >> 4;
+    const u16* p = block + (8 * kg + (q >> 2)) * pitch + piece_stride * (q & 3);
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p);
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * pitch));
+    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+    const u32x2 lo = __builtin_bit_cast(u32x2, a), hi = __builtin_bit_cast(u32x2, b);
+    return u32x4{lo.x, lo.y, hi.x, hi.y};
+}
+
 // ---- wave primitives ---------------------------------------------------------------------------
 // v + (v of another lane, picked by a DPP control; 0 where that lane lies outside the row or the row is
 // masked off)

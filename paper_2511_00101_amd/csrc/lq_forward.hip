@@ -620,14 +620,10 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     for (int q = 0; q < PAIRS; ++q)
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
-            const u16* col = lds_b + w * C::WN + 32 * q + 8 * (c >> 2) + 4 * m + (c & 3);
+            // lane c: column 32 q + 8 (c / 4) + 4 m + c % 4 of the wave's range, rank rows 32 ks + 8 g .. + 7
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                unsigned int e[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) e[i] = col[(32 * ks + 8 * g + i) * C::BPITCH];
-                bfrag[q][m][ks] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-            }
+            for (int ks = 0; ks < KSTEPS; ++ks)
+                bfrag[q][m][ks] = lds_read_transposed_16x32(lds_b + 32 * ks * C::BPITCH + w * C::WN + 32 * q + 4 * m, C::BPITCH, 8);
         }
     if (n_block == nb_begin) LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 4));
     if constexpr (PAIRS == 2) __syncthreads();  // every wave has its fragments: the B block's LDS becomes scratch
