@@ -28,7 +28,7 @@ struct FwdParams {
     int kinds;       // bit k set: segments of kind k take part (forward: all; backward: fine-tune only)
     int coherent;    // fused variant: the h slices are written and read with device-scope accesses
     unsigned int hpart_bytes;  // size of hpart (for the buffer descriptor of the device-scope 16-byte loads)
-    int* tickets;    // workspace header words 4..9: unit tickets of the two phases and the fused variant's barrier
+    int* tickets;    // workspace header words 4..: unit tickets ([0,1] shrink phase, [2,3] expand phase); the barrier's words: kBar*
 };
 
 constexpr int kAllKinds = 7;
