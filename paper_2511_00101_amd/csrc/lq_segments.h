@@ -224,12 +224,15 @@ template <class P>
 __device__ __forceinline__ ClassScan scan_class(const P& p, const Segs<P>& sg, int per, LenClass cls)
 {
     ClassScan cs;
-#pragma unroll
-    for (int b = 0; b < kCachedBatches; ++b) {
-        cs.nch[b] = chunks_in(sg.c[b].en - sg.c[b].st, sg.c[b].kd, per, cls);
-        cs.incl[b] = wave_inclusive_scan(cs.nch[b]);
-    }
+    cs.nch[0] = chunks_in(sg.c[0].en - sg.c[0].st, sg.c[0].kd, per, cls);
+    cs.incl[0] = wave_inclusive_scan(cs.nch[0]);
     cs.tot0 = lane_value(cs.incl[0], kWave - 1);
+    static_assert(kCachedBatches == 2, "the second batch is handled by name");
+    cs.nch[1] = cs.incl[1] = 0;
+    if (sg.n_seg > kWave) {  // wave uniform: most batches have at most 64 segments
+        cs.nch[1] = chunks_in(sg.c[1].en - sg.c[1].st, sg.c[1].kd, per, cls);
+        cs.incl[1] = wave_inclusive_scan(cs.nch[1]);
+    }
     cs.tot_cached = cs.tot0 + lane_value(cs.incl[1], kWave - 1);
     cs.total = cs.tot_cached;
     for (int s0 = kCachedBatches * kWave; s0 < sg.n_seg; s0 += kWave) {
