@@ -1007,20 +1007,20 @@ __device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs
     e.shorts = LenClass{1, kLongMin, p.kinds};
     e.long_blocks = (p.d_out + C::UN - 1) / C::UN;
 
-    // Rows per long unit: CT when that still gives every workgroup a couple of units, else fewer (down to 64:
-    // the B block is staged once per unit), so that a batch with few rows is still spread over the whole machine.
+    // Rows per long unit: CT, halved (down to 64: the B block is staged once per unit) until the units fill two
+    // rounds of the grid, or exactly one: so that a batch with few rows is still spread over the whole machine,
+    // and so that equal units (a batch of long fine-tune segments only) do not leave half a round empty.
     int per = C::CT;
-    {
-        int rows = 0, segs = 0;
+    if (sg.n_seg <= kCachedBatches * kWave) {  // (more segments than that: plenty of units anyway)
+        const int grid = (int)gridDim.x;
+        while (per > 64) {
+            int chunks = 0;
 #pragma unroll
-        for (int b = 0; b < kCachedBatches; ++b) {
-            const int len = sg.c[b].en - sg.c[b].st;
-            const bool in = chunks_in(len, sg.c[b].kd, 1, longs) > 0;
-            rows += wave_sum(in ? len : 0);
-            segs += wave_sum(in ? 1 : 0);
+            for (int b = 0; b < kCachedBatches; ++b) chunks += wave_sum(chunks_in(sg.c[b].en - sg.c[b].st, sg.c[b].kd, per, longs));
+            const long long units = (long long)chunks * e.long_blocks;
+            if (units >= 2LL * grid || (units >= grid && units % grid == 0)) break;
+            per >>= 1;
         }
-        if (sg.n_seg > kCachedBatches * kWave) rows = kBig / 2;  // many segments: plenty of units anyway
-        while (per > 64 && ((long long)(rows / per + segs) * e.long_blocks < 2LL * (int)gridDim.x)) per >>= 1;
     }
     e.per = per;
     e.full = LenClass{per + 1, kBig, p.kinds, true};
