@@ -131,9 +131,17 @@ __device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const
 // finished h of one element: the slices added in order
 __device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j, int parts)
 {
-    float sum = h_load(p.hpart + pos * p.rstride + j, p.coherent);
-    for (int part = 1; part < parts; ++part)
-        sum += h_load(p.hpart + ((long long)part * p.n_tokens + pos) * p.rstride + j, p.coherent);
+    // the first four slices are requested together (a slice that does not exist re-reads the last one and is
+    // not added): one round trip instead of one per slice
+    const long long slice = (long long)p.n_tokens * p.rstride;
+    const float* at = p.hpart + pos * p.rstride + j;
+    float v[4];
+#pragma unroll
+    for (int part = 0; part < 4; ++part) v[part] = h_load(at + min(part, parts - 1) * slice, p.coherent);
+    float sum = v[0];
+#pragma unroll
+    for (int part = 1; part < 4; ++part) sum += part < parts ? v[part] : 0.f;
+    for (int part = 4; part < parts; ++part) sum += h_load(at + part * slice, p.coherent);
     return sum;
 }
 
