@@ -13,6 +13,7 @@ constexpr int kBuildWaves = kBuildThreads / kWave;
 constexpr int kKeyRounds = 8;   // 64-token rounds whose keys a wave holds in registers
 constexpr int kBuildLdsBudget = 60000;  // bytes of dynamic LDS used for the histograms when they fit
 
+template <int WAVES = kBuildWaves>
 __device__ __forceinline__ int block_exclusive_scan(int v, int* s_tot, int& total)
 {
     const int lane = lane_id(), w = (int)threadIdx.x / kWave;
@@ -22,7 +23,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* s_tot, int& tota
     __syncthreads();
     int before = 0, all = 0;
 #pragma unroll
-    for (int i = 0; i < kBuildWaves; ++i) {
+    for (int i = 0; i < WAVES; ++i) {
         const int t = s_tot[i];
         if (i < w) before += t;
         all += t;
@@ -32,6 +33,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* s_tot, int& tota
 }
 
 // two exclusive scans (an int and a 64-bit count) that share their barriers
+template <int WAVES = kBuildWaves>
 __device__ __forceinline__ void block_exclusive_scan_pair(int v, long long h, int* s_tot, long long* s_tot64, int& ex_v,
                                                           long long& ex_h, int& total_v, long long& total_h)
 {
@@ -47,7 +49,7 @@ __device__ __forceinline__ void block_exclusive_scan_pair(int v, long long h, in
     int before_v = 0, all_v = 0;
     long long before_h = 0, all_h = 0;
 #pragma unroll
-    for (int i = 0; i < kBuildWaves; ++i) {
+    for (int i = 0; i < WAVES; ++i) {
         const int t = s_tot[i];
         const long long t64 = s_tot64[i];
         if (i < w) { before_v += t; before_h += t64; }
@@ -105,8 +107,9 @@ __device__ __forceinline__ int key_group(int key, int key_bits)
     return (__ffsll((long long)peers) - 1) | (__popcll(peers & ((1ull << lane) - 1ull)) << 8) | (__popcll(peers) << 16);
 }
 
-template <bool LDS_HIST>
-__global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
+// WAVES: 16, or 4 for a batch of up to 256 tokens (a small workgroup starts sooner and its barriers are cheaper)
+template <bool LDS_HIST, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void build_segments_kernel(
     const int32_t* __restrict__ token_adapter, const uint8_t* __restrict__ token_kind, int n_tokens,
     const int32_t* __restrict__ ranks, int n_adapters,
     int32_t* __restrict__ perm, int32_t* __restrict__ seg_starts, int32_t* __restrict__ seg_adapter,
@@ -114,12 +117,12 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     int32_t* ws_hist)
 {
     extern __shared__ int32_t lds_hist[];
-    __shared__ int s_tot[kBuildWaves];
-    __shared__ long long s_tot64[kBuildWaves];
+    __shared__ int s_tot[WAVES];
+    __shared__ long long s_tot64[WAVES];
 
     const int tid = (int)threadIdx.x, lane = lane_id(), w = tid / kWave;
     const int n_keys = 3 * n_adapters;
-    const int n_entries = n_keys * kBuildWaves;
+    const int n_entries = n_keys * WAVES;
     // hist[key * 16 + wave]: tokens with that key in that wave's token range; scanned in place into
     // the position in perm where that wave's first such token goes.
     // (a compile-time choice, so that the common case gets LDS atomics instead of flat ones)
@@ -129,7 +132,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     };
 
     // each wave owns a contiguous token range (a multiple of 64 long), walked 64 tokens at a time
-    int per_wave = (n_tokens + kBuildWaves - 1) / kBuildWaves;
+    int per_wave = (n_tokens + WAVES - 1) / WAVES;
     per_wave = (per_wave + kWave - 1) / kWave * kWave;
     const int t_begin = min(n_tokens, w * per_wave);
     const int t_end = min(n_tokens, t_begin + per_wave);
@@ -148,13 +151,13 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     };
     const bool keys_fit = per_wave <= kKeyRounds * kWave;  // workgroup uniform
     load_keys(t_begin);
-    const int keys_per_thread = (n_keys + kBuildThreads - 1) / kBuildThreads;
+    const int keys_per_thread = (n_keys + (WAVES * kWave) - 1) / (WAVES * kWave);
     const int k_begin = min(n_keys, tid * keys_per_thread);
     const int k_end = min(n_keys, k_begin + keys_per_thread);
     const int rank_first = k_begin < n_adapters ? ranks[k_begin] : 0;
     auto rank_of_key = [&](int k) { return k == k_begin ? rank_first : ranks[k]; };  // k < n_adapters
 
-    for (int i = tid; i < n_entries; i += kBuildThreads) *hist_at(i) = 0;
+    for (int i = tid; i < n_entries; i += (WAVES * kWave)) *hist_at(i) = 0;
     __syncthreads();
 
     int key_bits = 0;
@@ -171,22 +174,22 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
         for (int r = 0; r < kKeyRounds; ++r) {
             if (group_early) {
                 groups[r] = key_group(keys[r], key_bits);
-                if (keys[r] >= 0 && (groups[r] & 0xff) == lane) atomicAdd(hist_at(keys[r] * kBuildWaves + w), groups[r] >> 16);
+                if (keys[r] >= 0 && (groups[r] & 0xff) == lane) atomicAdd(hist_at(keys[r] * WAVES + w), groups[r] >> 16);
             } else if (keys[r] >= 0) {
-                atomicAdd(hist_at(keys[r] * kBuildWaves + w), 1);
+                atomicAdd(hist_at(keys[r] * WAVES + w), 1);
             }
         }
     }
     __syncthreads();
 
     // exclusive scan over (key major, wave minor)
-    const int per_thread = (n_entries + kBuildThreads - 1) / kBuildThreads;
+    const int per_thread = (n_entries + (WAVES * kWave) - 1) / (WAVES * kWave);
     const int e_begin = min(n_entries, tid * per_thread);
     const int e_end = min(n_entries, e_begin + per_thread);
     int local = 0;
     for (int i = e_begin; i < e_end; ++i) local += *hist_at(i);
     int n_live = 0;
-    int run = block_exclusive_scan(local, s_tot, n_live);
+    int run = block_exclusive_scan<WAVES>(local, s_tot, n_live);
     for (int i = e_begin; i < e_end; ++i) {
         const int c = *hist_at(i);
         *hist_at(i) = run;
@@ -198,8 +201,8 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     int my_segs = 0;
     long long my_h = 0;
     for (int k = k_begin; k < k_end; ++k) {
-        const int start = *hist_at(k * kBuildWaves);
-        const int next = (k + 1 < n_keys) ? *hist_at((k + 1) * kBuildWaves) : n_live;
+        const int start = *hist_at(k * WAVES);
+        const int next = (k + 1 < n_keys) ? *hist_at((k + 1) * WAVES) : n_live;
         const int cnt = next - start;
         if (cnt > 0) {
             ++my_segs;
@@ -208,10 +211,10 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
     }
     int total_segs = 0, seg = 0;
     long long total_h = 0, h_run = 0;
-    block_exclusive_scan_pair(my_segs, my_h, s_tot, s_tot64, seg, h_run, total_segs, total_h);
+    block_exclusive_scan_pair<WAVES>(my_segs, my_h, s_tot, s_tot64, seg, h_run, total_segs, total_h);
     for (int k = k_begin; k < k_end; ++k) {
-        const int start = *hist_at(k * kBuildWaves);
-        const int next = (k + 1 < n_keys) ? *hist_at((k + 1) * kBuildWaves) : n_live;
+        const int start = *hist_at(k * WAVES);
+        const int next = (k + 1 < n_keys) ? *hist_at((k + 1) * WAVES) : n_live;
         const int cnt = next - start;
         if (cnt > 0) {
             const int kind = k / n_adapters, a = k - kind * n_adapters;
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_kernel(
             const int grp = group_early && keys_fit ? groups[r] : key_group(key, key_bits);
             const int leader = key >= 0 ? (grp & 0xff) : lane;
             int slot = 0;
-            if (key >= 0 && lane == leader) slot = atomicAdd(hist_at(key * kBuildWaves + w), grp >> 16);
+            if (key >= 0 && lane == leader) slot = atomicAdd(hist_at(key * WAVES + w), grp >> 16);
             slot = __shfl(slot, leader, kWave);
             if (key >= 0) perm[slot + ((grp >> 8) & 0xff)] = t;
         }
@@ -423,12 +426,19 @@ extern "C" lq_status lora_build_segments(const int32_t* token_adapter, const uin
                                                counts);
         return e == hipSuccess ? LQ_OK : LQ_ERR_HIP;
     }
-    const hipError_t e =
-        use_lds ? lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<true>, dim3(1), dim3(lq::kBuildThreads), hist_bytes,
-                                    st, token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter,
-                                    seg_kind, h_offsets, n_segments, ws_hist)
-                : lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<false>, dim3(1), dim3(lq::kBuildThreads), 0, st,
-                                    token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter,
-                                    seg_kind, h_offsets, n_segments, ws_hist);
+    hipError_t e;
+    if (use_lds && n_tokens <= 4 * lq::kWave) {  // a small batch: four waves
+        e = lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<true, 4>, dim3(1), dim3(4 * lq::kWave), hist_bytes / 4, st,
+                              token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter, seg_kind,
+                              h_offsets, n_segments, ws_hist);
+    } else if (use_lds) {
+        e = lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<true, lq::kBuildWaves>, dim3(1), dim3(lq::kBuildThreads),
+                              hist_bytes, st, token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter,
+                              seg_kind, h_offsets, n_segments, ws_hist);
+    } else {
+        e = lq::launch_kernel(lq::kKernelBuild, lq::build_segments_kernel<false, lq::kBuildWaves>, dim3(1), dim3(lq::kBuildThreads), 0,
+                              st, token_adapter, token_kind, n_tokens, ranks, n_adapters, perm, seg_starts, seg_adapter, seg_kind,
+                              h_offsets, n_segments, ws_hist);
+    }
     return e == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }

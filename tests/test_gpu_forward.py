@@ -16,7 +16,7 @@ VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED]
 # ---------------------------------------------------------------------------------------------------
 # segment metadata: bit exact
 # ---------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("T,n_ad", [(0, 3), (1, 1), (63, 4), (64, 4), (65, 7), (1000, 64), (2047, 9), (2048, 16), (2049, 5),
+@pytest.mark.parametrize("T,n_ad", [(0, 3), (1, 1), (63, 4), (64, 4), (65, 7), (200, 300), (256, 64), (257, 64), (1000, 64), (2047, 9), (2048, 16), (2049, 5),
                                     (4097, 33), (8192, 32), (16385, 40), (5000, 300), (5000, 313), (20000, 1000),
                                     (140000, 24)])
 def test_build_segments_bit_exact(oracle_mod, T, n_ad):
