@@ -129,21 +129,43 @@ class SegmentTables:
                     h_offsets=self.h_offsets[: n + 1].cpu().numpy(), n_segments=n)
 
 
-def lora_build_segments(token_adapter: torch.Tensor, token_kind: torch.Tensor, ranks: torch.Tensor,
-                        out: SegmentTables, workspace: Optional[torch.Tensor] = None, stream=None) -> SegmentTables:
+class PreparedCall:
+    """An entry point with its arguments marshalled once: for loops that repeat the same call (the tensors must stay
+    alive and in place; the stream is the one that was current when the call was prepared)."""
+
+    def __init__(self, fn, args, where: str):
+        self.fn, self.args, self.where = fn, args, where
+
+    def __call__(self) -> None:
+        st = self.fn(*self.args)
+        if st != LQ_OK:
+            raise LqError(st, self.where)
+
+
+def _build_segments_args(token_adapter, token_kind, ranks, out, workspace, stream):
     n_tokens = int(token_adapter.shape[0])
     n_adapters = int(ranks.shape[0])
     assert token_adapter.dtype == torch.int32 and token_kind.dtype == torch.uint8 and ranks.dtype == torch.int32
     assert token_adapter.is_contiguous() and token_kind.is_contiguous() and ranks.is_contiguous()
-    st = lib().lora_build_segments(_ptr(token_adapter) if n_tokens else None, _ptr(token_kind) if n_tokens else None,
-                                   n_tokens, _ptr(ranks), n_adapters,
-                                   _ptr(out.perm), _ptr(out.seg_starts), _ptr(out.seg_adapter), _ptr(out.seg_kind),
-                                   _ptr(out.h_offsets), _ptr(out.n_segments), out.max_segments,
-                                   _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
-                                   _stream(stream))
+    return (_ptr(token_adapter) if n_tokens else None, _ptr(token_kind) if n_tokens else None,
+            n_tokens, _ptr(ranks), n_adapters,
+            _ptr(out.perm), _ptr(out.seg_starts), _ptr(out.seg_adapter), _ptr(out.seg_kind),
+            _ptr(out.h_offsets), _ptr(out.n_segments), out.max_segments,
+            _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+            _stream(stream))
+
+
+def lora_build_segments(token_adapter: torch.Tensor, token_kind: torch.Tensor, ranks: torch.Tensor,
+                        out: SegmentTables, workspace: Optional[torch.Tensor] = None, stream=None) -> SegmentTables:
+    st = lib().lora_build_segments(*_build_segments_args(token_adapter, token_kind, ranks, out, workspace, stream))
     if st != LQ_OK:
         raise LqError(st, "lora_build_segments")
     return out
+
+
+def prepare_build_segments(token_adapter, token_kind, ranks, out, workspace=None, stream=None) -> PreparedCall:
+    return PreparedCall(lib().lora_build_segments, _build_segments_args(token_adapter, token_kind, ranks, out, workspace, stream),
+                        "lora_build_segments")
 
 
 @dataclass
@@ -174,23 +196,31 @@ class AdapterTable:
         return len(self.A)
 
 
-def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,
-                           h_out: Optional[torch.Tensor], workspace: torch.Tensor,
-                           variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None) -> None:
+def _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream):
     assert x.dtype == torch.bfloat16 and y.dtype == torch.bfloat16
     assert x.stride(1) == 1 and y.stride(1) == 1
     n_tokens, d_in = int(x.shape[0]), int(x.shape[1])
     d_out = int(y.shape[1])
-    st = lib().lora_segmented_forward(
-        _ptr(x), x.stride(0), _ptr(y), y.stride(0), d_in, d_out,
-        _ptr(adapters.A_ptrs), _ptr(adapters.B_ptrs), _ptr(adapters.ranks), _ptr(adapters.scales),
-        adapters.n_adapters, adapters.max_rank,
-        _ptr(seg.perm) if use_perm else None, n_tokens,
-        _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
-        _ptr(h_out), _ptr(seg.h_offsets) if h_out is not None else None,
-        variant, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    return (_ptr(x), x.stride(0), _ptr(y), y.stride(0), d_in, d_out,
+            _ptr(adapters.A_ptrs), _ptr(adapters.B_ptrs), _ptr(adapters.ranks), _ptr(adapters.scales),
+            adapters.n_adapters, adapters.max_rank,
+            _ptr(seg.perm) if use_perm else None, n_tokens,
+            _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
+            _ptr(h_out), _ptr(seg.h_offsets) if h_out is not None else None,
+            variant, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+
+
+def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,
+                           h_out: Optional[torch.Tensor], workspace: torch.Tensor,
+                           variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None) -> None:
+    st = lib().lora_segmented_forward(*_forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream))
     if st != LQ_OK:
         raise LqError(st, "lora_segmented_forward")
+
+
+def prepare_forward(x, y, adapters, seg, h_out, workspace, variant=LQ_VARIANT_SPLIT, use_perm=True, stream=None) -> PreparedCall:
+    return PreparedCall(lib().lora_segmented_forward,
+                        _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream), "lora_segmented_forward")
 
 
 def lora_segmented_backward(x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, adapters: AdapterTable,

@@ -224,3 +224,23 @@ def test_launch_timing_api():
         lq.lora_profile_enable(False)
     d.forward(lq.LQ_VARIANT_SPLIT)
     assert all(n == 0 for _, n in lq.lora_profile_read().values())
+
+
+def test_prepared_calls_match_direct_calls(oracle_mod):
+    """binding.prepare_*: the same entry points with the arguments marshalled once."""
+    p = synth.config1()
+    direct, prepared = DeviceProblem(p), DeviceProblem(p)
+    direct.build()
+    y_direct, h_direct, _ = direct.forward(lq.LQ_VARIANT_FUSED)
+    h_elems = int(direct.seg.h_offsets.max().item())
+    prepared.h_out = torch.full((max(h_elems, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    ws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, prepared.adapters.max_rank, p.d_in, p.d_out, lq.LQ_VARIANT_FUSED))
+    build = lq.prepare_build_segments(prepared.token_adapter, prepared.token_kind, prepared.adapters.ranks, prepared.seg,
+                                      prepared.build_ws)
+    forward = lq.prepare_forward(prepared.x, prepared.y, prepared.adapters, prepared.seg, prepared.h_out, ws, lq.LQ_VARIANT_FUSED)
+    build()
+    forward()
+    torch.cuda.synchronize()
+    assert_tables_equal(prepared.seg.to_host(), oracle_mod.build_segments(p.batch.token_adapter, p.batch.token_kind, p.ranks))
+    assert np.array_equal(lq.bits_from_bf16(prepared.y), y_direct)
+    assert np.array_equal(prepared.h_out[:h_elems].cpu().numpy(), h_direct)
