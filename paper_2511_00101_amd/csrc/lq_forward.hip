@@ -1226,11 +1226,13 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     ExpandPlan plan;
     ShortAhead ahead;
     LongAhead<KSTEPS, PAIRS> lahead;
-    grid_barrier(p.err, gen0, [&]() {
+    const bool opened = grid_barrier(p.err, gen0, [&]() {
         plan = plan_expand<KSTEPS, PAIRS>(p, sg);
         ahead = short_request(p, sg, plan);
         lahead = long_request<KSTEPS, PAIRS>(p, sg, plan);
     });
+    // The wait ran out (somewhere): h is incomplete, so y is left as it is; bit 1 of the error word says so.
+    if (!opened) return;
     LQ_STAMP(1, 1);
     expand_phase<KSTEPS, PAIRS, true>(p, sg, plan, lds_raw, sh, s_slot, ahead, lahead);
 }

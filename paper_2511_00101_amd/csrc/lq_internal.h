@@ -46,7 +46,7 @@ hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream
 // Data that crosses it must be written and read with device-scope accesses (the XCDs' L2 caches are not
 // coherent with each other); the barrier itself uses no cache write-back or invalidation.  header: the
 // workspace header (error word at 0); gen0: the generation word read before this workgroup arrives.  The
-// wait is bounded; a timeout sets bit 1 of the error word.
+// wait is bounded; a timeout sets bit 1 of the error word and the caller's next phase is skipped.
 constexpr int kErrBarrierTimeout = 2;
 constexpr int kBarrierSpinLimit = 1 << 20;
 
@@ -56,14 +56,24 @@ constexpr int kBarrierSpinLimit = 1 << 20;
 // All counters are back at zero when the barrier opens.
 constexpr int kBarGen = 32, kBarTop = 64, kBarSub = 96, kBarLine = 32, kBarFan = 16;  // int offsets from the header
 
-// `overlap` runs in every thread between the workgroup's arrival and its wait for the others.
+// The generation word counts the barriers that opened (modulo 2^30).  A workgroup whose wait runs out sets bit 1
+// of the error word and poisons the generation word (kBarPoison), which sends every workgroup that is still
+// waiting, or that arrives later, or that starts later, down the same path: the caller's next phase is skipped by
+// all of them (up to the race between the poison and a barrier that opens at the same moment).  The poison
+// stays until the caller zeroes the workspace header.
+constexpr int kBarPoison = 1 << 30;
+__device__ __forceinline__ bool barrier_poisoned(int gen0) { return (gen0 & kBarPoison) != 0; }
+
+// `overlap` runs in every thread between the workgroup's arrival and its wait for the others.  Returns true
+// (in every thread of the workgroup) if the barrier opened, false if the wait ran out here or elsewhere.
 template <class Overlap>
-__device__ __forceinline__ void grid_barrier(int* header, int gen0, Overlap&& overlap)
+__device__ __forceinline__ bool grid_barrier(int* header, int gen0, Overlap&& overlap)
 {
     // every thread's device-scope (written-through) stores are acknowledged before its workgroup arrives
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) {
+    const int opened = (gen0 + 1) & (kBarPoison - 1);
+    if (threadIdx.x == 0 && !barrier_poisoned(gen0)) {
         int* gen = header + kBarGen;
         const int grid = (int)gridDim.x, k = (int)blockIdx.x % kBarFan;
         const int n_k = (grid - k + kBarFan - 1) / kBarFan, n_sub = min(grid, kBarFan);
@@ -73,24 +83,31 @@ __device__ __forceinline__ void grid_barrier(int* header, int gen0, Overlap&& ov
             int* top = header + kBarTop;
             if (__hip_atomic_fetch_add(top, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_sub - 1) {
                 __hip_atomic_store(top, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(gen, gen0 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(gen, opened, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
     overlap();
+    int failed = 0;
     if (threadIdx.x == 0) {
         int* gen = header + kBarGen;
-        int spins = 0;
-        while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen0) {
+        int spins = 0, now = gen0;
+        while (!barrier_poisoned(gen0)) {
+            now = __hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (now != gen0) break;
             __builtin_amdgcn_s_sleep(8);
-            if (++spins > kBarrierSpinLimit) {
-                atomicOr(header, kErrBarrierTimeout);
-                break;
-            }
+            if (++spins > kBarrierSpinLimit) break;
+        }
+        if (now != opened) {
+            failed = 1;
+            atomicOr(header, kErrBarrierTimeout);
+            if (!barrier_poisoned(now))
+                __hip_atomic_store(gen, gen0 | kBarPoison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    __syncthreads();
+    failed = __syncthreads_or(failed);
     asm volatile("" ::: "memory");  // loads of the next phase stay behind the barrier
+    return failed == 0;
 }
 
 // ---- optional timing of the library's own launches (lora_profile_enable / lora_profile_read) ----------------

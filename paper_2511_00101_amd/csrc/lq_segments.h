@@ -16,6 +16,18 @@ namespace lq {
 
 struct SegLane { int st, en, ad, kd; };  // table entries of segment (batch * 64 + lane); empty beyond n_seg
 
+// The tables may have been written by the caller: a segment's positions must lie inside [0, n_tokens] and must
+// not run backwards.  One that does not is treated as empty and reported (bit 0 of the error word), so that no
+// later index derived from it can leave perm, the activations or the partial-h buffer.
+template <class P>
+__device__ __forceinline__ void guard_seg_range(const P& p, SegLane& c)
+{
+    if (c.st < 0 || c.en < c.st || c.en > p.n_tokens) {
+        atomicOr(p.err, kErrBadSegment);
+        c.st = c.en = 0;
+    }
+}
+
 template <class P>
 __device__ __forceinline__ SegLane load_seg_lane(const P& p, int n_seg, int s)
 {
@@ -27,6 +39,7 @@ __device__ __forceinline__ SegLane load_seg_lane(const P& p, int n_seg, int s)
     c.ad = p.seg_adapter[sc];
     c.kd = p.seg_kind[sc];
     if (s >= n_seg) c.st = c.en = c.ad = c.kd = 0;
+    guard_seg_range(p, c);
     return c;
 }
 
@@ -191,6 +204,7 @@ __device__ __forceinline__ Segs<P> load_segs(const P& p)
     for (int b = 0; b < kCachedBatches; ++b) {
         sg.c[b] = raw[b];
         if (b * kWave + lane_id() >= sg.n_seg) sg.c[b].st = sg.c[b].en = sg.c[b].ad = sg.c[b].kd = 0;
+        guard_seg_range(p, sg.c[b]);
     }
     return sg;
 }

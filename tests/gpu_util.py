@@ -89,7 +89,7 @@ def check_forward(oracle_mod, p: synth.Problem, variant=lq.LQ_VARIANT_SPLIT):
     return y_bits, h, ref
 
 
-def long_batch_problem(seed, with_dy):
+def long_batch_problem(seed, with_dy, y0_zero=False):
     """40000 tokens (more than one batch of keys per builder wave, no k split, hundreds of chunks): a few long
     fine-tune and prefill segments, many short ones, narrow layers so that the oracle stays fast."""
     rng = np.random.default_rng(seed)
@@ -103,4 +103,4 @@ def long_batch_problem(seed, with_dy):
     order = rng.permutation(len(ta))
     ranks = rng.choice([8, 16, 32], size=n_ad)
     return synth.make_problem("long_batch", synth.Batch(ta[order], tk[order]), 512, 384, ranks, rng.uniform(0.5, 1.5, n_ad),
-                              seed + 1, with_dy=with_dy, w_std=0.03)
+                              seed + 1, with_dy=with_dy, w_std=0.03, y0_zero=y0_zero)

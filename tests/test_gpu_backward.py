@@ -93,9 +93,10 @@ def test_backward_repeat_is_bit_identical(oracle_mod):
         assert torch.equal(x, y)
 
 
-@pytest.mark.parametrize("layer,projection", [(0, 0), (31, 6)])
+@pytest.mark.parametrize("layer,projection", [(0, 0), (0, 1), (31, 4), (31, 6)])
 def test_backward_config5_calls(oracle_mod, layer, projection):
-    """Two of the 224 (layer, projection) calls of the layer stack with its seeded dy."""
+    """The four distinct shapes of the 224 (layer, projection) calls of the layer stack (q, k, gate, down) with
+    their seeded dy."""
     run_backward(oracle_mod, synth.config5(layer, projection, with_dy=True))
 
 

@@ -139,14 +139,54 @@ def test_bad_device_metadata_is_skipped_and_flagged(variant):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("corrupt", ["start_negative", "end_beyond_batch", "runs_backwards"])
+def test_corrupt_segment_range_is_skipped_and_flagged(oracle_mod, variant, corrupt):
+    """A segment whose positions leave [0, n_tokens] or run backwards (tables written by a careless caller) is
+    treated as empty and reported; every other segment is computed as usual and nothing is accessed out of
+    bounds (the guard clamps before any index is formed)."""
+    lens, ads, kinds = [40, 50, 6], [0, 1, 0], [0, 1, 2]
+    ta = np.concatenate([np.full(l, a, np.int32) for l, a in zip(lens, ads)])
+    tk = np.concatenate([np.full(l, k, np.uint8) for l, k in zip(lens, kinds)])
+    p = synth.make_problem("corrupt", synth.Batch(ta, tk), 256, 256, [8, 16], [1.0, 2.0], 5)
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, ta, tk)
+    d = DeviceProblem(p)
+    d.build()
+    starts = d.seg.seg_starts.cpu().numpy().copy()      # [0, 40, 90, 96]
+    if corrupt == "start_negative":
+        starts[0] = -5                                   # segment 0 = [-5, 40)
+        bad = [0]
+    elif corrupt == "end_beyond_batch":
+        starts[3] = 96 + 1000                            # segment 2 = [90, 1096)
+        bad = [2]
+    else:
+        starts[2] = 30                                   # segment 1 = [40, 30) runs backwards; segment 2 = [30, 96) is a
+        bad = [1]                                        # valid range that now overlaps others: only rows 0..29 are compared
+    d.seg.seg_starts[:4] = torch.from_numpy(starts[:4]).cuda()
+    y_bits, _, err = d.forward(variant, h_elems=40 * 8)
+    assert err & 1
+    y = synth.bf16_bits_to_f64(y_bits)
+    if corrupt == "runs_backwards":
+        assert_close(y[:30], ref.y[:30], "rows of segment 0 that no other segment touches")
+        return
+    bounds = [0, 40, 90, 96]
+    for g in range(3):
+        rows = slice(bounds[g], bounds[g + 1])
+        if g in bad:
+            assert np.array_equal(y_bits[rows], p.y0[rows])           # skipped: untouched
+        else:
+            assert_close(y[rows], ref.y[rows], f"segment {g}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
 def test_config2_decode_heavy(oracle_mod, variant):
     for y0_zero in (False, True):
         check_forward(oracle_mod, synth.config2(y0_zero=y0_zero), variant)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
-def test_config3_unified(oracle_mod, variant):
-    check_forward(oracle_mod, synth.config3(), variant)
+@pytest.mark.parametrize("y0_zero", [False, True])
+def test_config3_unified(oracle_mod, variant, y0_zero):
+    check_forward(oracle_mod, synth.config3(y0_zero=y0_zero), variant)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -169,16 +209,20 @@ def test_config4_mlp_hetero_ranks(oracle_mod, variant, which):
     check_forward(oracle_mod, synth.config4(which), variant)
 
 
-def test_config4_lora_term_alone(oracle_mod):
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config4_lora_term_alone(oracle_mod, variant, which):
     """y0 = 0, so the bound applies to the LoRA term itself and not to y0 + term."""
-    check_forward(oracle_mod, synth.config4("up", y0_zero=True), lq.LQ_VARIANT_SPLIT)
+    check_forward(oracle_mod, synth.config4(which, y0_zero=True), variant)
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("y0_zero", [False, True])
 @pytest.mark.parametrize("layer,projection", [(0, 0), (0, 1), (31, 4), (31, 6)])
-def test_config5_layer_stack_calls(oracle_mod, layer, projection):
-    """Four of the 224 (layer, projection) calls of the layer stack: q and k of layer 0, gate and down of layer 31."""
-    p = synth.config5(layer, projection, with_dy=False)
-    check_forward(oracle_mod, p, lq.LQ_VARIANT_SPLIT if projection % 2 == 0 else lq.LQ_VARIANT_FUSED)
+def test_config5_layer_stack_calls(oracle_mod, layer, projection, y0_zero, variant):
+    """The four distinct shapes of the 224 (layer, projection) calls of the layer stack (q and k of layer 0, gate
+    and down of layer 31), each in both variants, with y0 ~ N(0, 1) and with y0 = 0 (the LoRA term alone)."""
+    check_forward(oracle_mod, synth.config5(layer, projection, with_dy=False, y0_zero=y0_zero), variant)
 
 
 def test_large_rank_and_many_segments(oracle_mod):
@@ -192,16 +236,53 @@ def test_large_rank_and_many_segments(oracle_mod):
     order = rng.permutation(len(ta))
     # weights and scales small enough that |y| stays below 8: from there on half a bf16 ulp of the output
     # alone (2^-5) exceeds the absolute bound
-    p = synth.make_problem("many", synth.Batch(ta[order], tk[order]), 1024, 1536, ranks, rng.uniform(0.5, 1.0, n_ad), 321,
-                           w_std=0.03)
+    for y0_zero in (False, True):
+        p = synth.make_problem("many", synth.Batch(ta[order], tk[order]), 1024, 1536, ranks, rng.uniform(0.5, 1.0, n_ad), 321,
+                               w_std=0.03, y0_zero=y0_zero)
+        for variant in VARIANTS:
+            check_forward(oracle_mod, p, variant)
+
+
+@pytest.mark.parametrize("y0_zero", [False, True])
+def test_many_tokens(oracle_mod, y0_zero):
+    p = long_batch_problem(900, with_dy=False, y0_zero=y0_zero)
     for variant in VARIANTS:
         check_forward(oracle_mod, p, variant)
 
 
-def test_many_tokens(oracle_mod):
-    p = long_batch_problem(900, with_dy=False)
-    for variant in VARIANTS:
-        check_forward(oracle_mod, p, variant)
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_token_permutation_invariance(oracle_mod, variant):
+    """The update is per token, so the order of the tokens in the batch must not matter: permute the tokens, run the
+    HIP path on the permuted batch, undo the permutation, and compare with the oracle's result for the ORIGINAL
+    batch (y within tolerance; saved h through its own offsets; rows without an adapter bit-identical)."""
+    p = synth.small_mixed(41, 700, 1032, 776, [16, 8, 33, 24], drop_frac=0.1, w_std=0.04)
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    rng = np.random.default_rng(4242)
+    for _ in range(2):
+        sigma = rng.permutation(p.n_tokens)                      # row i of the permuted batch is token sigma[i]
+        q = synth.Problem(p.name + "_perm", p.d_in, p.d_out, p.ranks, p.scales, p.A, p.B, p.x[sigma], p.y0[sigma],
+                          synth.Batch(p.batch.token_adapter[sigma], p.batch.token_kind[sigma]))
+        d = DeviceProblem(q)
+        d.build()
+        tables = d.seg.to_host()
+        y_bits, h, err = d.forward(variant)
+        assert err == 0
+        back = np.empty_like(sigma)
+        back[sigma] = np.arange(p.n_tokens)
+        y_unperm = y_bits[back]
+        assert_close(synth.bf16_bits_to_f64(y_unperm), ref.y, "y of the permuted batch, un-permuted")
+        dead = p.batch.token_adapter < 0
+        assert np.array_equal(y_unperm[dead], p.y0[dead])
+        # saved h: token t's row sits where the permuted batch's own tables put it; its values are token t's
+        ref_off = oracle_mod.token_h_offsets(ref.segments, p.ranks, p.n_tokens)
+        for g in range(tables["n_segments"]):
+            if tables["seg_kind"][g] != 0:
+                continue
+            r = int(p.ranks[tables["seg_adapter"][g]])
+            rows = tables["perm"][tables["seg_starts"][g]: tables["seg_starts"][g + 1]]
+            got = h[tables["h_offsets"][g]: tables["h_offsets"][g] + len(rows) * r].reshape(len(rows), r)
+            want = np.stack([ref.h[ref_off[sigma[i]]: ref_off[sigma[i]] + r] for i in rows])
+            assert_close(got, want, f"h of segment {g}")
 
 
 def test_launch_timing_api():
@@ -244,3 +325,59 @@ def test_prepared_calls_match_direct_calls(oracle_mod):
     assert_tables_equal(prepared.seg.to_host(), oracle_mod.build_segments(p.batch.token_adapter, p.batch.token_kind, p.ranks))
     assert np.array_equal(lq.bits_from_bf16(prepared.y), y_direct)
     assert np.array_equal(prepared.h_out[:h_elems].cpu().numpy(), h_direct)
+
+
+def test_fused_wait_that_runs_out_leaves_y_untouched(oracle_mod):
+    """The single-launch variant's device-wide wait is bounded.  Here it can never complete (one arrival counter of
+    the workspace header is pre-loaded with a large negative value by the host), so every workgroup's wait runs out:
+    every kernel still exits normally, bit 1 of the error word is set, and y is bit-identical to y0 because the
+    expand phase is skipped.  The same workspace keeps refusing single-launch calls until its header is zeroed;
+    after that (or in two launches) the call gives the oracle's result."""
+    p = synth.config1()
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    d = DeviceProblem(p)
+    d.build()
+    ws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, d.adapters.max_rank, p.d_in, p.d_out, lq.LQ_VARIANT_FUSED))
+    words = ws.view(torch.int32)
+    words[96] = -(1 << 20)                          # first arrival counter (header word 96)
+    h_out = torch.zeros(ref.segments.h_elems, dtype=torch.float32, device="cuda")
+    for _ in range(2):                              # the second call finds the poisoned generation word at once
+        lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, lq.LQ_VARIANT_FUSED)
+        torch.cuda.synchronize()
+        assert int(words[0].item()) & 2
+        assert np.array_equal(lq.bits_from_bf16(d.y), p.y0)
+    # two launches do not use the barrier words: same workspace, error word cleared by the caller
+    words[0] = 0
+    lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, lq.LQ_VARIANT_SPLIT)
+    torch.cuda.synchronize()
+    assert int(words[0].item()) == 0
+    assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(d.y)), ref.y, "y after the two-launch call")
+    # header zeroed: the single launch works again
+    ws.zero_()
+    d.y.copy_(lq.bf16_from_bits(p.y0))
+    lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, lq.LQ_VARIANT_FUSED)
+    torch.cuda.synchronize()
+    assert int(words[0].item()) == 0
+    assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(d.y)), ref.y, "y after the header was zeroed")
+
+
+def test_one_workspace_many_calls(oracle_mod):
+    """One workspace reused by consecutive calls (two launches, one launch, two launches, one launch) on a batch
+    with many more units than resident workgroups, so that the ticket counters are drawn from: every call must
+    match the oracle, and the header's counters must be back at zero after every call."""
+    p = synth.config4("up")
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    d = DeviceProblem(p)
+    d.build()
+    ws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, d.adapters.max_rank, p.d_in, p.d_out, lq.LQ_VARIANT_FUSED))
+    y0 = lq.bf16_from_bits(p.y0)
+    for variant in (lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED):
+        d.y.copy_(y0)
+        h_out = torch.full((ref.segments.h_elems,), float("nan"), dtype=torch.float32, device="cuda")
+        lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, variant)
+        torch.cuda.synchronize()
+        header = ws.view(torch.int32)[:1024].cpu().numpy()
+        assert header[0] == 0
+        assert not np.any(header[np.arange(1024) != 32]), "counters of the header must be back at zero"  # word 32 counts barriers
+        assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(d.y)), ref.y, "y")
+        assert_close(h_out.cpu().numpy(), ref.h, "h_out")
