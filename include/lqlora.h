@@ -69,6 +69,12 @@ enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1, LQ_VARIANT_SHRINK_ONLY = 2, L
 
 const char* lora_status_string(lq_status status);
 
+/* One size that serves every call of this header on a batch of these dimensions (the largest of
+ * lora_build_workspace_bytes, lora_forward_workspace_bytes for every variant, and
+ * lora_backward_workspace_bytes): a caller that keeps one workspace per stream needs nothing else.
+ * The per-call sizers below give the exact requirement of each call. */
+size_t lora_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in, int32_t d_out);
+
 /* ---------------------------------------------------------------------------------------------
  * Segment metadata builder (integer only, deterministic, bit-exact).
  *
@@ -154,8 +160,11 @@ lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ld
  *   dA_ptrs / dB_ptrs  [n_adapters] device arrays of device pointers to float [r_a, d_in] / [r_a, d_out],
  *            accumulated into (caller zeroes); entries may be NULL (that gradient is skipped), and
  *            either table may be NULL; with both NULL only dx is computed
+ *   variant  LQ_VARIANT_FUSED: g and dx in one launch (same residency requirement as the forward's fused
+ *            variant; falls back to two launches where the partial-g region would reach 2 GiB);
+ *            LQ_VARIANT_SPLIT: two launches, no device-wide wait.  Other values: LQ_ERR_INVALID_ARG.
  *   workspace lora_backward_workspace_bytes(...) bytes; its first 4096 bytes zero as for the forward.
- *   Three launches: g and dx (shrink and expand in one launch), weight-gradient partials, their reduction.
+ *   Then the weight-gradient partials and their reduction (two more launches).
  *   The order of every sum is fixed, so results are reproducible run to run.
  * ------------------------------------------------------------------------------------------- */
 size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in,
@@ -170,7 +179,7 @@ lq_status lora_segmented_backward(const void* x, int64_t ldx, const void* dy, in
                                   const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
                                   const int32_t* n_segments, int32_t max_segments,
                                   const float* h_saved, const int64_t* h_offsets,
-                                  void* workspace, size_t workspace_bytes, void* stream);
+                                  int32_t variant, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Timing of the library's own kernel launches, for benchmarks (not part of the paper's method).

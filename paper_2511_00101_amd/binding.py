@@ -26,6 +26,7 @@ _i32, _i64, _vp, _sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c
 
 _SIGNATURES = {
     "lora_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "lora_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_build_workspace_bytes": (_sz, [_i32, _i32]),
     "lora_build_segments": (ctypes.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
     "lora_forward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
@@ -34,7 +35,7 @@ _SIGNATURES = {
     "lora_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_segmented_backward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp,
                                                _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
-                                               _vp, _vp, _vp, _sz, _vp]),
+                                               _vp, _vp, _i32, _vp, _sz, _vp]),
     "lora_profile_enable": (ctypes.c_int, [_i32]),
     "lora_profile_read": (ctypes.c_int, [_vp, _vp, _i32]),
 }
@@ -79,6 +80,10 @@ def _stream(stream) -> Optional[int]:
 
 def lora_status_string(status: int) -> str:
     return lib().lora_status_string(int(status)).decode()
+
+
+def lora_workspace_bytes(n_tokens: int, n_adapters: int, max_rank: int, d_in: int, d_out: int) -> int:
+    return int(lib().lora_workspace_bytes(n_tokens, n_adapters, max_rank, d_in, d_out))
 
 
 def lora_build_workspace_bytes(n_tokens: int, n_adapters: int) -> int:
@@ -207,7 +212,7 @@ def _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stre
             _ptr(seg.perm) if use_perm else None, n_tokens,
             _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
             _ptr(h_out), _ptr(seg.h_offsets) if h_out is not None else None,
-            variant, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+            variant, _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
 
 
 def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,
@@ -225,7 +230,8 @@ def prepare_forward(x, y, adapters, seg, h_out, workspace, variant=LQ_VARIANT_SP
 
 def lora_segmented_backward(x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, adapters: AdapterTable,
                             dA_ptrs: Optional[torch.Tensor], dB_ptrs: Optional[torch.Tensor], seg: SegmentTables,
-                            h_saved: torch.Tensor, workspace: torch.Tensor, use_perm: bool = True, stream=None) -> None:
+                            h_saved: torch.Tensor, workspace: torch.Tensor, variant: int = LQ_VARIANT_FUSED,
+                            use_perm: bool = True, stream=None) -> None:
     assert x.dtype == torch.bfloat16 and dy.dtype == torch.bfloat16 and dx.dtype == torch.bfloat16
     n_tokens, d_in = int(x.shape[0]), int(x.shape[1])
     d_out = int(dy.shape[1])
@@ -235,7 +241,7 @@ def lora_segmented_backward(x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor,
         _ptr(adapters.ranks), _ptr(adapters.scales), adapters.n_adapters, adapters.max_rank,
         _ptr(seg.perm) if use_perm else None, n_tokens,
         _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
-        _ptr(h_saved), _ptr(seg.h_offsets), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _ptr(h_saved), _ptr(seg.h_offsets), variant, _ptr(workspace), workspace.numel() * workspace.element_size(),
         _stream(stream))
     if st != LQ_OK:
         raise LqError(st, "lora_segmented_backward")

@@ -65,6 +65,17 @@ extern "C" lq_status lora_profile_read(double* total_us, int64_t* launches, int3
     return status;
 }
 
+extern "C" size_t lora_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in, int32_t d_out)
+{
+    size_t need = lora_build_workspace_bytes(n_tokens, n_adapters);
+    for (int variant = LQ_VARIANT_SPLIT; variant <= LQ_VARIANT_EXPAND_ONLY; ++variant) {
+        const size_t f = lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant);
+        if (f > need) need = f;
+    }
+    const size_t b = lora_backward_workspace_bytes(n_tokens, n_adapters, max_rank, d_in, d_out);
+    return b > need ? b : need;
+}
+
 extern "C" const char* lora_status_string(lq_status status)
 {
     switch (status) {

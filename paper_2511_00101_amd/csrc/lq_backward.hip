@@ -333,11 +333,12 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
                                              const int32_t* seg_starts, const int32_t* seg_adapter,
                                              const uint8_t* seg_kind, const int32_t* n_segments, int32_t max_segments,
                                              const float* h_saved, const int64_t* h_offsets,
-                                             void* workspace, size_t workspace_bytes, void* stream)
+                                             int32_t variant, void* workspace, size_t workspace_bytes, void* stream)
 {
     using namespace lq;
     if (n_tokens < 0 || d_in <= 0 || d_out <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1)
         return LQ_ERR_INVALID_ARG;
+    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED) return LQ_ERR_INVALID_ARG;
     if (!A_ptrs || !B_ptrs || !ranks || !scales || !seg_starts || !seg_adapter || !seg_kind || !n_segments)
         return LQ_ERR_INVALID_ARG;
     if (n_tokens > 0 && (!x || !dy || !dx)) return LQ_ERR_INVALID_ARG;
@@ -374,12 +375,12 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     s1.h_out = want_w ? gsum : nullptr; s1.h_offsets = want_w ? reinterpret_cast<const long long*>(h_offsets) : nullptr;
     s1.hpart = reinterpret_cast<float*>(ws + kWsHeaderBytes);
     s1.ksplit = 1; s1.rstride = rstride_for(max_rank);
-    s1.err = reinterpret_cast<int*>(ws); s1.tickets = reinterpret_cast<int*>(ws) + 4;
+    s1.header = s1.err = reinterpret_cast<int*>(ws); s1.tickets = reinterpret_cast<int*>(ws) + 4;
     s1.ksplit_hint = 0; s1.kinds = kFinetuneOnly;
-    // 2. dx += s g A on fine-tune rows: the forward's expand over d_in against A.  Both in the single-launch
-    // variant when its buffer descriptor can address the slices (else two launches with the same k split).
+    // 2. dx += s g A on fine-tune rows: the forward's expand over d_in against A.  LQ_VARIANT_FUSED: both in a
+    // single launch when its buffer descriptor can address the slices; else two launches with the same k split.
     // Whichever phase finishes g (the shrink without a split, the expand with one) also stores it to gsum.
-    const bool one_launch = h_slices_bytes(n_tokens, max_rank) <= 0x7fffffffull;
+    const bool one_launch = variant == LQ_VARIANT_FUSED && h_slices_bytes(n_tokens, max_rank) <= 0x7fffffffull;
     s1.coherent = one_launch; s1.hpart_bytes = one_launch ? (unsigned int)h_slices_bytes(n_tokens, max_rank) : 0;
     if (one_launch) {
         if (run_shrink_expand(s1, LQ_VARIANT_FUSED, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;

@@ -320,7 +320,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_segments_multi_kernel(
         for (int i = 0; i < kBuildWaves; ++i) mine += lds_hist[tid * kBuildWaves + i];
         __hip_atomic_store(counts + tid * n_groups + g, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (!grid_barrier(header, gen0, [] {})) {
+    if (!grid_barrier(header, header, gen0, [] {})) {
         // the counts never met (bit 1 of the error word is set): an empty batch is the only safe answer
         if (g == 0 && tid == 0) {
             seg_starts[0] = 0;

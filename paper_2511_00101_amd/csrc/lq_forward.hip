@@ -1217,7 +1217,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     const Segs<FwdParams> sg = load_segs(p);
     // The generation is read before this workgroup arrives, hence before the last arrival can change it;
     // and after the table loads, so that their results need not wait for this slower, uncached load.
-    const int gen0 = __hip_atomic_load(p.err + kBarGen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int gen0 = __hip_atomic_load(p.header + kBarGen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
     LQ_STAMP(1, 0);
@@ -1226,7 +1226,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
     ExpandPlan plan;
     ShortAhead ahead;
     LongAhead<KSTEPS, PAIRS> lahead;
-    const bool opened = grid_barrier(p.err, gen0, [&]() {
+    const bool opened = grid_barrier(p.header, p.err, gen0, [&]() {
         plan = plan_expand<KSTEPS, PAIRS>(p, sg);
         ahead = short_request(p, sg, plan);
         lahead = long_request<KSTEPS, PAIRS>(p, sg, plan);
@@ -1375,19 +1375,19 @@ extern "C" size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_ran
     return (size_t)lq::kWsHeaderBytes + lq::h_slices_bytes(n_tokens, max_rank);
 }
 
-extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
-                                            int32_t d_in, int32_t d_out,
-                                            const void* const* A_ptrs, const void* const* B_ptrs,
-                                            const int32_t* ranks, const float* scales, int32_t n_adapters,
-                                            int32_t max_rank,
-                                            const int32_t* perm, int32_t n_tokens,
-                                            const int32_t* seg_starts, const int32_t* seg_adapter,
-                                            const uint8_t* seg_kind,
-                                            const int32_t* n_segments, int32_t max_segments,
-                                            float* h_out, const int64_t* h_offsets,
-                                            int32_t variant, void* workspace, size_t workspace_bytes, void* stream)
+namespace lq {
+namespace {
+
+// Host-side checks and launch shared by the entry points below.  err_word: where the kernels report device-side
+// errors (NULL: word 0 of the workspace).
+lq_status forward_checked(const void* x, int64_t ldx, void* y, int64_t ldy, int32_t d_in, int32_t d_out,
+                          const void* const* A_ptrs, const void* const* B_ptrs, const int32_t* ranks, const float* scales,
+                          int32_t n_adapters, int32_t max_rank, const int32_t* perm, int32_t n_tokens,
+                          const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
+                          const int32_t* n_segments, int32_t max_segments, float* h_out, const int64_t* h_offsets,
+                          int32_t variant, void* workspace, size_t workspace_bytes, int32_t* err_word, hipStream_t stream,
+                          bool launch)
 {
-    using namespace lq;
     if (n_tokens < 0 || d_in <= 0 || d_out <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1)
         return LQ_ERR_INVALID_ARG;
     if (variant < LQ_VARIANT_SPLIT || variant > LQ_VARIANT_EXPAND_ONLY) return LQ_ERR_INVALID_ARG;
@@ -1403,7 +1403,7 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
         return LQ_ERR_WORKSPACE;
     // the fused variant addresses the partial-h region through a buffer descriptor with 32-bit offsets
     if (variant == LQ_VARIANT_FUSED && h_slices_bytes(n_tokens, max_rank) > 0x7fffffffull) return LQ_ERR_UNSUPPORTED;
-    if (n_tokens == 0 || max_segments == 0) return LQ_OK;
+    if (n_tokens == 0 || max_segments == 0 || !launch) return LQ_OK;
 
     FwdParams p;
     p.x = static_cast<const u16*>(x); p.ldx = ldx;
@@ -1416,8 +1416,9 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     p.n_segments = n_segments; p.max_segments = max_segments;
     p.h_out = h_out; p.h_offsets = reinterpret_cast<const long long*>(h_offsets);
     p.rstride = rstride_for(max_rank);
-    p.err = static_cast<int*>(workspace);
-    p.tickets = static_cast<int*>(workspace) + 4;
+    p.header = static_cast<int*>(workspace);
+    p.err = err_word ? err_word : p.header;
+    p.tickets = p.header + 4;
     p.hpart = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWsHeaderBytes);
 
     int seg_bound = max_segments;
@@ -1428,5 +1429,25 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     p.kinds = kAllKinds;
     p.coherent = variant == LQ_VARIANT_FUSED;
     p.hpart_bytes = (unsigned int)h_slices_bytes(n_tokens, max_rank);
-    return run_shrink_expand(p, variant, seg_bound, static_cast<hipStream_t>(stream)) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    return run_shrink_expand(p, variant, seg_bound, stream) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+}
+
+}  // namespace
+}  // namespace lq
+
+extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
+                                            int32_t d_in, int32_t d_out,
+                                            const void* const* A_ptrs, const void* const* B_ptrs,
+                                            const int32_t* ranks, const float* scales, int32_t n_adapters,
+                                            int32_t max_rank,
+                                            const int32_t* perm, int32_t n_tokens,
+                                            const int32_t* seg_starts, const int32_t* seg_adapter,
+                                            const uint8_t* seg_kind,
+                                            const int32_t* n_segments, int32_t max_segments,
+                                            float* h_out, const int64_t* h_offsets,
+                                            int32_t variant, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return lq::forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, n_adapters, max_rank, perm, n_tokens,
+                               seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets, variant,
+                               workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream), true);
 }

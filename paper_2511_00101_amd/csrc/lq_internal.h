@@ -23,7 +23,8 @@ struct FwdParams {
     int ksplit;      // a power of two
     int ks_log2;
     int rstride;     // 32, 64 or 128
-    int* err;
+    int* header;     // the workspace header (4096 bytes): ticket counters and the barrier's words
+    int* err;        // error word (normally word 0 of the header)
     int ksplit_hint; // host only: > 0 forces this split (the expand half of a pair repeats the shrink half's)
     int kinds;       // bit k set: segments of kind k take part (forward: all; backward: fine-tune only)
     int coherent;    // fused variant: the h slices are written and read with device-scope accesses
@@ -45,7 +46,7 @@ hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream
 // ---- device-wide barrier of a launch whose workgroups are all resident (grid = occupancy x compute units) ----
 // Data that crosses it must be written and read with device-scope accesses (the XCDs' L2 caches are not
 // coherent with each other); the barrier itself uses no cache write-back or invalidation.  header: the
-// workspace header (error word at 0); gen0: the generation word read before this workgroup arrives.  The
+// workspace header; err: the error word; gen0: the generation word read before this workgroup arrives.  The
 // wait is bounded; a timeout sets bit 1 of the error word and the caller's next phase is skipped.
 constexpr int kErrBarrierTimeout = 2;
 constexpr int kBarrierSpinLimit = 1 << 20;
@@ -67,7 +68,7 @@ __device__ __forceinline__ bool barrier_poisoned(int gen0) { return (gen0 & kBar
 // `overlap` runs in every thread between the workgroup's arrival and its wait for the others.  Returns true
 // (in every thread of the workgroup) if the barrier opened, false if the wait ran out here or elsewhere.
 template <class Overlap>
-__device__ __forceinline__ bool grid_barrier(int* header, int gen0, Overlap&& overlap)
+__device__ __forceinline__ bool grid_barrier(int* header, int* err, int gen0, Overlap&& overlap)
 {
     // every thread's device-scope (written-through) stores are acknowledged before its workgroup arrives
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -100,7 +101,7 @@ __device__ __forceinline__ bool grid_barrier(int* header, int gen0, Overlap&& ov
         }
         if (now != opened) {
             failed = 1;
-            atomicOr(header, kErrBarrierTimeout);
+            atomicOr(err, kErrBarrierTimeout);
             if (!barrier_poisoned(now))
                 __hip_atomic_store(gen, gen0 | kBarPoison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }

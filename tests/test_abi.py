@@ -45,6 +45,11 @@ def test_workspace_sizes(lqlib):
     assert lqlib.lora_build_workspace_bytes(100, 64) >= 256
     c = lqlib.lora_backward_workspace_bytes(1024, 4, 16, 512, 768)
     assert c > lqlib.lora_forward_workspace_bytes(1024, 16, 512, 768, 0)
+    # the one-size-fits-all answer is the largest of the per-call ones
+    for (T, n_ad, r, d_in, d_out) in ((1024, 4, 16, 512, 768), (256, 64, 16, 4096, 4096), (100000, 2000, 128, 64, 64), (0, 1, 1, 8, 8)):
+        each = [lqlib.lora_build_workspace_bytes(T, n_ad), lqlib.lora_backward_workspace_bytes(T, n_ad, r, d_in, d_out)]
+        each += [lqlib.lora_forward_workspace_bytes(T, r, d_in, d_out, v) for v in range(4)]
+        assert lqlib.lora_workspace_bytes(T, n_ad, r, d_in, d_out) == max(each)
 
 
 def test_host_validation_returns_codes_without_launching(lqlib):
@@ -70,10 +75,11 @@ def test_host_validation_returns_codes_without_launching(lqlib):
     assert fwd(T=0) == lqlib.LQ_OK                                # empty batch: nothing to do, nothing launched
 
     def bwd(x=one, dy=al, dx=ctypes.c_void_p(0x3000), d_in=64, d_out=64, ldx=64, T=4, ws=ctypes.c_void_p(0x4000),
-            ws_bytes=1 << 30, max_rank=8):
+            ws_bytes=1 << 30, max_rank=8, variant=1):
         return L.lora_segmented_backward(x, ldx, dy, 64, dx, 64, d_in, d_out, one, one, None, None, one, one, 2, max_rank,
-                                         one, T, one, one, one, one, 4, None, None, ws, ws_bytes, None)
+                                         one, T, one, one, one, one, 4, None, None, variant, ws, ws_bytes, None)
 
+    assert bwd(variant=2) == lqlib.LQ_ERR_INVALID_ARG            # only the two-launch and the single-launch forms
     assert bwd(d_in=0) == lqlib.LQ_ERR_INVALID_ARG
     assert bwd(dx=one) == lqlib.LQ_ERR_INVALID_ARG               # dx aliases x
     assert bwd(ldx=8) == lqlib.LQ_ERR_INVALID_ARG

@@ -16,7 +16,11 @@ WGRAD_REL_FROBENIUS = 1e-3
 WGRAD_REL_MAX = 2e-3   # of the largest reference magnitude
 
 
-def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_SPLIT, dx0_seed=5):
+VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED]
+
+
+def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_FUSED, dx0_seed=5):
+    """Forward (for the saved h) and backward, both in `variant`, against the oracle's gradient."""
     rng = np.random.default_rng(dx0_seed)
     dx0 = synth.normal_bf16(rng, (p.n_tokens, p.d_in), 1.0)
     ref_f = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
@@ -32,7 +36,7 @@ def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_SPLIT, dx0_seed=5):
     dA_ptrs = torch.tensor([t.data_ptr() for t in dA], dtype=torch.int64, device=dev)
     dB_ptrs = torch.tensor([t.data_ptr() for t in dB], dtype=torch.int64, device=dev)
     ws = lq.workspace(lq.lora_backward_workspace_bytes(p.n_tokens, p.n_adapters, d.adapters.max_rank, p.d_in, p.d_out), dev)
-    lq.lora_segmented_backward(d.x, d.dy, dx, d.adapters, dA_ptrs, dB_ptrs, d.seg, d.h_out, ws)
+    lq.lora_segmented_backward(d.x, d.dy, dx, d.adapters, dA_ptrs, dB_ptrs, d.seg, d.h_out, ws, variant)
     torch.cuda.synchronize()
     assert int(ws[0].item() & 0xffffffff) == 0
 
@@ -64,10 +68,11 @@ def test_backward_tiny_config1(oracle_mod):
     (12, 700, 1032, 776, [16, 128, 5, 24]),
     (13, 1300, 2048, 1024, [32, 32]),        # segments longer than one 512-row weight-gradient chunk
 ])
-def test_backward_small_mixed(oracle_mod, seed, T, d_in, d_out, ranks):
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_backward_small_mixed(oracle_mod, variant, seed, T, d_in, d_out, ranks):
     p = synth.small_mixed(seed, T, d_in, d_out, ranks, drop_frac=0.1, with_dy=True, w_std=0.03,
                           scales=np.linspace(0.5, 1.5, len(ranks)))
-    run_backward(oracle_mod, p)
+    run_backward(oracle_mod, p, variant)
 
 
 def test_backward_without_weight_gradients(oracle_mod):
@@ -94,10 +99,11 @@ def test_backward_repeat_is_bit_identical(oracle_mod):
 
 
 @pytest.mark.parametrize("layer,projection", [(0, 0), (0, 1), (31, 4), (31, 6)])
-def test_backward_config5_calls(oracle_mod, layer, projection):
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_backward_config5_calls(oracle_mod, variant, layer, projection):
     """The four distinct shapes of the 224 (layer, projection) calls of the layer stack (q, k, gate, down) with
     their seeded dy."""
-    run_backward(oracle_mod, synth.config5(layer, projection, with_dy=True))
+    run_backward(oracle_mod, synth.config5(layer, projection, with_dy=True), variant)
 
 
 def test_backward_many_adapters_and_tokens(oracle_mod):
@@ -117,4 +123,5 @@ def test_backward_many_adapters_and_tokens(oracle_mod):
 
 def test_backward_many_tokens(oracle_mod):
     """40000 tokens, two fine-tune segments of thousands of rows: weight gradients from many row chunks."""
-    run_backward(oracle_mod, long_batch_problem(901, with_dy=True))
+    for variant in VARIANTS:
+        run_backward(oracle_mod, long_batch_problem(901, with_dy=True), variant)
