@@ -147,6 +147,34 @@ lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ld
                                  int32_t variant, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The forward for callers that CANNOT ALLOCATE device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * lora_segmented_forward, minus the workspace: the partial-h buffer and the counters live in a
+ * device array that belongs to the library (LQ_STATIC_WORKSPACE_BYTES, held by every GPU the
+ * library runs on until the process ends).  The call allocates nothing and enqueues only kernels
+ * (one small fill kernel that clears the counters, then the forward's).
+ *   variant     LQ_VARIANT_SPLIT or LQ_VARIANT_FUSED (else LQ_ERR_INVALID_ARG)
+ *   error_word  device int32, may be NULL: receives (ORed in) the bits the workspace's word 0 would;
+ *               with NULL those bits are not visible to the caller
+ *   LQ_ERR_WORKSPACE if lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) exceeds
+ *   LQ_STATIC_WORKSPACE_BYTES (32 MiB of partial h: 8192 tokens at ranks up to 64, 65536 tokens at ranks
+ *   up to 32 ...); use the call above with a workspace of your own then.
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *   streams, or threads) race; calls on one stream are ordered and safe.
+ * ------------------------------------------------------------------------------------------- */
+#define LQ_STATIC_WORKSPACE_BYTES (4096 + (32 << 20))
+
+lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int64_t ldy,
+                                        int32_t d_in, int32_t d_out,
+                                        const void* const* A_ptrs, const void* const* B_ptrs,
+                                        const int32_t* ranks, const float* scales, int32_t n_adapters, int32_t max_rank,
+                                        const int32_t* perm, int32_t n_tokens,
+                                        const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
+                                        const int32_t* n_segments, int32_t max_segments,
+                                        float* h_out, const int64_t* h_offsets,
+                                        int32_t variant, int32_t* error_word, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Backward of the forward above for FINE-TUNE segments (other kinds are skipped).  The paper
  * leaves this to autograd, one call per LoRA linear, and names a dedicated kernel as future
  * work (Section 4.2, Appendix A).  Exact gradient of the forward as defined here, with

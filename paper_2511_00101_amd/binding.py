@@ -18,6 +18,7 @@ LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, LQ_ERR_HIP = ra
 LQ_SEG_FINETUNE, LQ_SEG_PREFILL, LQ_SEG_DECODE = 0, 1, 2
 LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED, LQ_VARIANT_SHRINK_ONLY, LQ_VARIANT_EXPAND_ONLY = 0, 1, 2, 3
 LQ_MAX_RANK = 128
+LQ_STATIC_WORKSPACE_BYTES = 4096 + (32 << 20)
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblqlora.so")
 _lib = None
@@ -32,6 +33,8 @@ _SIGNATURES = {
     "lora_forward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_segmented_forward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _i32,
                                               _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
+    "lora_segmented_forward_static": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _i32,
+                                                     _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp]),
     "lora_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_segmented_backward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp,
                                                _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
@@ -221,6 +224,17 @@ def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTa
     st = lib().lora_segmented_forward(*_forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream))
     if st != LQ_OK:
         raise LqError(st, "lora_segmented_forward")
+
+
+def lora_segmented_forward_static(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,
+                                  h_out: Optional[torch.Tensor], error_word: Optional[torch.Tensor] = None,
+                                  variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None) -> None:
+    """The forward with the library's own device array as workspace (allocates nothing)."""
+    args = _forward_args(x, y, adapters, seg, h_out, None, variant, use_perm, stream)
+    assert error_word is None or error_word.dtype == torch.int32
+    st = lib().lora_segmented_forward_static(*args[:22], _ptr(error_word), args[24])   # all but the workspace pair
+    if st != LQ_OK:
+        raise LqError(st, "lora_segmented_forward_static")
 
 
 def prepare_forward(x, y, adapters, seg, h_out, workspace, variant=LQ_VARIANT_SPLIT, use_perm=True, stream=None) -> PreparedCall:

@@ -27,6 +27,7 @@
 // row-contiguous pattern as long as nothing else competes for the address path, which is why A_a, B_a
 // and h reach the MFMA through LDS instead.
 #include "lq_internal.h"
+#include <mutex>
 #include <type_traits>
 
 namespace lq {
@@ -1450,4 +1451,78 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
     return lq::forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, n_adapters, max_rank, perm, n_tokens,
                                seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets, variant,
                                workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream), true);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The forward for callers that cannot allocate (code under HIP graph capture, tight serving loops): the workspace
+// is a file-scope device array instead of a caller buffer.  Every GPU holds its own copy of the array at its own
+// address, looked up once per device; host code only ever uses that looked-up address, never the array's name.
+// ---------------------------------------------------------------------------------------------------------------
+namespace lq {
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[LQ_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];  // per device: address of that device's copy of `scratch` (null: not looked up yet)
+std::mutex g_scratch_mutex;
+
+// address of the current device's scratch array (looked up on the first call on that device), or null
+void* scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+// The header's counters must start at zero.  Every launch leaves them there, except one whose device-wide wait ran
+// out; the previous call's partial h may stay.  A fill kernel rather than a memset node, so that the call can be
+// captured into a graph.
+__global__ __launch_bounds__(1024) void clear_header_kernel(int* header)
+{
+    header[threadIdx.x] = 0;
+}
+
+}  // namespace
+}  // namespace lq
+
+extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int64_t ldy,
+                                                   int32_t d_in, int32_t d_out,
+                                                   const void* const* A_ptrs, const void* const* B_ptrs,
+                                                   const int32_t* ranks, const float* scales, int32_t n_adapters,
+                                                   int32_t max_rank,
+                                                   const int32_t* perm, int32_t n_tokens,
+                                                   const int32_t* seg_starts, const int32_t* seg_adapter,
+                                                   const uint8_t* seg_kind,
+                                                   const int32_t* n_segments, int32_t max_segments,
+                                                   float* h_out, const int64_t* h_offsets,
+                                                   int32_t variant, int32_t* error_word, void* stream)
+{
+    using namespace lq;
+    static_assert(kWsHeaderBytes == 1024 * sizeof(int), "clear_header_kernel clears one word per thread");
+    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED) return LQ_ERR_INVALID_ARG;
+    // (sizes first: a batch beyond the array's capacity is refused whatever else is wrong with the call)
+    if (n_tokens > 0 && max_rank >= 1 && max_rank <= LQ_MAX_RANK &&
+        lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) > (size_t)LQ_STATIC_WORKSPACE_BYTES)
+        return LQ_ERR_WORKSPACE;
+    // host-side validation with a stand-in workspace address: nothing is launched, nothing is dereferenced
+    void* const stand_in = reinterpret_cast<void*>(uintptr_t{256});
+    lq_status status = forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, n_adapters, max_rank, perm,
+                                       n_tokens, seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets,
+                                       variant, stand_in, (size_t)LQ_STATIC_WORKSPACE_BYTES, error_word, nullptr, false);
+    if (status != LQ_OK || n_tokens == 0 || max_segments == 0) return status;
+    void* ws = scratch_of_current_device();
+    if (!ws) return LQ_ERR_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(clear_header_kernel, dim3(1), dim3(1024), 0, st, static_cast<int*>(ws));
+    if (hipGetLastError() != hipSuccess) return LQ_ERR_HIP;
+    return forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, n_adapters, max_rank, perm, n_tokens,
+                           seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets, variant, ws,
+                           (size_t)LQ_STATIC_WORKSPACE_BYTES, error_word, st, true);
 }

@@ -1,0 +1,87 @@
+"""The forward entry point that allocates nothing (its workspace is a device array that belongs to the library),
+called through the C ABI and compared with the entry point that takes a caller workspace: same kernels, same
+order of every sum, so the outputs must be bit-identical; and both must match the oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_00101_amd import binding as lq
+from paper_2511_00101_amd import synth
+
+from gpu_util import DeviceProblem, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _call_static(d, h_out, err, variant):
+    """Raw C-ABI call (ctypes), arguments in the order of include/lqlora.h."""
+    p = d.p
+    L = lq.lib()
+    st = L.lora_segmented_forward_static(
+        d.x.data_ptr(), d.x.stride(0), d.y.data_ptr(), d.y.stride(0), p.d_in, p.d_out,
+        d.adapters.A_ptrs.data_ptr(), d.adapters.B_ptrs.data_ptr(), d.adapters.ranks.data_ptr(), d.adapters.scales.data_ptr(),
+        d.adapters.n_adapters, d.adapters.max_rank, d.seg.perm.data_ptr(), p.n_tokens,
+        d.seg.seg_starts.data_ptr(), d.seg.seg_adapter.data_ptr(), d.seg.seg_kind.data_ptr(), d.seg.n_segments.data_ptr(),
+        d.seg.max_segments, h_out.data_ptr(), d.seg.h_offsets.data_ptr(), variant, err.data_ptr(),
+        torch.cuda.current_stream().cuda_stream)
+    return st
+
+
+def _one(oracle_mod, p, variant):
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    # the existing entry point, caller workspace
+    a = DeviceProblem(p)
+    a.build()
+    y_ws, h_ws, err_ws = a.forward(variant, h_elems=ref.segments.h_elems)
+    assert err_ws == 0
+    # the entry point under test
+    b = DeviceProblem(p)
+    b.build()
+    h_out = torch.full((max(ref.segments.h_elems, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert _call_static(b, h_out, err, variant) == lq.LQ_OK
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    y_st = lq.bits_from_bf16(b.y)
+    h_st = h_out[: ref.segments.h_elems].cpu().numpy()
+    assert np.array_equal(y_st, y_ws), "y differs from the caller-workspace entry point"
+    assert np.array_equal(h_st, h_ws), "h_out differs from the caller-workspace entry point"
+    assert_close(synth.bf16_bits_to_f64(y_st), ref.y, f"{p.name} y")
+    assert_close(h_st, ref.h, f"{p.name} h_out")
+
+
+@pytest.mark.parametrize("variant", [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED])
+def test_static_workspace_forward_two_calls_in_a_row(oracle_mod, variant):
+    """Two calls in a row on the same GPU (they share its array, which keeps the first call's contents), the second
+    with a smaller batch, a smaller rank stride and no k split."""
+    _one(oracle_mod, synth.config3(), variant)                                        # 4864 tokens, k split, saved h
+    _one(oracle_mod, synth.small_mixed(61, 300, 1032, 776, [16, 128, 5, 24, 33], drop_frac=0.1, w_std=0.05), variant)
+    _one(oracle_mod, synth.config1(), variant)
+
+
+def test_static_workspace_forward_refuses_what_does_not_fit():
+    p = synth.config1()
+    d = DeviceProblem(p)
+    d.build()
+    h_out = torch.zeros(64 * 8, dtype=torch.float32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    L = lq.lib()
+    big_T = 200000     # rank stride 128 x 4 bytes x 200000 tokens > 32 MiB
+
+    def call(n_tokens, max_rank, variant=lq.LQ_VARIANT_SPLIT):
+        return L.lora_segmented_forward_static(
+            d.x.data_ptr(), d.x.stride(0), d.y.data_ptr(), d.y.stride(0), p.d_in, p.d_out,
+            d.adapters.A_ptrs.data_ptr(), d.adapters.B_ptrs.data_ptr(), d.adapters.ranks.data_ptr(),
+            d.adapters.scales.data_ptr(), d.adapters.n_adapters, max_rank, d.seg.perm.data_ptr(), n_tokens,
+            d.seg.seg_starts.data_ptr(), d.seg.seg_adapter.data_ptr(), d.seg.seg_kind.data_ptr(),
+            d.seg.n_segments.data_ptr(), d.seg.max_segments, h_out.data_ptr(), d.seg.h_offsets.data_ptr(), variant,
+            err.data_ptr(), None)
+
+    assert lq.lora_forward_workspace_bytes(big_T, 128, p.d_in, p.d_out, 0) > lq.LQ_STATIC_WORKSPACE_BYTES
+    assert call(big_T, 128) == lq.LQ_ERR_WORKSPACE          # refused on the host: nothing is launched
+    assert call(p.n_tokens, 8, variant=lq.LQ_VARIANT_SHRINK_ONLY) == lq.LQ_ERR_INVALID_ARG
+    y_before = lq.bits_from_bf16(d.y)
+    torch.cuda.synchronize()
+    assert np.array_equal(lq.bits_from_bf16(d.y), y_before)
