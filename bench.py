@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the segmented multi-LoRA hot path on one MI355X.
 
-A step = one pass of the whole path over one batch: segment-metadata builder + forward (shrink,
-h-save, expand; split or fused variant) [+ backward of the fine-tune rows for the layer-stack
-workload].  Inputs are synthetic (paper_2511_00101_amd/synth.py), already resident in HBM, and
-rotated over enough replicas (> 1 GiB in total) that no step finds its operands in L2 or in the
-Infinity Cache left there by the previous step.
+Headline (`value`, `roofline`, `cpu_baseline`): the forward of the 8B-shaped 32-layer stack, the largest
+configuration (benchmark configs[4]): a step = segment-metadata builder + the 224 forward calls (7 LoRA
+projections x 32 layers; shrink, h-save, expand in one launch each) over one mixed batch of 5632 tokens; `value`
+= tokens of the batch / step time.  `configs` carries the single-call workloads (a step = builder + forward,
+operands rotated over > 1 GiB of replicas) and the layer stack's backward.  Inputs are synthetic, resident in HBM
+before the timed region, and no two calls share an operand, so that nothing the accounting counts is served from L2
+or the Infinity Cache.
 
-Prints ONE JSON line (see README/DESIGN for the fields).  `value` is tokens/s of the headline
-workload (the decode-heavy batch, benchmark configs[1]); `roofline` is the HBM roofline of the
-dominant kernel from HIP-event timing of each launch (the dispatch's own start and end time stamps); `cpu_baseline` is the fp64 oracle on the host
-cores; `configs` carries the same measurements for the other single-call workloads.
+`roofline` is the HBM roofline of the dominant kernel: algorithmic bytes per launch / that kernel's average launch
+duration, taken from the dispatches' own start and end time stamps (HIP events on the launch stream, see
+lora_profile_enable); `traffic` is read from the committed rocprofv3 counter summary under profiles/.
+`cpu_baseline` is the fp64 oracle on the host cores on a bounded sample.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -98,39 +100,16 @@ class Replicas:
         forward()
 
 
-def time_steps(rep, steps, warmup):
-    """Wall clock over exactly `steps` steps, synchronised on both sides."""
-    torch = rep.torch
-    for i in range(warmup):
-        rep.step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        rep.step(warmup + i)
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
-
-
-def time_kernels(rep, steps, warmup):
-    """Average duration of each kernel over `steps` steps, from HIP events on the launch stream: the library
-    launches every kernel with a pair of events that receive the dispatch's own start and end time stamps
-    (lora_profile_enable / lora_profile_read), which is the duration rocprofv3's kernel trace reports
-    (profiles/), without the gaps between launches."""
-    torch, lq = rep.torch, rep.lq
-    for i in range(warmup):
-        rep.step(i)
-    torch.cuda.synchronize()
-    lq.lora_profile_enable(True)
-    for i in range(steps):
-        rep.step(warmup + i)
-    torch.cuda.synchronize()
-    prof = lq.lora_profile_read()
-    lq.lora_profile_enable(False)
-    return {name: dict(avg_us=total / n, launches=n) for name, (total, n) in prof.items() if n}
-
-
 PROFILE_FILES = dict(cfg2_decode_heavy="forward_cfg2_decode_heavy.txt", cfg3_unified="forward_cfg3_unified.txt",
-                     cfg4_mlp_up="forward_cfg4_mlp_up.txt", cfg4_mlp_down="forward_cfg4_mlp_down.txt")
+                     cfg4_mlp_up="forward_cfg4_mlp_up.txt", cfg4_mlp_down="forward_cfg4_mlp_down.txt",
+                     cfg5_layer_stack="forward_cfg5_layer_stack.txt")
+
+
+def traffic_source(workload):
+    """Where roofline.traffic comes from: counters need rocprofv3, so the figure is the one of the committed
+    summary of this workload (it goes stale when a kernel changes; the summary names its command)."""
+    name = PROFILE_FILES.get(workload)
+    return f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by profiles/copy_calibration.txt)" if name else None
 
 
 def counter_traffic(workload, phase):
@@ -148,10 +127,12 @@ def counter_traffic(workload, phase):
 
 
 def measure(p, variant, steps, warmup):
+    """One single-call workload: a step = segment builder + forward."""
+    import torch
     work = algorithmic_work(p)
     rep = Replicas(p, variant)
-    s_per_step = time_steps(rep, steps, warmup)
-    kern = time_kernels(rep, steps, warmup)
+    s_per_step, per_step = timed_steps(torch, rep.step, steps, warmup)
+    kern = profiled(rep.lq, torch, lambda: [rep.step(warmup + i) for i in range(steps)])
     fwd_names = [k for k in kern if k != "build"]
     fwd_us = sum(kern[k]["avg_us"] for k in fwd_names)
     if "forward_fused" in kern:
@@ -160,33 +141,40 @@ def measure(p, variant, steps, warmup):
         dom = "expand" if work["expand"] >= work["shrink"] else "shrink"
         dom_bytes = work[dom]
     dom_gbps = dom_bytes / (kern[dom]["avg_us"] * 1e-6) / 1e9
+    traffic = counter_traffic(p.name, dom)
     res = dict(
-        workload=p.name, tokens=work["tokens"], d_in=p.d_in, d_out=p.d_out, replicas=rep.n,
-        ms_per_step=s_per_step * 1e3, tokens_per_s=work["tokens"] / s_per_step,
+        workload=p.name, tokens=work["tokens"], d_in=p.d_in, d_out=p.d_out, replicas=rep.n, steps=steps,
+        ms_per_step=s_per_step * 1e3, per_step=per_step, tokens_per_s=work["tokens"] / s_per_step,
         forward_us=fwd_us, forward_gbps=work["total"] / (fwd_us * 1e-6) / 1e9,
         forward_tflops=work["flops"] / (fwd_us * 1e-6) / 1e12,
         forward_hbm_frac=work["total"] / (fwd_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
         forward_mfma_frac=work["flops"] / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         algorithmic_bytes=work["total"], flops=work["flops"], kernels=kern,
         roofline=dict(bound="hbm", kernel=dom, achieved=dom_gbps, peak=HBM_PEAK_GBPS, unit="GB/s",
-                      frac=dom_gbps / HBM_PEAK_GBPS, traffic=counter_traffic(p.name, dom), algorithmic_bytes=dom_bytes,
-                      avg_launch_us=kern[dom]["avg_us"]))
+                      frac=dom_gbps / HBM_PEAK_GBPS, traffic=traffic, traffic_source=traffic_source(p.name) if traffic else None,
+                      algorithmic_bytes=dom_bytes, avg_launch_us=kern[dom]["avg_us"]),
+        error_word=int(rep.fws[0].item() & 0xffffffff) | int(rep.bws[0].item() & 0xffffffff))
     del rep
     return res
 
 
+LAYER_STACK_NAME = "cfg5_layer_stack"
+
+
 class LayerStack:
     """The 8B-shaped 32-layer stack (benchmark configs[4]): 7 LoRA projections per layer with their own
-    adapter weights, one batch structure for all 224 calls; forward of every call, then backward of the
-    fine-tune rows of every call.  Activations and weights are drawn on the GPU (same distributions as the
-    seeded generators; the parity tests use the seeded ones on sampled calls)."""
+    adapter weights, one batch structure for all 224 calls.  Every call has its OWN x, y (and dx) tensor, so no
+    byte that the accounting counts can come from the Infinity Cache left there by a neighbouring call (in a
+    real layer q, k, v and gate, up read the same x: that sharing is not exploited and not counted here).
+    Activations and weights are drawn on the GPU with torch's generator (same distributions as the seeded
+    generators; the parity tests run the seeded ones on sampled calls, this loop is timed, not checked)."""
 
-    def __init__(self, variant, n_layers=None):
+    def __init__(self, variant, with_backward, n_layers=None):
         import numpy as np
         import torch
         from paper_2511_00101_amd import binding as lq
         from paper_2511_00101_amd import synth
-        self.lq, self.torch, self.variant = lq, torch, variant
+        self.lq, self.torch, self.variant, self.with_backward = lq, torch, variant, with_backward
         self.n_layers = n_layers or synth.N_LAYERS
         dev = "cuda"
         b = synth.config5_batch()
@@ -194,109 +182,185 @@ class LayerStack:
         T = b.n_tokens
         self.T = T
         n_ad, r = 16, 32
-        self.ranks_np = np.full(n_ad, r, np.int32)
+        self.n_adapters, self.rank = n_ad, r
         gen = torch.Generator(device=dev).manual_seed(5000)
         bf = torch.bfloat16
 
-        def act(cols, std=1.0):
-            return (torch.randn(T, cols, generator=gen, device=dev, dtype=torch.float32) * std).to(bf)
+        def act(cols):
+            return torch.randn(T, cols, generator=gen, device=dev, dtype=torch.float32).to(bf)
 
         self.ta = torch.from_numpy(b.token_adapter).to(dev)
         self.tk = torch.from_numpy(b.token_kind).to(dev)
         self.seg = lq.SegmentTables.empty(T, n_ad, dev)
         self.bws = lq.workspace(lq.lora_build_workspace_bytes(T, n_ad), dev)
         self.calls = []
-        max_fws = max_bws = 0
+        max_ws = 0
         for layer in range(self.n_layers):
-            xs = {4096: act(4096), 14336: act(14336)}          # q,k,v,(o),gate,up read a 4096-wide x; down a 14336-wide one
-            x_o = act(4096)
-            dxs = {4096: act(4096), 14336: act(14336)}
-            dx_o = act(4096)
             for pi, (name, d_in, d_out) in enumerate(synth.LAYER_PROJECTIONS):
                 A = [(torch.randn(r, d_in, generator=gen, device=dev) * 0.02).to(bf) for _ in range(n_ad)]
                 B = [(torch.randn(r, d_out, generator=gen, device=dev) * 0.02).to(bf) for _ in range(n_ad)]
                 ad = lq.AdapterTable.from_tensors(A, B, [2.0] * n_ad, dev)
-                y = act(d_out)                                   # y0; after the forward it doubles as dy for the backward
-                dA = [torch.zeros(r, d_in, device=dev) if a < 2 else None for a in range(n_ad)]
-                dB = [torch.zeros(r, d_out, device=dev) if a < 2 else None for a in range(n_ad)]
-                dA_ptrs = torch.tensor([t.data_ptr() if t is not None else 0 for t in dA], dtype=torch.int64, device=dev)
-                dB_ptrs = torch.tensor([t.data_ptr() if t is not None else 0 for t in dB], dtype=torch.int64, device=dev)
-                h_out = torch.zeros(4096 * r, dtype=torch.float32, device=dev)
-                self.calls.append(dict(x=x_o if name == "o" else xs[d_in], dx=dx_o if name == "o" else dxs[d_in], y=y, ad=ad,
-                                       h_out=h_out, dA=dA, dB=dB, dA_ptrs=dA_ptrs, dB_ptrs=dB_ptrs, d_in=d_in, d_out=d_out))
-                max_fws = max(max_fws, lq.lora_forward_workspace_bytes(T, r, d_in, d_out, variant))
-                max_bws = max(max_bws, lq.lora_backward_workspace_bytes(T, n_ad, r, d_in, d_out))
-        self.fws = lq.workspace(max_fws, dev)
-        self.bwd_ws = lq.workspace(max_bws, dev)
+                c = dict(name=name, x=act(d_in), y=act(d_out), ad=ad, d_in=d_in, d_out=d_out,  # y: y0; later it doubles as dy
+                         h_out=torch.zeros(4096 * r, dtype=torch.float32, device=dev))
+                if with_backward:
+                    c["dx"] = act(d_in)
+                    c["dA"] = [torch.zeros(r, d_in, device=dev) if a < 2 else None for a in range(n_ad)]
+                    c["dB"] = [torch.zeros(r, d_out, device=dev) if a < 2 else None for a in range(n_ad)]
+                    c["dA_ptrs"] = torch.tensor([t.data_ptr() if t is not None else 0 for t in c["dA"]], dtype=torch.int64, device=dev)
+                    c["dB_ptrs"] = torch.tensor([t.data_ptr() if t is not None else 0 for t in c["dB"]], dtype=torch.int64, device=dev)
+                self.calls.append(c)
+                max_ws = max(max_ws, lq.lora_workspace_bytes(T, n_ad, r, d_in, d_out) if with_backward
+                             else lq.lora_forward_workspace_bytes(T, r, d_in, d_out, variant))
+        self.ws = lq.workspace(max_ws, dev)
         self.ranks = self.calls[0]["ad"].ranks
+        self.build = lq.prepare_build_segments(self.ta, self.tk, self.ranks, self.seg, self.bws)
+        self.fwd = [lq.prepare_forward(c["x"], c["y"], c["ad"], self.seg, c["h_out"], self.ws, variant) for c in self.calls]
+        self.build()
+        torch.cuda.synchronize()
 
     def work(self):
-        """Algorithmic bytes / flops of one step (forward of all calls + backward of the fine-tune rows)."""
-        import numpy as np
+        """Algorithmic bytes / flops: forward of all calls, and backward of the fine-tune rows of all calls."""
         b = self.batch
         n_live, n_ft = b.n_tokens, int((b.token_kind == 0).sum())
-        r, used, used_ft = 32, 16, 2
+        r, used, used_ft = self.rank, self.n_adapters, 2
         fwd_b = bwd_b = fwd_f = bwd_f = 0
         for c in self.calls:
             di, do = c["d_in"], c["d_out"]
             fwd_b += n_live * di * 2 + n_live * do * 4 + used * r * (di + do) * 2 + n_ft * r * 4
             fwd_f += 2 * r * (di + do) * n_live
-            # backward: dy and x read once each for the weight gradients and once for g / dx's operands are the same
-            # rows, dx read + written, A and B of the fine-tune adapters, dA and dB read + written, h read
+            # backward: dy and x of the fine-tune rows read once, dx read + written, A and B of the fine-tune adapters,
+            # dA and dB read + written, the saved h read
             bwd_b += n_ft * do * 2 + n_ft * di * 2 + n_ft * di * 4 + used_ft * r * (di + do) * 2 + used_ft * r * (di + do) * 8 + n_ft * r * 4
             bwd_f += 2 * r * (di + do) * n_ft * 2
-        return dict(fwd_bytes=fwd_b, bwd_bytes=bwd_b, fwd_flops=fwd_f, bwd_flops=bwd_f, tokens=n_live)
+        return dict(fwd_bytes=fwd_b, bwd_bytes=bwd_b, fwd_flops=fwd_f, bwd_flops=bwd_f, tokens=n_live, calls=len(self.calls))
 
     def step(self, i=0):
-        lq = self.lq
-        lq.lora_build_segments(self.ta, self.tk, self.ranks, self.seg, self.bws)
-        for c in self.calls:
-            lq.lora_segmented_forward(c["x"], c["y"], c["ad"], self.seg, c["h_out"], self.fws, self.variant)
-        for c in reversed(self.calls):
-            lq.lora_segmented_backward(c["x"], c["y"], c["dx"], c["ad"], c["dA_ptrs"], c["dB_ptrs"], self.seg, c["h_out"],
-                                       self.bwd_ws)
-
-    def forward_only(self):
-        for c in self.calls:
-            self.lq.lora_segmented_forward(c["x"], c["y"], c["ad"], self.seg, c["h_out"], self.fws, self.variant)
+        """Headline step: the segment builder once (all calls share the batch structure), then every call's forward."""
+        self.build()
+        for f in self.fwd:
+            f()
 
     def backward_only(self):
+        lq = self.lq
         for c in reversed(self.calls):
-            self.lq.lora_segmented_backward(c["x"], c["y"], c["dx"], c["ad"], c["dA_ptrs"], c["dB_ptrs"], self.seg, c["h_out"],
-                                            self.bwd_ws)
+            lq.lora_segmented_backward(c["x"], c["y"], c["dx"], c["ad"], c["dA_ptrs"], c["dB_ptrs"], self.seg, c["h_out"],
+                                       self.ws, self.variant)
+
+    def error_word(self):
+        return int(self.ws[0].item() & 0xffffffff) | int(self.bws[0].item() & 0xffffffff)
 
 
-def measure_layer_stack(variant, steps, warmup):
-    import torch
-    st = LayerStack(variant)
-    w = st.work()
+def timed_steps(torch, step, steps, warmup):
+    """Exactly `steps` steps between two synchronisations (wall clock), after `warmup` untimed ones; an event after
+    every step gives the per-step times as well (their median does not depend on a single slow step)."""
     for i in range(warmup):
-        st.step(i)
+        step(i)
     torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
+    ev[0].record()
     for i in range(steps):
-        st.step(i)
+        step(warmup + i)
+        ev[i + 1].record()
     torch.cuda.synchronize()
-    s_per_step = (time.perf_counter() - t0) / steps
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    ev[0].record(); st.forward_only(); ev[1].record(); st.backward_only(); ev[2].record()
+    wall = (time.perf_counter() - t0) / steps
+    per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    return wall, dict(median_ms=per[len(per) // 2], min_ms=per[0], max_ms=per[-1])
+
+
+def profiled(lq, torch, run):
+    """Per-kernel average durations of `run()` from the dispatch time stamps (lora_profile_*)."""
+    lq.lora_profile_enable(True)
+    run()
     torch.cuda.synchronize()
-    fwd_ms, bwd_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
-    kernels = {}
-    for which, run in (("forward", st.forward_only), ("backward", st.backward_only)):
-        st.lq.lora_profile_enable(True)
-        run()
+    prof = lq.lora_profile_read()
+    lq.lora_profile_enable(False)
+    return {name: dict(avg_us=total / n, launches=n) for name, (total, n) in prof.items() if n}
+
+
+def measure_layer_stack(variant, steps, warmup, with_backward):
+    """Headline: builder + the 224 forward calls.  With `with_backward`, the backward of the fine-tune rows of all
+    calls is measured as well (its own entry)."""
+    import torch
+    st = LayerStack(variant, with_backward)
+    w = st.work()
+    s_per_step, per_step = timed_steps(torch, st.step, steps, warmup)
+    kern = profiled(st.lq, torch, lambda: [st.step(i) for i in range(max(1, min(steps, 3)))])
+    dom = "forward_fused" if "forward_fused" in kern else "expand"
+    n_steps_prof = max(1, min(steps, 3))
+    fwd_us = sum(k["avg_us"] * k["launches"] for name, k in kern.items() if name != "build") / n_steps_prof   # per step
+    per_launch = w["fwd_bytes"] / w["calls"]
+    if dom == "forward_fused":
+        dom_bytes = per_launch
+    else:   # two launches: the expand kernel carries y, B and the saved h
+        n_ft = int((st.batch.token_kind == 0).sum())
+        dom_bytes = sum(st.T * c["d_out"] * 4 + st.n_adapters * st.rank * c["d_out"] * 2 + n_ft * st.rank * 4 for c in st.calls) / w["calls"]
+    dom_gbps = dom_bytes / (kern[dom]["avg_us"] * 1e-6) / 1e9
+    traffic = counter_traffic(LAYER_STACK_NAME, dom)
+    head = dict(
+        workload=LAYER_STACK_NAME, tokens=w["tokens"], calls=w["calls"], ms_per_step=s_per_step * 1e3, per_step=per_step,
+        tokens_per_s=w["tokens"] / s_per_step, forward_us=fwd_us,
+        forward_gbps=w["fwd_bytes"] / (fwd_us * 1e-6) / 1e9, forward_tflops=w["fwd_flops"] / (fwd_us * 1e-6) / 1e12,
+        forward_hbm_frac=w["fwd_bytes"] / (fwd_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+        forward_mfma_frac=w["fwd_flops"] / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        algorithmic_bytes=w["fwd_bytes"], flops=w["fwd_flops"], kernels=kern,
+        roofline=dict(bound="hbm", kernel=dom, achieved=dom_gbps, peak=HBM_PEAK_GBPS, unit="GB/s", frac=dom_gbps / HBM_PEAK_GBPS,
+                      traffic=traffic, traffic_source=traffic_source(LAYER_STACK_NAME) if traffic else None,
+                      algorithmic_bytes=dom_bytes, avg_launch_us=kern[dom]["avg_us"],
+                      note="average over the step's 224 launches of 4 shapes: bytes and duration are both per launch"),
+        error_word=st.error_word())
+    bwd = None
+    if with_backward:
+        st.backward_only()
         torch.cuda.synchronize()
-        kernels[which] = {name: dict(avg_us=total / n, launches=n) for name, (total, n) in st.lq.lora_profile_read().items() if n}
-        st.lq.lora_profile_enable(False)
-    return dict(workload="cfg5_layer_stack (32 layers x 7 projections, forward + backward of the fine-tune rows)",
-                tokens=w["tokens"], calls=len(st.calls), ms_per_step=s_per_step * 1e3, tokens_per_s=w["tokens"] / s_per_step,
-                forward_ms=fwd_ms, backward_ms=bwd_ms,
-                forward_gbps=w["fwd_bytes"] / (fwd_ms * 1e-3) / 1e9, backward_gbps=w["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9,
-                forward_tflops=w["fwd_flops"] / (fwd_ms * 1e-3) / 1e12, backward_tflops=w["bwd_flops"] / (bwd_ms * 1e-3) / 1e12,
-                forward_hbm_frac=w["fwd_bytes"] / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                backward_hbm_frac=w["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                algorithmic_bytes=w["fwd_bytes"] + w["bwd_bytes"], flops=w["fwd_flops"] + w["bwd_flops"], kernels=kernels)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        reps = 3
+        ev[0].record()
+        for _ in range(reps):
+            st.backward_only()
+        ev[1].record()
+        torch.cuda.synchronize()
+        bwd_ms = ev[0].elapsed_time(ev[1]) / reps
+        bk = profiled(st.lq, torch, st.backward_only)
+        bdom = max(bk, key=lambda k: bk[k]["avg_us"] * bk[k]["launches"])
+        kernel_us = sum(k["avg_us"] * k["launches"] for k in bk.values())
+        # the backward's launches form one pipeline over the same bytes: its roofline entry is the whole call
+        # (algorithmic bytes of a call / summed duration of its launches)
+        per_call_us = kernel_us / w["calls"]
+        gbps = w["bwd_bytes"] / w["calls"] / (per_call_us * 1e-6) / 1e9
+        bwd = dict(workload=LAYER_STACK_NAME + "_backward (fine-tune rows of all 224 calls)", tokens=int((st.batch.token_kind == 0).sum()),
+                   calls=w["calls"], ms_per_step=bwd_ms, backward_gbps=w["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9,
+                   backward_tflops=w["bwd_flops"] / (bwd_ms * 1e-3) / 1e12,
+                   backward_hbm_frac=w["bwd_bytes"] / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                   algorithmic_bytes=w["bwd_bytes"], flops=w["bwd_flops"], kernels=bk,
+                   roofline=dict(bound="hbm", kernel="all launches of a call (largest: %s)" % bdom, achieved=gbps, peak=HBM_PEAK_GBPS,
+                                 unit="GB/s", frac=gbps / HBM_PEAK_GBPS, traffic=None, algorithmic_bytes=w["bwd_bytes"] / w["calls"],
+                                 avg_launch_us=per_call_us),
+                   error_word=st.error_word())
+    del st
+    return head, bwd
+
+
+def layer_stack_cpu_baseline(budget_s=12.0):
+    """The fp64 oracle, as it stands, on the host cores, on a bounded sample of the headline workload: the seven
+    calls of layer 0 (seeded inputs), repeated for ~budget_s; scaled to the 32 layers of a step."""
+    import oracle
+    from paper_2511_00101_amd import synth
+    oracle.build()
+    problems = [synth.config5(0, pi, with_dy=False) for pi in range(len(synth.LAYER_PROJECTIONS))]
+    n, t0 = 0, time.perf_counter()
+    while True:
+        for p in problems:
+            oracle.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s:
+            break
+    per_layer = el / n
+    T = problems[0].n_tokens
+    return dict(value=T / (per_layer * synth.N_LAYERS), unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"the 7 forward calls of layer 0 ({T} tokens each, metadata + forward), {n} times in {el:.1f} s; "
+                       f"one layer takes {per_layer:.2f} s, scaled by the {synth.N_LAYERS} layers of a step")
 
 
 def cpu_baseline(p, budget_s=12.0):
@@ -317,13 +381,16 @@ def cpu_baseline(p, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--variant", choices=["auto", "split", "fused"], default="auto",
                     help="auto: the single-launch (fused) variant, which is at least as fast as two launches on every "
                          "workload here; split: two launches, with the shrink / expand breakdown")
-    ap.add_argument("--workload", default="cfg2", help="headline workload: cfg1, cfg2, cfg3, cfg4up, cfg4down")
-    ap.add_argument("--others", default="cfg3,cfg4up,cfg4down,cfg5", help="comma list of further workloads ('' = none)")
+    ap.add_argument("--workload", default="cfg5",
+                    help="headline workload: cfg5 (the 32-layer stack's forward, the largest configuration), or one of the "
+                         "single-call ones cfg1, cfg2, cfg3, cfg4up, cfg4down")
+    ap.add_argument("--others", default="cfg2,cfg3,cfg4up,cfg4down,cfg5bwd",
+                    help="comma list of further workloads for the `configs` list ('' = none); cfg5bwd: the layer stack's backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of known size (256 MiB read + 256 MiB written, 8 times) so that "
@@ -350,36 +417,57 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps(dict(copy_bytes_read=src.numel(), copy_bytes_written=dst.numel(), copies=8)))
         return
-    def variant_for(problem):
-        return lq.LQ_VARIANT_SPLIT if args.variant == "split" else lq.LQ_VARIANT_FUSED
+    variant = lq.LQ_VARIANT_SPLIT if args.variant == "split" else lq.LQ_VARIANT_FUSED
     makers = dict(cfg1=synth.config1, cfg2=synth.config2, cfg3=synth.config3,
                   cfg4up=lambda: synth.config4("up"), cfg4down=lambda: synth.config4("down"))
+    # single-call workloads take microseconds per step: they are timed over more steps than a layer-stack step needs
+    small_steps = dict(cfg1=400, cfg2=400, cfg3=200, cfg4up=80, cfg4down=80)
+    other_names = [n for n in args.others.split(",") if n and n != args.workload]
 
-    p = makers[args.workload]()
-    variant = variant_for(p)
-    head = measure(p, variant, args.steps, args.warmup)
     others = []
-    for name in [n for n in args.others.split(",") if n and n != args.workload]:
-        if name == "cfg5":
-            others.append(measure_layer_stack(lq.LQ_VARIANT_SPLIT if args.variant == "split" else lq.LQ_VARIANT_FUSED, 3, 1))
+    if args.workload == "cfg5":
+        head, bwd = measure_layer_stack(variant, args.steps, args.warmup, with_backward="cfg5bwd" in other_names)
+        cpu = None if args.no_cpu_baseline else layer_stack_cpu_baseline()
+        workload = (f"{head['workload']} forward: 32 layers x 7 projections = {head['calls']} calls (q,o 4096->4096; k,v 4096->1024; "
+                    f"gate,up 4096->14336; down 14336->4096), {head['tokens']} tokens (4096 fine-tune + 1024 prefill + 512 decode), "
+                    f"16 adapters rank 32")
+        step = f"segment builder + {head['calls']} forward calls (the calls share the batch structure, so the tables are built once)"
+        extra = dict(calls=head["calls"], inputs="drawn on the GPU by torch's generator, every call with its own x, y and weights; "
+                                                 "timed, not checked (the parity tests check sampled calls with the seeded generators)")
+        if bwd:
+            others.append(bwd)
+    else:
+        p = makers[args.workload]()
+        head = measure(p, variant, max(args.steps, small_steps[args.workload]), max(args.warmup, 10))
+        cpu = None if args.no_cpu_baseline else cpu_baseline(p)
+        workload = f"{head['workload']}: {head['tokens']} tokens, {head['d_in']}->{head['d_out']}, {p.n_adapters} adapters rank {int(p.ranks.max())}"
+        step = "segment builder + forward"
+        extra = dict(replicas=head["replicas"], timed_steps=head["steps"])
+        del p
+    for name in other_names:
+        if name in ("cfg5bwd", "cfg5"):
+            if name == "cfg5" or args.workload != "cfg5":
+                h5, b5 = measure_layer_stack(variant, 3, 1, with_backward=name == "cfg5bwd")
+                others.append(b5 if name == "cfg5bwd" else h5)
             continue
         q = makers[name]()
-        others.append(measure(q, variant_for(q), max(20, args.steps // 4), max(5, args.warmup // 2)))
+        others.append(measure(q, variant, small_steps[name], 10))
         del q
-    cpu = None if args.no_cpu_baseline else cpu_baseline(p)
 
     line = dict(
         metric=METRIC, value=head["tokens_per_s"], unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
         ms_per_step=head["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
         data="synthetic",
-        config=dict(workload=f"{head['workload']}: {head['tokens']} tokens, {head['d_in']}->{head['d_out']}, "
-                             f"{p.n_adapters} adapters rank {int(p.ranks.max())}",
-                    variant="fused" if variant == lq.LQ_VARIANT_FUSED else "split",
-                    replicas=head["replicas"], step="segment builder + forward"),
+        config=dict(workload=workload, variant="fused" if variant == lq.LQ_VARIANT_FUSED else "split", step=step, **extra),
         roofline=head["roofline"], cpu_baseline=cpu,
         forward=dict(us=head["forward_us"], gbps=head["forward_gbps"], tflops=head["forward_tflops"],
-                     hbm_frac=head["forward_hbm_frac"], mfma_frac=head["forward_mfma_frac"], kernels=head["kernels"]),
+                     hbm_frac=head["forward_hbm_frac"], mfma_frac=head["forward_mfma_frac"], kernels=head["kernels"],
+                     per_step=head["per_step"], error_word=head["error_word"]),
         configs=others)
+    bad = [head["error_word"]] + [o.get("error_word", 0) for o in others]
+    if any(bad):
+        print(f"bench.py: a workspace error word is non-zero after the timed loops: {bad}", file=sys.stderr)
+        sys.exit(3)
     print(json.dumps(line))
 
 
