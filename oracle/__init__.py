@@ -40,10 +40,10 @@ def _load():
         L.lq_oracle_build_segments.restype = i32
         L.lq_oracle_build_segments.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
         L.lq_oracle_forward.restype = None
-        L.lq_oracle_forward.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.lq_oracle_forward.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.lq_oracle_backward.restype = None
         L.lq_oracle_backward.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, vp, i32,
-                                         vp, vp, vp, vp, vp, vp, vp]
+                                         vp, vp, vp, vp, vp, vp, vp, vp]
         L.lq_oracle_num_threads.restype = i32
         _lib = L
     return _lib
@@ -116,7 +116,10 @@ class ForwardResult:
     segments: Segments
 
 
-def forward(x, y0, A: List[np.ndarray], B: List[np.ndarray], ranks, scales, token_adapter, token_kind) -> ForwardResult:
+def forward(x, y0, A: List[np.ndarray], B: List[np.ndarray], ranks, scales, token_adapter, token_kind,
+            token_scales=None) -> ForwardResult:
+    """token_scales: optional float32[T]; when given it replaces scales[adapter] for every token (the dynamic,
+    per-request scale of Section 3.3)."""
     x = np.ascontiguousarray(x, dtype=np.uint16)
     y0 = np.ascontiguousarray(y0, dtype=np.uint16)
     A = [np.ascontiguousarray(a, dtype=np.uint16) for a in A]
@@ -134,8 +137,10 @@ def forward(x, y0, A: List[np.ndarray], B: List[np.ndarray], ranks, scales, toke
     y = np.zeros((T, d_out), np.float64)
     h = np.zeros(max(seg.h_elems, 1), np.float64)
     At, Bt = _ptr_table(A), _ptr_table(B)
+    ts = None if token_scales is None else np.ascontiguousarray(token_scales, dtype=np.float32)
+    assert ts is None or ts.shape == (T,)
     _load().lq_oracle_forward(_p(x), d_in, _p(y0), d_out, T, d_in, d_out, At, Bt, _p(rk), _p(sc), rk.shape[0],
-                              _p(ta), _p(tk), _p(hoff), _p(y), _p(h))
+                              _p(ta), _p(tk), _p(hoff), _p(ts), _p(y), _p(h))
     return ForwardResult(y, h[:seg.h_elems], seg)
 
 
@@ -147,7 +152,7 @@ class BackwardResult:
     g: np.ndarray            # float64[h_elems]  dy B^T of fine-tune rows (unscaled), metadata layout
 
 
-def backward(x, dy, dx0, A, B, ranks, scales, token_adapter, token_kind) -> BackwardResult:
+def backward(x, dy, dx0, A, B, ranks, scales, token_adapter, token_kind, token_scales=None) -> BackwardResult:
     x = np.ascontiguousarray(x, dtype=np.uint16)
     dy = np.ascontiguousarray(dy, dtype=np.uint16)
     dx0 = None if dx0 is None else np.ascontiguousarray(dx0, dtype=np.uint16)
@@ -165,7 +170,9 @@ def backward(x, dy, dx0, A, B, ranks, scales, token_adapter, token_kind) -> Back
     dB = [np.zeros((int(r), d_out), np.float64) for r in rk]
     dx = np.zeros((T, d_in), np.float64)
     g = np.zeros(max(seg.h_elems, 1), np.float64)
+    ts = None if token_scales is None else np.ascontiguousarray(token_scales, dtype=np.float32)
+    assert ts is None or ts.shape == (T,)
     _load().lq_oracle_backward(_p(x), d_in, _p(dy), d_out, _p(dx0), d_in, T, d_in, d_out, _ptr_table(A), _ptr_table(B),
-                               _p(rk), _p(sc), rk.shape[0], _p(ta), _p(tk), _p(hoff),
+                               _p(rk), _p(sc), rk.shape[0], _p(ta), _p(tk), _p(hoff), _p(ts),
                                _ptr_table(dA), _ptr_table(dB), _p(dx), _p(g))
     return BackwardResult(dA, dB, dx, g[:seg.h_elems])

@@ -14,11 +14,17 @@
  *       y[t,n] = y0[t,n] + s_a * sum_j h[j] * B_a[j,n]        n < d_out    (B_a is [r_a, d_out])
  *   fine-tuning tokens additionally keep the unscaled h (what autograd would keep for the
  *   backward pass, Section 3.3); tokens without a valid adapter keep y0.
+ *   Scale (Section 3.3 names two modes): the static per-adapter s_a above, or a dynamic scale
+ *   "applied on a per-request basis during the forward pass".  The reading taken: an optional
+ *   per-token array token_scale (all tokens of a request carry the request's value) that, when
+ *   given, REPLACES s_a for every token:  y[t,n] = y0[t,n] + token_scale[t] * sum_j h[j] B_a[j,n].
  *
  * Pins (tests/test_oracle_pins.py): B = 0, single adapter vs. a dense fp64 matmul, rank-1
  * outer product, token-permutation invariance, exact rational brute force on tiny shapes,
  * linearity in the scale, central differences for the gradient, a hand-written expected
- * segment table and a library stable sort for the metadata.  No function here is unpinned.
+ * segment table and a library stable sort for the metadata; the per-token scale by the dense
+ * form with a diagonal matrix, by row-wise linearity, by its agreement with the per-adapter
+ * scale when the values coincide, and by exact differences.  No function here is unpinned.
  *
  * Inputs are bfloat16 bit patterns (uint16) decoded here, independently of any other code.
  */
@@ -114,7 +120,8 @@ void lq_oracle_forward(const uint16_t* x, int64_t ldx, const uint16_t* y0, int64
                        const uint16_t* const* A, const uint16_t* const* B,
                        const int32_t* ranks, const float* scales, int32_t n_adapters,
                        const int32_t* token_adapter, const uint8_t* token_kind,
-                       const int64_t* token_h_offset, double* y_ref, double* h_ref)
+                       const int64_t* token_h_offset, const float* token_scale /* NULL: per-adapter scales */,
+                       double* y_ref, double* h_ref)
 {
 #pragma omp parallel
     {
@@ -132,7 +139,7 @@ void lq_oracle_forward(const uint16_t* x, int64_t ldx, const uint16_t* y0, int64
                 continue;
             }
             int32_t r = ranks[a];
-            double s = (double)scales[a];
+            double s = token_scale ? (double)token_scale[t] : (double)scales[a];
             for (int32_t j = 0; j < r; ++j) {
                 const uint16_t* Aj = A[a] + (int64_t)j * d_in;
                 double acc = 0.0;
@@ -159,6 +166,7 @@ void lq_oracle_forward(const uint16_t* x, int64_t ldx, const uint16_t* y0, int64
  *     dB_a[j,n] += s_a * sum_t h[t,j] * dy[t,n]          (h recomputed here in fp64)
  *     dA_a[j,k] += s_a * sum_t g[t,j] * x[t,k]
  *     dx[t,k]   = dx0[t,k] + s_a * sum_j g[t,j] * A_a[j,k]
+ * (with a per-token scale, s_a becomes token_scale[t] and moves inside the sums over t)
  * dA[a] is [r_a, d_in] fp64, dB[a] is [r_a, d_out] fp64, both accumulated into (caller zeroes);
  * dx_ref is [n_tokens, d_in] fp64 and receives dx0 (bf16) plus the update; rows of other
  * kinds receive dx0 unchanged.  g_ref (optional) receives g at the same offsets as h.
@@ -170,7 +178,7 @@ void lq_oracle_backward(const uint16_t* x, int64_t ldx, const uint16_t* dy, int6
                         const uint16_t* const* A, const uint16_t* const* B,
                         const int32_t* ranks, const float* scales, int32_t n_adapters,
                         const int32_t* token_adapter, const uint8_t* token_kind,
-                        const int64_t* token_h_offset,
+                        const int64_t* token_h_offset, const float* token_scale /* NULL: per-adapter scales */,
                         double* const* dA, double* const* dB, double* dx_ref, double* g_ref)
 {
     int32_t max_rank = 1;
@@ -191,7 +199,7 @@ void lq_oracle_backward(const uint16_t* x, int64_t ldx, const uint16_t* dy, int6
         int32_t a = token_adapter[t];
         if (!token_is_live(a, token_kind[t], n_adapters) || token_kind[t] != LQO_FINETUNE) continue;
         int32_t r = ranks[a];
-        double s = (double)scales[a];
+        double s = token_scale ? (double)token_scale[t] : (double)scales[a];
         for (int32_t j = 0; j < r; ++j) {
             double acc_h = 0.0, acc_g = 0.0;
             for (int32_t k = 0; k < d_in; ++k) acc_h += bf16_decode(xt[k]) * bf16_decode(A[a][(int64_t)j * d_in + k]);
@@ -211,7 +219,6 @@ void lq_oracle_backward(const uint16_t* x, int64_t ldx, const uint16_t* dy, int6
     /* weight gradients: one row (a, j) at a time, tokens summed in their natural order */
     for (int32_t a = 0; a < n_adapters; ++a) {
         int32_t r = ranks[a];
-        double s = (double)scales[a];
 #pragma omp parallel for schedule(static)
         for (int32_t j = 0; j < r; ++j) {
             double* dBj = dB[a] + (int64_t)j * d_out;
@@ -220,6 +227,7 @@ void lq_oracle_backward(const uint16_t* x, int64_t ldx, const uint16_t* dy, int6
                 if (token_adapter[t] != a || token_kind[t] != LQO_FINETUNE) continue;
                 const uint16_t* xt = x + (int64_t)t * ldx;
                 const uint16_t* dyt = dy + (int64_t)t * lddy;
+                double s = token_scale ? (double)token_scale[t] : (double)scales[a];
                 double hj = h_all[(size_t)t * max_rank + j];
                 double gj = g_all[(size_t)t * max_rank + j];
                 for (int32_t n = 0; n < d_out; ++n) dBj[n] += s * hj * bf16_decode(dyt[n]);

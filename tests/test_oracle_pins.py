@@ -256,17 +256,59 @@ def test_config1_structure(oracle_mod):
 
 
 # ---------------------------------------------------------------------------------------------
+# dynamic per-request scale (Section 3.3): a per-token array that replaces the per-adapter scale
+# ---------------------------------------------------------------------------------------------
+def test_token_scale_single_adapter_is_dense_matmul_with_a_diagonal(oracle_mod):
+    rng = np.random.default_rng(15)
+    T, d_in, d_out, r = 45, 80, 56, 8
+    x, y0 = synth.normal_bf16(rng, (T, d_in), 1.0), synth.normal_bf16(rng, (T, d_out), 1.0)
+    A, B = synth.normal_bf16(rng, (r, d_in), 0.02), synth.normal_bf16(rng, (r, d_out), 0.02)
+    ts = rng.uniform(-2.0, 3.0, size=T).astype(np.float32)
+    res = oracle_mod.forward(x, y0, [A], [B], [r], [123.0], np.zeros(T, np.int32), np.zeros(T, np.uint8), token_scales=ts)
+    expect = f64(y0) + np.diag(ts.astype(np.float64)) @ (f64(x) @ f64(A).T) @ f64(B)
+    np.testing.assert_allclose(res.y, expect, rtol=1e-12, atol=1e-12)
+    # a transposed or misplaced diagonal (scale indexed by column) gives something else
+    wrong = f64(y0) + (f64(x) @ f64(A).T) @ f64(B) * np.resize(ts, d_out).astype(np.float64)[None, :]
+    assert np.abs(res.y - wrong).max() > 1e-3
+    # the saved h stays unscaled
+    np.testing.assert_allclose(res.h.reshape(T, r), f64(x) @ f64(A).T, rtol=1e-12, atol=1e-12)
+
+
+def test_token_scale_agrees_with_adapter_scale_and_is_row_wise_linear(oracle_mod):
+    p = synth.small_mixed(8, T=40, d_in=32, d_out=24, ranks=[4, 8, 2], drop_frac=0.15)
+    base = run_forward(oracle_mod, p)
+    ta = p.batch.token_adapter
+    same = np.where(ta >= 0, p.scales[np.maximum(ta, 0)], 77.0).astype(np.float32)
+    res = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, ta, p.batch.token_kind, token_scales=same)
+    assert np.array_equal(res.y, base.y) and np.array_equal(res.h, base.h)
+    # doubling one token's scale doubles that row's update and leaves every other row alone (powers of two: exact)
+    t = int(np.flatnonzero(ta >= 0)[3])
+    bumped = same.copy()
+    bumped[t] *= 2.0
+    res2 = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, ta, p.batch.token_kind, token_scales=bumped)
+    y0 = f64(p.y0)
+    others = np.arange(p.n_tokens) != t
+    assert np.array_equal(res2.y[others], base.y[others])
+    np.testing.assert_allclose(res2.y[t] - y0[t], 2.0 * (base.y[t] - y0[t]), rtol=1e-12, atol=1e-15)
+    # rows without an adapter ignore their scale
+    dead = ta < 0
+    assert dead.any() and np.array_equal(res.y[dead], y0[dead])
+
+
+# ---------------------------------------------------------------------------------------------
 # backward
 # ---------------------------------------------------------------------------------------------
-def loss_of(oracle_mod, x, y0, A, B, ranks, scales, ta, tk, dy):
-    res = oracle_mod.forward(x, y0, A, B, ranks, scales, ta, tk)
+def loss_of(oracle_mod, x, y0, A, B, ranks, scales, ta, tk, dy, token_scales=None):
+    res = oracle_mod.forward(x, y0, A, B, ranks, scales, ta, tk, token_scales=token_scales)
     ft = (tk == 0) & (ta >= 0)
     return float(np.sum(f64(dy)[ft] * res.y[ft]))
 
 
-def test_backward_against_exact_differences(oracle_mod):
+@pytest.mark.parametrize("per_token", [False, True])
+def test_backward_against_exact_differences(oracle_mod, per_token):
     """L = sum dy*y over fine-tune rows is linear in each single input element, so a one-sided difference
-    with a bf16-representable step is exact: L(e + delta) - L(e) = delta * dL/de."""
+    with a bf16-representable step is exact: L(e + delta) - L(e) = delta * dL/de.  With per_token the scale is
+    the dynamic per-token one (values k/8, exact)."""
     rng = np.random.default_rng(61)
     T, d_in, d_out = 10, 7, 6
     ranks = np.array([2, 3], np.int32)
@@ -276,8 +318,9 @@ def test_backward_against_exact_differences(oracle_mod):
     B = [grid_bits(rng, (int(r), d_out), -64, 64) for r in ranks]
     ta = np.array([0, 1, 1, 0, -1, 1, 0, 0, 1, 1], np.int32)
     tk = np.array([0, 0, 1, 0, 0, 2, 0, 1, 0, 0], np.uint8)
-    bw = oracle_mod.backward(x, dy, None, A, B, ranks, scales, ta, tk)
-    L0 = loss_of(oracle_mod, x, y0, A, B, ranks, scales, ta, tk, dy)
+    ts = (rng.integers(-16, 17, size=T) / 8.0).astype(np.float32) if per_token else None
+    bw = oracle_mod.backward(x, dy, None, A, B, ranks, scales, ta, tk, token_scales=ts)
+    L0 = loss_of(oracle_mod, x, y0, A, B, ranks, scales, ta, tk, dy, ts)
     delta = 1.0 / 64.0
 
     def bump(bits, idx):
@@ -292,16 +335,16 @@ def test_backward_against_exact_differences(oracle_mod):
             for k in range(d_in):
                 A2 = list(A)
                 A2[a] = bump(A[a], (j, k))
-                d = loss_of(oracle_mod, x, y0, A2, B, ranks, scales, ta, tk, dy) - L0
+                d = loss_of(oracle_mod, x, y0, A2, B, ranks, scales, ta, tk, dy, ts) - L0
                 assert d == pytest.approx(delta * bw.dA[a][j, k], rel=1e-9, abs=1e-9)
             for n in range(d_out):
                 B2 = list(B)
                 B2[a] = bump(B[a], (j, n))
-                d = loss_of(oracle_mod, x, y0, A, B2, ranks, scales, ta, tk, dy) - L0
+                d = loss_of(oracle_mod, x, y0, A, B2, ranks, scales, ta, tk, dy, ts) - L0
                 assert d == pytest.approx(delta * bw.dB[a][j, n], rel=1e-9, abs=1e-9)
     for t in range(T):
         for k in range(d_in):
-            d = loss_of(oracle_mod, bump(x, (t, k)), y0, A, B, ranks, scales, ta, tk, dy) - L0
+            d = loss_of(oracle_mod, bump(x, (t, k)), y0, A, B, ranks, scales, ta, tk, dy, ts) - L0
             assert d == pytest.approx(delta * bw.dx[t, k], rel=1e-9, abs=1e-9)
     assert np.abs(bw.dA[0]).max() > 0 and np.abs(bw.dB[1]).max() > 0 and np.abs(bw.dx).max() > 0
     # rows that are not fine-tune rows get no gradient
@@ -321,3 +364,18 @@ def test_backward_single_adapter_dense_form(oracle_mod):
     np.testing.assert_allclose(bw.dA[0], s * G.T @ X, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(bw.dx, f64(dx0) + s * G @ Af, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(bw.g, G.reshape(-1), rtol=1e-11, atol=1e-12)
+
+
+def test_backward_token_scale_single_adapter_dense_form(oracle_mod):
+    rng = np.random.default_rng(73)
+    T, d_in, d_out, r = 30, 40, 28, 4
+    x, dy, dx0 = (synth.normal_bf16(rng, (T, d_in), 1.0), synth.normal_bf16(rng, (T, d_out), 1.0),
+                  synth.normal_bf16(rng, (T, d_in), 1.0))
+    A, B = synth.normal_bf16(rng, (r, d_in), 0.02), synth.normal_bf16(rng, (r, d_out), 0.02)
+    ts = rng.uniform(-1.0, 2.0, size=T).astype(np.float32)
+    bw = oracle_mod.backward(x, dy, dx0, [A], [B], [r], [9.0], np.zeros(T, np.int32), np.zeros(T, np.uint8), token_scales=ts)
+    X, DY, Af, Bf, S = f64(x), f64(dy), f64(A), f64(B), np.diag(ts.astype(np.float64))
+    G = DY @ Bf.T
+    np.testing.assert_allclose(bw.dB[0], (X @ Af.T).T @ S @ DY, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(bw.dA[0], G.T @ S @ X, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(bw.dx, f64(dx0) + S @ G @ Af, rtol=1e-11, atol=1e-12)
