@@ -117,6 +117,11 @@ lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token
  *   A_ptrs   [n_adapters] device array of device pointers to bf16 [r_a, d_in]
  *   B_ptrs   [n_adapters] device array of device pointers to bf16 [r_a, d_out]
  *   ranks    int32[n_adapters], scales float[n_adapters] (applied in fp32 to h * B before the add)
+ *   token_scales  float[n_tokens] or NULL.  Section 3.3 names two scale modes: static (folded into the
+ *            weights at load, or scales[a] here) and dynamic, "applied on a per-request basis during the
+ *            forward pass".  When given, token_scales[t] REPLACES scales[adapter] for token row t (every
+ *            token of a request carries the request's value; requests that share an adapter may differ);
+ *            the saved h stays unscaled.  NULL: the per-adapter scales.
  *   max_rank host scalar >= every rank in use (sizes the h scratch); <= LQ_MAX_RANK
  *   perm     int32, row of x / y for each position of the segment order; NULL = identity
  *   seg_*    as produced by lora_build_segments (or by the caller); n_segments is a device scalar,
@@ -139,7 +144,8 @@ size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t 
 lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
                                  int32_t d_in, int32_t d_out,
                                  const void* const* A_ptrs, const void* const* B_ptrs,
-                                 const int32_t* ranks, const float* scales, int32_t n_adapters, int32_t max_rank,
+                                 const int32_t* ranks, const float* scales, const float* token_scales,
+                                 int32_t n_adapters, int32_t max_rank,
                                  const int32_t* perm, int32_t n_tokens,
                                  const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
                                  const int32_t* n_segments, int32_t max_segments,
@@ -167,7 +173,8 @@ lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ld
 lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int64_t ldy,
                                         int32_t d_in, int32_t d_out,
                                         const void* const* A_ptrs, const void* const* B_ptrs,
-                                        const int32_t* ranks, const float* scales, int32_t n_adapters, int32_t max_rank,
+                                        const int32_t* ranks, const float* scales, const float* token_scales,
+                                        int32_t n_adapters, int32_t max_rank,
                                         const int32_t* perm, int32_t n_tokens,
                                         const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
                                         const int32_t* n_segments, int32_t max_segments,
@@ -180,6 +187,7 @@ lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int
  * work (Section 4.2, Appendix A).  Exact gradient of the forward as defined here, with
  * g = dy * B_a^T:
  *     dB_a += s_a * h^T dy        dA_a += s_a * g^T x        dx[t, :] += s_a * g[t, :] * A_a
+ * (with token_scales, as in the forward, s_a becomes the row's own scale inside the sums over rows)
  *
  *   dy       bf16 [n_tokens, d_out] (rows of fine-tune tokens are read)
  *   dx       bf16 [n_tokens, d_in], read-modify-write on fine-tune rows only (one rounding per call);
@@ -202,7 +210,8 @@ lq_status lora_segmented_backward(const void* x, int64_t ldx, const void* dy, in
                                   int32_t d_in, int32_t d_out,
                                   const void* const* A_ptrs, const void* const* B_ptrs,
                                   float* const* dA_ptrs, float* const* dB_ptrs,
-                                  const int32_t* ranks, const float* scales, int32_t n_adapters, int32_t max_rank,
+                                  const int32_t* ranks, const float* scales, const float* token_scales,
+                                  int32_t n_adapters, int32_t max_rank,
                                   const int32_t* perm, int32_t n_tokens,
                                   const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
                                   const int32_t* n_segments, int32_t max_segments,

@@ -31,13 +31,13 @@ _SIGNATURES = {
     "lora_build_workspace_bytes": (_sz, [_i32, _i32]),
     "lora_build_segments": (ctypes.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
     "lora_forward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
-    "lora_segmented_forward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _i32,
+    "lora_segmented_forward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                               _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
-    "lora_segmented_forward_static": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _i32,
+    "lora_segmented_forward_static": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                                      _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp]),
     "lora_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_segmented_backward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp,
-                                               _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
+                                               _vp, _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
                                                _vp, _vp, _i32, _vp, _sz, _vp]),
     "lora_profile_enable": (ctypes.c_int, [_i32]),
     "lora_profile_read": (ctypes.c_int, [_vp, _vp, _i32]),
@@ -204,14 +204,21 @@ class AdapterTable:
         return len(self.A)
 
 
-def _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream):
+def _token_scales_ptr(token_scales, n_tokens):
+    if token_scales is None:
+        return None
+    assert token_scales.dtype == torch.float32 and token_scales.is_contiguous() and token_scales.numel() == n_tokens
+    return token_scales.data_ptr()
+
+
+def _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream, token_scales=None):
     assert x.dtype == torch.bfloat16 and y.dtype == torch.bfloat16
     assert x.stride(1) == 1 and y.stride(1) == 1
     n_tokens, d_in = int(x.shape[0]), int(x.shape[1])
     d_out = int(y.shape[1])
     return (_ptr(x), x.stride(0), _ptr(y), y.stride(0), d_in, d_out,
             _ptr(adapters.A_ptrs), _ptr(adapters.B_ptrs), _ptr(adapters.ranks), _ptr(adapters.scales),
-            adapters.n_adapters, adapters.max_rank,
+            _token_scales_ptr(token_scales, n_tokens), adapters.n_adapters, adapters.max_rank,
             _ptr(seg.perm) if use_perm else None, n_tokens,
             _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
             _ptr(h_out), _ptr(seg.h_offsets) if h_out is not None else None,
@@ -220,39 +227,45 @@ def _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stre
 
 def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,
                            h_out: Optional[torch.Tensor], workspace: torch.Tensor,
-                           variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None) -> None:
-    st = lib().lora_segmented_forward(*_forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream))
+                           variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None,
+                           token_scales: Optional[torch.Tensor] = None) -> None:
+    st = lib().lora_segmented_forward(*_forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream,
+                                                     token_scales))
     if st != LQ_OK:
         raise LqError(st, "lora_segmented_forward")
 
 
 def lora_segmented_forward_static(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,
                                   h_out: Optional[torch.Tensor], error_word: Optional[torch.Tensor] = None,
-                                  variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None) -> None:
+                                  variant: int = LQ_VARIANT_SPLIT, use_perm: bool = True, stream=None,
+                                  token_scales: Optional[torch.Tensor] = None) -> None:
     """The forward with the library's own device array as workspace (allocates nothing)."""
-    args = _forward_args(x, y, adapters, seg, h_out, None, variant, use_perm, stream)
+    args = _forward_args(x, y, adapters, seg, h_out, None, variant, use_perm, stream, token_scales)
     assert error_word is None or error_word.dtype == torch.int32
-    st = lib().lora_segmented_forward_static(*args[:22], _ptr(error_word), args[24])   # all but the workspace pair
+    st = lib().lora_segmented_forward_static(*args[:23], _ptr(error_word), args[25])   # all but the workspace pair
     if st != LQ_OK:
         raise LqError(st, "lora_segmented_forward_static")
 
 
-def prepare_forward(x, y, adapters, seg, h_out, workspace, variant=LQ_VARIANT_SPLIT, use_perm=True, stream=None) -> PreparedCall:
+def prepare_forward(x, y, adapters, seg, h_out, workspace, variant=LQ_VARIANT_SPLIT, use_perm=True, stream=None,
+                    token_scales=None) -> PreparedCall:
     return PreparedCall(lib().lora_segmented_forward,
-                        _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream), "lora_segmented_forward")
+                        _forward_args(x, y, adapters, seg, h_out, workspace, variant, use_perm, stream, token_scales),
+                        "lora_segmented_forward")
 
 
 def lora_segmented_backward(x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, adapters: AdapterTable,
                             dA_ptrs: Optional[torch.Tensor], dB_ptrs: Optional[torch.Tensor], seg: SegmentTables,
                             h_saved: torch.Tensor, workspace: torch.Tensor, variant: int = LQ_VARIANT_FUSED,
-                            use_perm: bool = True, stream=None) -> None:
+                            use_perm: bool = True, stream=None, token_scales: Optional[torch.Tensor] = None) -> None:
     assert x.dtype == torch.bfloat16 and dy.dtype == torch.bfloat16 and dx.dtype == torch.bfloat16
     n_tokens, d_in = int(x.shape[0]), int(x.shape[1])
     d_out = int(dy.shape[1])
     st = lib().lora_segmented_backward(
         _ptr(x), x.stride(0), _ptr(dy), dy.stride(0), _ptr(dx), dx.stride(0), d_in, d_out,
         _ptr(adapters.A_ptrs), _ptr(adapters.B_ptrs), _ptr(dA_ptrs), _ptr(dB_ptrs),
-        _ptr(adapters.ranks), _ptr(adapters.scales), adapters.n_adapters, adapters.max_rank,
+        _ptr(adapters.ranks), _ptr(adapters.scales), _token_scales_ptr(token_scales, n_tokens),
+        adapters.n_adapters, adapters.max_rank,
         _ptr(seg.perm) if use_perm else None, n_tokens,
         _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
         _ptr(h_saved), _ptr(seg.h_offsets), variant, _ptr(workspace), workspace.numel() * workspace.element_size(),

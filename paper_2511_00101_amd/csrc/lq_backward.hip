@@ -41,6 +41,7 @@ struct BwdParams {
     float* const* dA_ptrs; float* const* dB_ptrs;
     const void* const* A_ptrs; const void* const* B_ptrs;  // only for the table helpers
     const int32_t* ranks; const float* scales; int n_adapters; int max_rank;
+    const float* token_scales;  // per token row; when given it replaces scales[adapter] and moves inside the sums over tokens
     const int32_t* perm; int n_tokens;
     const int32_t* seg_starts; const int32_t* seg_adapter; const uint8_t* seg_kind;
     const int32_t* n_segments; int max_segments;
@@ -98,10 +99,10 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
     const float* hsrc = (for_b ? p.h_saved : p.g) + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * rank;
     constexpr int DEPTH = NT == 1 ? 4 : NT == 2 ? 3 : NT == 4 ? 2 : 1;  // steps in flight (as many as the registers allow)
     u32x4 gy[DEPTH][YQ];
-    float gh[DEPTH][NT];
+    float gh[DEPTH][NT + 1];  // [NT]: the row's own scale (1 when the scale is the adapter's, applied by the reduction)
     // all loads are unconditional (clamped addresses), so the number in flight is static; what lies
     // outside the unit is zeroed when it is stored to LDS
-    auto stage_load = [&](int step, u32x4 (&y)[YQ], float (&h)[NT]) {
+    auto stage_load = [&](int step, u32x4 (&y)[YQ], float (&h)[NT + 1]) {
         const int i = step * kStepRows + y_row;
         const int row = lds_row[min(i, kWgRows - 1)];
         const u16* yrow = Y + (long long)(row >= 0 ? row : safe_row) * ldy;
@@ -110,8 +111,9 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
         const float* hrow = hsrc + (long long)min(i, u.len - 1) * rank;
 #pragma unroll
         for (int q = 0; q < NT; ++q) h[q] = hrow[min(y_piece + 16 * q, rank - 1)];
+        h[NT] = p.token_scales ? p.token_scales[max(row, 0)] : 1.f;
     };
-    auto stage_store = [&](int step, int buf, const u32x4 (&y)[YQ], const float (&h)[NT]) {
+    auto stage_store = [&](int step, int buf, const u32x4 (&y)[YQ], const float (&h)[NT + 1]) {
         u16* ly = reinterpret_cast<u16*>(lds + buf * C::BUF_BYTES);
         u16* lh = reinterpret_cast<u16*>(lds + buf * C::BUF_BYTES + C::Y_BYTES);
         const int i = step * kStepRows + y_row;
@@ -124,7 +126,7 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
         // h / g as bf16 high and low parts (together ~16 mantissa bits), split here once instead of in every wave
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
-            const float v = (i < u.len && y_piece + 16 * q < rank) ? h[q] : 0.f;
+            const float v = (i < u.len && y_piece + 16 * q < rank) ? h[q] * h[NT] : 0.f;
             const unsigned int hi = pack_bf16x2(v, 0.f) & 0xffffu;
             const unsigned int lo = pack_bf16x2(v - bf16_lo(hi), 0.f) & 0xffffu;
             lh[y_row * C::HPITCH + y_piece + 16 * q] = (u16)hi;
@@ -242,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
         if (u.ad < 0 || u.ad >= p.n_adapters) continue;
         const int rank = p.ranks[u.ad];
         if (rank < 1 || rank > p.max_rank) continue;
-        const float scale = p.scales[u.ad];
+        const float scale = p.token_scales ? 1.f : p.scales[u.ad];  // (per-token scales were applied row by row)
         const int n_chunks = (u.seg_len + kWgRows - 1) / kWgRows;
         const int j0 = (sub / col_blocks) * kRedRanks;
         const int col = (sub % col_blocks) * kThreads + (int)threadIdx.x;
@@ -328,8 +330,8 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
                                              int64_t lddx, int32_t d_in, int32_t d_out,
                                              const void* const* A_ptrs, const void* const* B_ptrs,
                                              float* const* dA_ptrs, float* const* dB_ptrs,
-                                             const int32_t* ranks, const float* scales, int32_t n_adapters,
-                                             int32_t max_rank, const int32_t* perm, int32_t n_tokens,
+                                             const int32_t* ranks, const float* scales, const float* token_scales,
+                                             int32_t n_adapters, int32_t max_rank, const int32_t* perm, int32_t n_tokens,
                                              const int32_t* seg_starts, const int32_t* seg_adapter,
                                              const uint8_t* seg_kind, const int32_t* n_segments, int32_t max_segments,
                                              const float* h_saved, const int64_t* h_offsets,
@@ -366,6 +368,7 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     s1.d_in = d_out; s1.d_out = d_in;
     s1.A_ptrs = B_ptrs; s1.B_ptrs = A_ptrs; s1.ranks = ranks; s1.scales = scales;
     s1.n_adapters = n_adapters; s1.max_rank = max_rank;
+    s1.token_scales = token_scales;
     s1.perm = perm; s1.n_tokens = n_tokens;
     s1.seg_starts = seg_starts; s1.seg_adapter = seg_adapter; s1.seg_kind = seg_kind;
     s1.n_segments = n_segments; s1.max_segments = max_segments;
@@ -398,6 +401,7 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
         b.d_in = d_in; b.d_out = d_out;
         b.dA_ptrs = dA_ptrs; b.dB_ptrs = dB_ptrs; b.A_ptrs = A_ptrs; b.B_ptrs = B_ptrs;
         b.ranks = ranks; b.scales = scales; b.n_adapters = n_adapters; b.max_rank = max_rank;
+        b.token_scales = token_scales;
         b.perm = perm; b.n_tokens = n_tokens;
         b.seg_starts = seg_starts; b.seg_adapter = seg_adapter; b.seg_kind = seg_kind;
         b.n_segments = n_segments; b.max_segments = max_segments;

@@ -552,11 +552,17 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         const int n_items = (u.len + 15) / 16 * 16 * (C::ROWS / 8);
         f32x4 h0[ITEMS], h1[ITEMS];
         const float* hp[ITEMS];
+        float sc[ITEMS];  // the row's scale: the adapter's, or the token's own (dynamic scaling, Section 3.3)
 #pragma unroll
         for (int it = 0; it < ITEMS; ++it) {
             if (it * kThreads >= n_items) break;  // workgroup uniform
             const int id = (int)threadIdx.x + it * kThreads;
             const int i = id / (C::ROWS / 8), jg = id % (C::ROWS / 8);
+            sc[it] = s.scale;
+            if (p.token_scales) {  // kernel uniform
+                const int r = row_of(p, u.pos + min(i, u.len - 1));
+                sc[it] = p.token_scales[max(r, 0)];
+            }
             // (rank groups beyond the adapter's re-read its last one; they are zeroed below)
             hp[it] = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * min(jg, (s.rank - 1) >> 3);
             h_load8(p, hp[it], h0[it], h1[it]);
@@ -587,7 +593,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                 const float raw = e < 4 ? h0[it][e & 3] : h1[it][e & 3];
                 const bool live = i < u.len && 8 * jg + e < s.rank;
                 if (save && live) h_dst[(long long)i * s.rank + 8 * jg + e] = raw;
-                v[e] = live ? raw * s.scale : 0.f;
+                v[e] = live ? raw * sc[it] : 0.f;
             }
             u32x4 hi, lo;
             split_bf16(v, hi, lo);
@@ -845,13 +851,20 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
         else row[t] = t < u.len ? row_of(p, u.pos + t) : -1;
     }
 
+    // the rows' scales: the adapter's, or the tokens' own (dynamic scaling, Section 3.3)
+    float tsc[kTT];
+#pragma unroll
+    for (int t = 0; t < kTT; ++t) tsc[t] = p.token_scales ? p.token_scales[max(row[t], 0)] : s.scale;
+
     // item i = lane + 64 q is (row t = i % 4, rank j = i / 4); the first two per lane cover ranks up to 32
+    static_assert(kTT == 4, "the scale of an item's row is picked by name");
     auto h_item = [&](int i) {
         const int t = i & (kTT - 1), j = i >> 2;
         const float h = h_sum(p, u.pos + min(t, u.len - 1), min(j, s.rank - 1), parts);
         const bool live = t < u.len && j < s.rank;
         if (save && live) h_dst[(long long)t * s.rank + j] = h;
-        return live ? h * s.scale : 0.f;
+        const float scale = t == 0 ? tsc[0] : t == 1 ? tsc[1] : t == 2 ? tsc[2] : tsc[3];
+        return live ? h * scale : 0.f;
     };
     const float h0 = h_item(lane), h1 = h_item(lane + kWave);
 
@@ -1383,7 +1396,7 @@ namespace {
 // errors (NULL: word 0 of the workspace).
 lq_status forward_checked(const void* x, int64_t ldx, void* y, int64_t ldy, int32_t d_in, int32_t d_out,
                           const void* const* A_ptrs, const void* const* B_ptrs, const int32_t* ranks, const float* scales,
-                          int32_t n_adapters, int32_t max_rank, const int32_t* perm, int32_t n_tokens,
+                          const float* token_scales, int32_t n_adapters, int32_t max_rank, const int32_t* perm, int32_t n_tokens,
                           const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
                           const int32_t* n_segments, int32_t max_segments, float* h_out, const int64_t* h_offsets,
                           int32_t variant, void* workspace, size_t workspace_bytes, int32_t* err_word, hipStream_t stream,
@@ -1412,6 +1425,7 @@ lq_status forward_checked(const void* x, int64_t ldx, void* y, int64_t ldy, int3
     p.d_in = d_in; p.d_out = d_out;
     p.A_ptrs = A_ptrs; p.B_ptrs = B_ptrs; p.ranks = ranks; p.scales = scales;
     p.n_adapters = n_adapters; p.max_rank = max_rank;
+    p.token_scales = token_scales;
     p.perm = perm; p.n_tokens = n_tokens;
     p.seg_starts = seg_starts; p.seg_adapter = seg_adapter; p.seg_kind = seg_kind;
     p.n_segments = n_segments; p.max_segments = max_segments;
@@ -1439,8 +1453,8 @@ lq_status forward_checked(const void* x, int64_t ldx, void* y, int64_t ldy, int3
 extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
                                             int32_t d_in, int32_t d_out,
                                             const void* const* A_ptrs, const void* const* B_ptrs,
-                                            const int32_t* ranks, const float* scales, int32_t n_adapters,
-                                            int32_t max_rank,
+                                            const int32_t* ranks, const float* scales, const float* token_scales,
+                                            int32_t n_adapters, int32_t max_rank,
                                             const int32_t* perm, int32_t n_tokens,
                                             const int32_t* seg_starts, const int32_t* seg_adapter,
                                             const uint8_t* seg_kind,
@@ -1448,7 +1462,7 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
                                             float* h_out, const int64_t* h_offsets,
                                             int32_t variant, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return lq::forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, n_adapters, max_rank, perm, n_tokens,
+    return lq::forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, token_scales, n_adapters, max_rank, perm, n_tokens,
                                seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets, variant,
                                workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream), true);
 }
@@ -1495,8 +1509,8 @@ __global__ __launch_bounds__(1024) void clear_header_kernel(int* header)
 extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int64_t ldy,
                                                    int32_t d_in, int32_t d_out,
                                                    const void* const* A_ptrs, const void* const* B_ptrs,
-                                                   const int32_t* ranks, const float* scales, int32_t n_adapters,
-                                                   int32_t max_rank,
+                                                   const int32_t* ranks, const float* scales, const float* token_scales,
+                                                   int32_t n_adapters, int32_t max_rank,
                                                    const int32_t* perm, int32_t n_tokens,
                                                    const int32_t* seg_starts, const int32_t* seg_adapter,
                                                    const uint8_t* seg_kind,
@@ -1513,7 +1527,7 @@ extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, v
         return LQ_ERR_WORKSPACE;
     // host-side validation with a stand-in workspace address: nothing is launched, nothing is dereferenced
     void* const stand_in = reinterpret_cast<void*>(uintptr_t{256});
-    lq_status status = forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, n_adapters, max_rank, perm,
+    lq_status status = forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, token_scales, n_adapters, max_rank, perm,
                                        n_tokens, seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets,
                                        variant, stand_in, (size_t)LQ_STATIC_WORKSPACE_BYTES, error_word, nullptr, false);
     if (status != LQ_OK || n_tokens == 0 || max_segments == 0) return status;
@@ -1522,7 +1536,7 @@ extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, v
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(clear_header_kernel, dim3(1), dim3(1024), 0, st, static_cast<int*>(ws));
     if (hipGetLastError() != hipSuccess) return LQ_ERR_HIP;
-    return forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, n_adapters, max_rank, perm, n_tokens,
+    return forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, token_scales, n_adapters, max_rank, perm, n_tokens,
                            seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets, variant, ws,
                            (size_t)LQ_STATIC_WORKSPACE_BYTES, error_word, st, true);
 }

@@ -15,6 +15,7 @@ struct FwdParams {
     int d_in, d_out;
     const void* const* A_ptrs; const void* const* B_ptrs;
     const int32_t* ranks; const float* scales; int n_adapters; int max_rank;
+    const float* token_scales;  // per token row; when given it replaces scales[adapter] (null: per-adapter scales)
     const int32_t* perm; int n_tokens;
     const int32_t* seg_starts; const int32_t* seg_adapter; const uint8_t* seg_kind;
     const int32_t* n_segments; int max_segments;

@@ -31,7 +31,7 @@ class DeviceProblem:
         lq.lora_build_segments(self.token_adapter, self.token_kind, self.adapters.ranks, self.seg, self.build_ws)
         return self.seg
 
-    def forward(self, variant=lq.LQ_VARIANT_SPLIT, h_elems=None, use_perm=True):
+    def forward(self, variant=lq.LQ_VARIANT_SPLIT, h_elems=None, use_perm=True, token_scales=None):
         p = self.p
         if h_elems is None:
             h_elems = int(self.seg.h_offsets.max().item())
@@ -40,7 +40,9 @@ class DeviceProblem:
         ws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, self.adapters.max_rank, p.d_in, p.d_out, variant),
                           self.x.device)
         self.fwd_ws = ws
-        lq.lora_segmented_forward(self.x, self.y, self.adapters, self.seg, self.h_out, ws, variant, use_perm)
+        self.token_scales = None if token_scales is None else torch.from_numpy(np.ascontiguousarray(token_scales, np.float32)).to(self.x.device)
+        lq.lora_segmented_forward(self.x, self.y, self.adapters, self.seg, self.h_out, ws, variant, use_perm,
+                                  token_scales=self.token_scales)
         torch.cuda.synchronize()
         return lq.bits_from_bf16(self.y), self.h_out[:h_elems].cpu().numpy(), int(ws[0].item() & 0xffffffff)
 
@@ -71,13 +73,14 @@ def assert_tables_equal(dev_tables: dict, ref) -> None:
     assert np.array_equal(dev_tables["perm"], ref.perm)
 
 
-def check_forward(oracle_mod, p: synth.Problem, variant=lq.LQ_VARIANT_SPLIT):
+def check_forward(oracle_mod, p: synth.Problem, variant=lq.LQ_VARIANT_SPLIT, token_scales=None):
     """Full element-by-element comparison of one problem with the oracle."""
-    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind,
+                             token_scales=token_scales)
     d = DeviceProblem(p)
     d.build()
     assert_tables_equal(d.seg.to_host(), ref.segments)
-    y_bits, h, err = d.forward(variant, h_elems=ref.segments.h_elems)
+    y_bits, h, err = d.forward(variant, h_elems=ref.segments.h_elems, token_scales=token_scales)
     assert err == 0
     y = synth.bf16_bits_to_f64(y_bits)
     assert_close(y, ref.y, f"{p.name} y")

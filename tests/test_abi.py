@@ -59,7 +59,7 @@ def test_host_validation_returns_codes_without_launching(lqlib):
 
     def fwd(x=one, ldx=64, y=al, ldy=64, d_in=64, d_out=64, n_ad=2, max_rank=8, T=4, max_seg=4, variant=0,
             ws=ctypes.c_void_p(0x4000), ws_bytes=1 << 30):
-        return L.lora_segmented_forward(x, ldx, y, ldy, d_in, d_out, one, one, one, one, n_ad, max_rank, one, T,
+        return L.lora_segmented_forward(x, ldx, y, ldy, d_in, d_out, one, one, one, one, None, n_ad, max_rank, one, T,
                                         one, one, one, one, max_seg, None, None, variant, ws, ws_bytes, None)
 
     assert fwd(d_in=0) == lqlib.LQ_ERR_INVALID_ARG
@@ -76,7 +76,7 @@ def test_host_validation_returns_codes_without_launching(lqlib):
 
     def bwd(x=one, dy=al, dx=ctypes.c_void_p(0x3000), d_in=64, d_out=64, ldx=64, T=4, ws=ctypes.c_void_p(0x4000),
             ws_bytes=1 << 30, max_rank=8, variant=1):
-        return L.lora_segmented_backward(x, ldx, dy, 64, dx, 64, d_in, d_out, one, one, None, None, one, one, 2, max_rank,
+        return L.lora_segmented_backward(x, ldx, dy, 64, dx, 64, d_in, d_out, one, one, None, None, one, one, None, 2, max_rank,
                                          one, T, one, one, one, one, 4, None, None, variant, ws, ws_bytes, None)
 
     assert bwd(variant=2) == lqlib.LQ_ERR_INVALID_ARG            # only the two-launch and the single-launch forms

@@ -19,16 +19,17 @@ WGRAD_REL_MAX = 2e-3   # of the largest reference magnitude
 VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED]
 
 
-def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_FUSED, dx0_seed=5):
+def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_FUSED, dx0_seed=5, token_scales=None):
     """Forward (for the saved h) and backward, both in `variant`, against the oracle's gradient."""
     rng = np.random.default_rng(dx0_seed)
     dx0 = synth.normal_bf16(rng, (p.n_tokens, p.d_in), 1.0)
     ref_f = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
-    ref_b = oracle_mod.backward(p.x, p.dy, dx0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    ref_b = oracle_mod.backward(p.x, p.dy, dx0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind,
+                                token_scales=token_scales)
 
     d = DeviceProblem(p)
     d.build()
-    d.forward(variant, h_elems=ref_f.segments.h_elems)          # writes h_out, which the backward consumes
+    d.forward(variant, h_elems=ref_f.segments.h_elems, token_scales=token_scales)   # writes h_out, which the backward consumes
     dev = d.x.device
     dx = lq.bf16_from_bits(dx0, dev)
     dA = [torch.zeros(int(r), p.d_in, dtype=torch.float32, device=dev) for r in p.ranks]
@@ -36,7 +37,8 @@ def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_FUSED, dx0_seed=5):
     dA_ptrs = torch.tensor([t.data_ptr() for t in dA], dtype=torch.int64, device=dev)
     dB_ptrs = torch.tensor([t.data_ptr() for t in dB], dtype=torch.int64, device=dev)
     ws = lq.workspace(lq.lora_backward_workspace_bytes(p.n_tokens, p.n_adapters, d.adapters.max_rank, p.d_in, p.d_out), dev)
-    lq.lora_segmented_backward(d.x, d.dy, dx, d.adapters, dA_ptrs, dB_ptrs, d.seg, d.h_out, ws, variant)
+    lq.lora_segmented_backward(d.x, d.dy, dx, d.adapters, dA_ptrs, dB_ptrs, d.seg, d.h_out, ws, variant,
+                               token_scales=d.token_scales)
     torch.cuda.synchronize()
     assert int(ws[0].item() & 0xffffffff) == 0
 
@@ -73,6 +75,16 @@ def test_backward_small_mixed(oracle_mod, variant, seed, T, d_in, d_out, ranks):
     p = synth.small_mixed(seed, T, d_in, d_out, ranks, drop_frac=0.1, with_dy=True, w_std=0.03,
                           scales=np.linspace(0.5, 1.5, len(ranks)))
     run_backward(oracle_mod, p, variant)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_backward_dynamic_per_token_scale(oracle_mod, variant):
+    """The gradient with Section 3.3's dynamic scale: the row's own scale inside every sum over rows."""
+    p = synth.small_mixed(14, 1300, 1032, 520, [32, 8, 24], drop_frac=0.1, with_dy=True, w_std=0.03)
+    p.scales = np.full_like(p.scales, 1000.0)       # must be ignored
+    rng = np.random.default_rng(3)
+    ts = rng.choice([0.0, 0.25, -0.5, 1.0, 1.5, 2.0], size=p.n_tokens).astype(np.float32)
+    run_backward(oracle_mod, p, variant, token_scales=ts)
 
 
 def test_backward_without_weight_gradients(oracle_mod):

@@ -189,6 +189,30 @@ def test_config3_unified(oracle_mod, variant, y0_zero):
     check_forward(oracle_mod, synth.config3(y0_zero=y0_zero), variant)
 
 
+def request_scales(p, seed):
+    """A per-token scale as per-request dynamic scaling would produce it: runs of tokens (requests) share a value,
+    different requests of the same adapter differ; some are negative, some zero."""
+    rng = np.random.default_rng(seed)
+    ts = np.empty(p.n_tokens, np.float32)
+    t = 0
+    while t < p.n_tokens:
+        n = int(rng.integers(1, 40))
+        ts[t: t + n] = rng.choice([0.0, 0.25, -0.5, 1.0, 1.5, 2.0, 3.0])
+        t += n
+    return ts
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("y0_zero", [False, True])
+def test_dynamic_per_token_scale(oracle_mod, variant, y0_zero):
+    """Section 3.3's dynamic scaling: token_scales replaces the per-adapter scale row by row, in the short (decode)
+    units and in the long (MFMA) ones, with and without a k split; the saved h stays unscaled."""
+    for p in (synth.small_mixed(51, 300, 1032, 776, [16, 128, 5, 24, 33], drop_frac=0.1, y0_zero=y0_zero, w_std=0.03),   # (|y| stays below 8)
+              synth.config2(y0_zero=y0_zero), synth.config3(y0_zero=y0_zero)):
+        p.scales = np.full_like(p.scales, 1000.0)       # must be ignored
+        check_forward(oracle_mod, p, variant, token_scales=request_scales(p, 7))
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_repeat_calls_are_bit_identical(variant):
     p = synth.config2()

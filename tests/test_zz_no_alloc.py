@@ -22,7 +22,7 @@ def _call_static(d, h_out, err, variant):
     st = L.lora_segmented_forward_static(
         d.x.data_ptr(), d.x.stride(0), d.y.data_ptr(), d.y.stride(0), p.d_in, p.d_out,
         d.adapters.A_ptrs.data_ptr(), d.adapters.B_ptrs.data_ptr(), d.adapters.ranks.data_ptr(), d.adapters.scales.data_ptr(),
-        d.adapters.n_adapters, d.adapters.max_rank, d.seg.perm.data_ptr(), p.n_tokens,
+        None, d.adapters.n_adapters, d.adapters.max_rank, d.seg.perm.data_ptr(), p.n_tokens,
         d.seg.seg_starts.data_ptr(), d.seg.seg_adapter.data_ptr(), d.seg.seg_kind.data_ptr(), d.seg.n_segments.data_ptr(),
         d.seg.max_segments, h_out.data_ptr(), d.seg.h_offsets.data_ptr(), variant, err.data_ptr(),
         torch.cuda.current_stream().cuda_stream)
@@ -74,7 +74,7 @@ def test_static_workspace_forward_refuses_what_does_not_fit():
         return L.lora_segmented_forward_static(
             d.x.data_ptr(), d.x.stride(0), d.y.data_ptr(), d.y.stride(0), p.d_in, p.d_out,
             d.adapters.A_ptrs.data_ptr(), d.adapters.B_ptrs.data_ptr(), d.adapters.ranks.data_ptr(),
-            d.adapters.scales.data_ptr(), d.adapters.n_adapters, max_rank, d.seg.perm.data_ptr(), n_tokens,
+            d.adapters.scales.data_ptr(), None, d.adapters.n_adapters, max_rank, d.seg.perm.data_ptr(), n_tokens,
             d.seg.seg_starts.data_ptr(), d.seg.seg_adapter.data_ptr(), d.seg.seg_kind.data_ptr(),
             d.seg.n_segments.data_ptr(), d.seg.max_segments, h_out.data_ptr(), d.seg.h_offsets.data_ptr(), variant,
             err.data_ptr(), None)
