@@ -65,6 +65,7 @@ enum { LQ_SEG_FINETUNE = 0, LQ_SEG_PREFILL = 1, LQ_SEG_DECODE = 2 };
 enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1, LQ_VARIANT_SHRINK_ONLY = 2, LQ_VARIANT_EXPAND_ONLY = 3 };
 
 #define LQ_MAX_RANK 128
+#define LQ_MAX_GROUP 4      /* linear layers per grouped call */
 #define LQ_MAX_ADAPTERS 4096
 
 const char* lora_status_string(lq_status status);
@@ -151,6 +152,38 @@ lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ld
                                  const int32_t* n_segments, int32_t max_segments,
                                  float* h_out, const int64_t* h_offsets,
                                  int32_t variant, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Grouped forward: n_proj linear layers that read the SAME x in one call, each with its own y,
+ * d_out, adapter tables and saved h.  Algorithm 1 computes Q, K and V from one X (and the MLP its
+ * gate and up projections from one X); issued as one call they share the pass over x (workgroups
+ * that share an L2 take the same rows of different layers side by side) and the launch.  The batch,
+ * its tables, ranks, scales and token_scales are common to the layers; adapter a has the same rank in
+ * every layer.  The result of every layer is what lora_segmented_forward gives for it alone.
+ *
+ *   host_y, host_ldy, host_d_out, host_A_ptrs, host_B_ptrs, host_h_out
+ *            HOST arrays of n_proj entries (read during the call, not kept): per layer the device
+ *            pointer y, its leading dimension, d_out, the device pointer tables A_ptrs / B_ptrs
+ *            ([n_adapters] device pointers to bf16 [r_a, d_in] / [r_a, d_out]) and the device pointer
+ *            h_out (host_h_out or any of its entries may be NULL: nothing saved)
+ *   n_proj   1..LQ_MAX_GROUP; the y of two layers must differ
+ *   workspace lora_forward_group_workspace_bytes(n_proj, n_tokens, max_rank) bytes, first 4096 zero
+ *            as for the single call
+ *   everything else as in lora_segmented_forward.
+ * ------------------------------------------------------------------------------------------- */
+size_t lora_forward_group_workspace_bytes(int32_t n_proj, int32_t n_tokens, int32_t max_rank);
+
+lq_status lora_segmented_forward_group(const void* x, int64_t ldx, int32_t d_in, int32_t n_proj,
+                                       void* const* host_y, const int64_t* host_ldy, const int32_t* host_d_out,
+                                       const void* const* const* host_A_ptrs, const void* const* const* host_B_ptrs,
+                                       float* const* host_h_out,
+                                       const int32_t* ranks, const float* scales, const float* token_scales,
+                                       int32_t n_adapters, int32_t max_rank,
+                                       const int32_t* perm, int32_t n_tokens,
+                                       const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
+                                       const int32_t* n_segments, int32_t max_segments,
+                                       const int64_t* h_offsets,
+                                       int32_t variant, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * The forward for callers that CANNOT ALLOCATE device memory: code under HIP graph capture, tight

@@ -18,6 +18,7 @@ LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, LQ_ERR_HIP = ra
 LQ_SEG_FINETUNE, LQ_SEG_PREFILL, LQ_SEG_DECODE = 0, 1, 2
 LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED, LQ_VARIANT_SHRINK_ONLY, LQ_VARIANT_EXPAND_ONLY = 0, 1, 2, 3
 LQ_MAX_RANK = 128
+LQ_MAX_GROUP = 4
 LQ_STATIC_WORKSPACE_BYTES = 4096 + (32 << 20)
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblqlora.so")
@@ -33,6 +34,9 @@ _SIGNATURES = {
     "lora_forward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "lora_segmented_forward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                               _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
+    "lora_forward_group_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "lora_segmented_forward_group": (ctypes.c_int, [_vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
+                                                    _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _sz, _vp]),
     "lora_segmented_forward_static": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                                      _vp, _i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp]),
     "lora_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
@@ -233,6 +237,56 @@ def lora_segmented_forward(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTa
                                                      token_scales))
     if st != LQ_OK:
         raise LqError(st, "lora_segmented_forward")
+
+
+def lora_forward_group_workspace_bytes(n_proj: int, n_tokens: int, max_rank: int) -> int:
+    return int(lib().lora_forward_group_workspace_bytes(n_proj, n_tokens, max_rank))
+
+
+def _group_args(x, ys, adapters, seg, h_outs, workspace, variant, use_perm, stream, token_scales):
+    """Arguments of lora_segmented_forward_group; the host arrays are returned as well (they must outlive the call)."""
+    n = len(ys)
+    assert n == len(adapters) and 1 <= n <= LQ_MAX_GROUP and (h_outs is None or len(h_outs) == n)
+    assert x.dtype == torch.bfloat16 and x.stride(1) == 1 and all(y.dtype == torch.bfloat16 and y.stride(1) == 1 for y in ys)
+    a0 = adapters[0]
+    assert all(ad.n_adapters == a0.n_adapters and ad.max_rank == a0.max_rank for ad in adapters)
+    n_tokens, d_in = int(x.shape[0]), int(x.shape[1])
+    hy = (ctypes.c_void_p * n)(*[y.data_ptr() for y in ys])
+    hld = (ctypes.c_int64 * n)(*[y.stride(0) for y in ys])
+    hd = (ctypes.c_int32 * n)(*[int(y.shape[1]) for y in ys])
+    hA = (ctypes.c_void_p * n)(*[ad.A_ptrs.data_ptr() for ad in adapters])
+    hB = (ctypes.c_void_p * n)(*[ad.B_ptrs.data_ptr() for ad in adapters])
+    hh = None if h_outs is None else (ctypes.c_void_p * n)(*[_ptr(h) for h in h_outs])
+    keep = (hy, hld, hd, hA, hB, hh)
+    cast = lambda a: None if a is None else ctypes.cast(a, ctypes.c_void_p)
+    args = (_ptr(x), x.stride(0), d_in, n, cast(hy), cast(hld), cast(hd), cast(hA), cast(hB), cast(hh),
+            _ptr(a0.ranks), _ptr(a0.scales), _token_scales_ptr(token_scales, n_tokens), a0.n_adapters, a0.max_rank,
+            _ptr(seg.perm) if use_perm else None, n_tokens,
+            _ptr(seg.seg_starts), _ptr(seg.seg_adapter), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments,
+            _ptr(seg.h_offsets) if h_outs is not None else None,
+            variant, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    return args, keep
+
+
+def lora_segmented_forward_group(x: torch.Tensor, ys: Sequence[torch.Tensor], adapters: Sequence[AdapterTable],
+                                 seg: SegmentTables, h_outs: Optional[Sequence[Optional[torch.Tensor]]],
+                                 workspace: torch.Tensor, variant: int = LQ_VARIANT_FUSED, use_perm: bool = True, stream=None,
+                                 token_scales: Optional[torch.Tensor] = None) -> None:
+    """Several linear layers that read the same x (q, k, v; gate, up) in one call.  The adapter tables of the
+    layers must agree in the number of adapters, their ranks and their scales (those of adapters[0] are used)."""
+    args, keep = _group_args(x, ys, adapters, seg, h_outs, workspace, variant, use_perm, stream, token_scales)
+    st = lib().lora_segmented_forward_group(*args)
+    del keep
+    if st != LQ_OK:
+        raise LqError(st, "lora_segmented_forward_group")
+
+
+def prepare_forward_group(x, ys, adapters, seg, h_outs, workspace, variant=LQ_VARIANT_FUSED, use_perm=True, stream=None,
+                          token_scales=None) -> PreparedCall:
+    args, keep = _group_args(x, ys, adapters, seg, h_outs, workspace, variant, use_perm, stream, token_scales)
+    call = PreparedCall(lib().lora_segmented_forward_group, args, "lora_segmented_forward_group")
+    call.keep = keep   # the host arrays the arguments point to
+    return call
 
 
 def lora_segmented_forward_static(x: torch.Tensor, y: torch.Tensor, adapters: AdapterTable, seg: SegmentTables,

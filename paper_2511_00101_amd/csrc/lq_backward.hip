@@ -355,18 +355,17 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
         return LQ_ERR_WORKSPACE;
     if (n_tokens == 0 || max_segments == 0) return LQ_OK;
 
-    int seg_bound = max_segments;
-    if (seg_bound > n_tokens) seg_bound = n_tokens;
-    if (seg_bound > n_adapters) seg_bound = n_adapters;  // fine-tune segments only
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
 
     // 1. g = dy B^T on fine-tune rows: the forward's shrink over d_out against B
     FwdParams s1;
     s1.x = static_cast<const u16*>(dy); s1.ldx = lddy;
-    s1.y = static_cast<u16*>(dx); s1.ldy = lddx;
-    s1.d_in = d_out; s1.d_out = d_in;
-    s1.A_ptrs = B_ptrs; s1.B_ptrs = A_ptrs; s1.ranks = ranks; s1.scales = scales;
+    s1.d_in = d_out;
+    Proj q;
+    q.y = static_cast<u16*>(dx); q.ldy = lddx; q.d_out = d_in;
+    q.A_ptrs = B_ptrs; q.B_ptrs = A_ptrs;
+    s1.ranks = ranks; s1.scales = scales;
     s1.n_adapters = n_adapters; s1.max_rank = max_rank;
     s1.token_scales = token_scales;
     s1.perm = perm; s1.n_tokens = n_tokens;
@@ -375,8 +374,11 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     // the finished g goes where the forward would save h: [segment offset + row x rank + j], for the weight gradients
     float* gsum = reinterpret_cast<float*>(ws + kWsHeaderBytes + h_slices_bytes(n_tokens, max_rank));
     const bool want_w = dA_ptrs || dB_ptrs;
-    s1.h_out = want_w ? gsum : nullptr; s1.h_offsets = want_w ? reinterpret_cast<const long long*>(h_offsets) : nullptr;
+    q.h_out = want_w ? gsum : nullptr; s1.h_offsets = want_w ? reinterpret_cast<const long long*>(h_offsets) : nullptr;
+    s1.n_proj = 1;
+    for (int k = 0; k < kMaxProj; ++k) s1.proj[k] = q;
     s1.hpart = reinterpret_cast<float*>(ws + kWsHeaderBytes);
+    s1.hproj = 0;
     s1.ksplit = 1; s1.rstride = rstride_for(max_rank);
     s1.header = s1.err = reinterpret_cast<int*>(ws); s1.tickets = reinterpret_cast<int*>(ws) + 4;
     s1.ksplit_hint = 0; s1.kinds = kFinetuneOnly;
@@ -386,11 +388,11 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     const bool one_launch = variant == LQ_VARIANT_FUSED && h_slices_bytes(n_tokens, max_rank) <= 0x7fffffffull;
     s1.coherent = one_launch; s1.hpart_bytes = one_launch ? (unsigned int)h_slices_bytes(n_tokens, max_rank) : 0;
     if (one_launch) {
-        if (run_shrink_expand(s1, LQ_VARIANT_FUSED, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+        if (run_shrink_expand(s1, LQ_VARIANT_FUSED, st) != hipSuccess) return LQ_ERR_HIP;
     } else {
-        if (run_shrink_expand(s1, LQ_VARIANT_SHRINK_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+        if (run_shrink_expand(s1, LQ_VARIANT_SHRINK_ONLY, st) != hipSuccess) return LQ_ERR_HIP;
         s1.ksplit_hint = s1.ksplit;
-        if (run_shrink_expand(s1, LQ_VARIANT_EXPAND_ONLY, seg_bound, st) != hipSuccess) return LQ_ERR_HIP;
+        if (run_shrink_expand(s1, LQ_VARIANT_EXPAND_ONLY, st) != hipSuccess) return LQ_ERR_HIP;
     }
 
     // 3. partial weight gradients (from x, dy, the saved h and the finished g), then their reduction into dA / dB

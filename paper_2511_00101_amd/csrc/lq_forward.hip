@@ -122,20 +122,21 @@ struct HDest { float* base; float* save; int save_ld; };
 __device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, int nsplit)
 {
     HDest d;
-    d.base = p.hpart + ((long long)ks * p.n_tokens + u.pos) * p.rstride;
-    const bool save = nsplit == 1 && u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets;
-    d.save = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
+    d.base = p.hpart + u.pi * p.hproj + ((long long)ks * p.n_tokens + u.pos) * p.rstride;
+    float* h_out = p.proj[u.pi].h_out;
+    const bool save = nsplit == 1 && u.kd == LQ_SEG_FINETUNE && h_out && p.h_offsets;
+    d.save = save ? h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     d.save_ld = s.rank;
     return d;
 }
 
 // finished h of one element: the slices added in order
-__device__ __forceinline__ float h_sum(const FwdParams& p, long long pos, int j, int parts)
+__device__ __forceinline__ float h_sum(const FwdParams& p, int pi, long long pos, int j, int parts)
 {
     // the first four slices are requested together (a slice that does not exist re-reads the last one and is
     // not added): one round trip instead of one per slice
     const long long slice = (long long)p.n_tokens * p.rstride;
-    const float* at = p.hpart + pos * p.rstride + j;
+    const float* at = p.hpart + pi * p.hproj + pos * p.rstride + j;
     float v[4];
 #pragma unroll
     for (int part = 0; part < 4; ++part) v[part] = h_load(at + min(part, parts - 1) * slice, p.coherent);
@@ -509,6 +510,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     using C = ExpandCfg<KSTEPS, PAIRS>;
     constexpr int STAGE = C::ROWS * (C::UN / 8) / kThreads;  // 16-byte pieces of the B block per thread
     static_assert(C::ROWS * (C::UN / 8) % kThreads == 0, "staging loop assumes an even split");
+    const Proj pj = p.proj[u.pi];  // this unit's linear layer: y, d_out (B comes with s)
     u16* lds_b = reinterpret_cast<u16*>(lds);
     u32x4* lds_h = reinterpret_cast<u32x4*>(lds + C::B_BYTES);
     int* lds_row = reinterpret_cast<int*>(lds + C::B_BYTES + C::H_BYTES);
@@ -523,7 +525,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         for (int i = 0; i < STAGE; ++i) {
             const int id = (int)threadIdx.x + i * kThreads;
             const int j = id / (C::UN / 8), n = n_block * C::UN + (id % (C::UN / 8)) * 8;
-            bstage[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * p.d_out + min(n, p.d_out - 8));
+            bstage[i] = *(gconst_u32x4)(s.B + (long long)min(j, s.rank - 1) * pj.d_out + min(n, pj.d_out - 8));
         }
     };
     if constexpr (AHEAD) {
@@ -543,8 +545,8 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     }
     LQ_STAMP(1, LQ_UNIT_SLOT(u.it, 1));
     const int parts = p.ksplit;
-    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && nb_begin == 0 && parts > 1;
-    float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
+    const bool save = u.kd == LQ_SEG_FINETUNE && pj.h_out && p.h_offsets && nb_begin == 0 && parts > 1;
+    float* h_dst = save ? pj.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     {
         // item = (row i, 8 ranks); a thread's items are loaded together, slice after slice
         constexpr int ITEMS = C::CT * (C::ROWS / 8) / kThreads;
@@ -564,7 +566,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                 sc[it] = p.token_scales[max(r, 0)];
             }
             // (rank groups beyond the adapter's re-read its last one; they are zeroed below)
-            hp[it] = p.hpart + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * min(jg, (s.rank - 1) >> 3);
+            hp[it] = p.hpart + u.pi * p.hproj + (long long)(u.pos + min(i, u.len - 1)) * p.rstride + 8 * min(jg, (s.rank - 1) >> 3);
             h_load8(p, hp[it], h0[it], h1[it]);
         }
         for (int part = 1; part < parts; ++part) {
@@ -612,19 +614,19 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     int row_f[4];
     u32x4 y_f[4];
     if constexpr (PAIRS == 2) {
-        const int n_ld = min(n_unit + w * C::WN + 8 * (lane & 7), p.d_out - 8);
+        const int n_ld = min(n_unit + w * C::WN + 8 * (lane & 7), pj.d_out - 8);
         const int safe = max(lds_row[0], 0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             row_f[j] = lds_row[min(8 * j + (lane >> 3), C::CT - 1)];
-            y_f[j] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row_f[j] >= 0 ? row_f[j] : safe) * p.ldy + n_ld);
+            y_f[j] = *reinterpret_cast<const u32x4*>(pj.y + (long long)(row_f[j] >= 0 ? row_f[j] : safe) * pj.ldy + n_ld);
         }
     }
 #pragma unroll
     for (int i = 0; i < STAGE; ++i) {
         const int id = (int)threadIdx.x + i * kThreads;
         const int j = id / (C::UN / 8), n = n_unit + (id % (C::UN / 8)) * 8;
-        const bool live = j < s.rank && n < p.d_out;
+        const bool live = j < s.rank && n < pj.d_out;
         *reinterpret_cast<u32x4*>(lds_b + j * C::BPITCH + (n - n_unit)) = live ? bstage[i] : u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
@@ -642,7 +644,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         }
     if (n_block == nb_begin) LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 4));
     if constexpr (PAIRS == 2) __syncthreads();  // every wave has its fragments: the B block's LDS becomes scratch
-    if (n_wave >= p.d_out) continue;
+    if (n_wave >= pj.d_out) continue;
 
     const int n_steps = (u.len + 31) / 32;
     const int safe_row = max(lds_row[0], 0);
@@ -656,14 +658,14 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         // Loads are unconditional (dead rows and columns read a live address); only the stores are masked.
         float* slab = reinterpret_cast<float*>(lds_b) + w * (16 * 64);
         const int r8 = lane >> 3, piece = lane & 7;
-        const int n_c = n_wave + 8 * piece, n_ld = min(n_c, p.d_out - 8);
+        const int n_c = n_wave + 8 * piece, n_ld = min(n_c, pj.d_out - 8);
         int row_n[4];
         u32x4 y_n[4];
         auto fetch = [&](int step) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 row_n[j] = lds_row[min(step * 32 + 8 * j + r8, C::CT - 1)];
-                y_n[j] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row_n[j] >= 0 ? row_n[j] : safe_row) * p.ldy + n_ld);
+                y_n[j] = *reinterpret_cast<const u32x4*>(pj.y + (long long)(row_n[j] >= 0 ? row_n[j] : safe_row) * pj.ldy + n_ld);
             }
         };
 #pragma unroll
@@ -711,7 +713,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                     const int j = 2 * t + jj, rt = 8 * jj + r8;  // row of the step's instruction j = row rt of the tile
                     const f32x4 d0 = *reinterpret_cast<const f32x4*>(slab + rt * 64 + (((2 * piece) ^ rt) & 15) * 4);
                     const f32x4 d1 = *reinterpret_cast<const f32x4*>(slab + rt * 64 + (((2 * piece + 1) ^ rt) & 15) * 4);
-                    if (row[j] >= 0 && step * 32 + 8 * j + r8 < u.len && n_c < p.d_out) {
+                    if (row[j] >= 0 && step * 32 + 8 * j + r8 < u.len && n_c < pj.d_out) {
                         float yf[8];
                         unpack8(yv[j], yf);
                         u32x4 o;
@@ -719,7 +721,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                         o.y = pack_bf16x2(yf[2] + d0[2], yf[3] + d0[3]);
                         o.z = pack_bf16x2(yf[4] + d1[0], yf[5] + d1[1]);
                         o.w = pack_bf16x2(yf[6] + d1[2], yf[7] + d1[3]);
-                        *reinterpret_cast<u32x4*>(p.y + (long long)row[j] * p.ldy + n_c) = o;
+                        *reinterpret_cast<u32x4*>(pj.y + (long long)row[j] * pj.ldy + n_c) = o;
                     }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -734,14 +736,14 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
         const int n_lane = n_wave + 8 * g;  // + 32 q
         int n_ld[PAIRS];
     #pragma unroll
-        for (int q = 0; q < PAIRS; ++q) n_ld[q] = min(n_lane + 32 * q, p.d_out - 8);
+        for (int q = 0; q < PAIRS; ++q) n_ld[q] = min(n_lane + 32 * q, pj.d_out - 8);
         int row_n[2];
         u32x4 y_n[2][PAIRS];
         auto fetch = [&](int step) {
     #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 row_n[t] = lds_row[min(step * 32 + t * 16 + c, C::CT - 1)];
-                const u16* yrow = p.y + (long long)(row_n[t] >= 0 ? row_n[t] : safe_row) * p.ldy;
+                const u16* yrow = pj.y + (long long)(row_n[t] >= 0 ? row_n[t] : safe_row) * pj.ldy;
     #pragma unroll
                 for (int q = 0; q < PAIRS; ++q) y_n[t][q] = *reinterpret_cast<const u32x4*>(yrow + n_ld[q]);
             }
@@ -784,7 +786,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                 if (row[t] >= 0 && step * 32 + t * 16 + c < u.len) {
     #pragma unroll
                     for (int q = 0; q < PAIRS; ++q) {
-                        if (n_lane + 32 * q < p.d_out) {
+                        if (n_lane + 32 * q < pj.d_out) {
                             float yf[8];
                             unpack8(yv[t][q], yf);
                             u32x4 o;
@@ -792,7 +794,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
                             o.y = pack_bf16x2(yf[2] + acc[q][0][2], yf[3] + acc[q][0][3]);
                             o.z = pack_bf16x2(yf[4] + acc[q][1][0], yf[5] + acc[q][1][1]);
                             o.w = pack_bf16x2(yf[6] + acc[q][1][2], yf[7] + acc[q][1][3]);
-                            *reinterpret_cast<u32x4*>(p.y + (long long)row[t] * p.ldy + n_lane + 32 * q) = o;
+                            *reinterpret_cast<u32x4*>(pj.y + (long long)row[t] * pj.ldy + n_lane + 32 * q) = o;
                         }
                     }
                 }
@@ -834,12 +836,13 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
 {
     constexpr int JG = kShortGroup;
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
+    const Proj pj = p.proj[u.pi];  // this unit's linear layer: y, d_out (B comes with s)
     float* hs = &sh.hs[w][0][0];  // hs[j][t] at j * kTT + t
     const int parts = p.ksplit;
-    const bool save = u.kd == LQ_SEG_FINETUNE && p.h_out && p.h_offsets && n_block == 0 && parts > 1;
-    float* h_dst = save ? p.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
+    const bool save = u.kd == LQ_SEG_FINETUNE && pj.h_out && p.h_offsets && n_block == 0 && parts > 1;
+    float* h_dst = save ? pj.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     const int n = n_block * kShortN + lane * 8;
-    const int n_ld = min(n, p.d_out - 8);
+    const int n_ld = min(n, pj.d_out - 8);
     const int rank_up = (s.rank + JG - 1) / JG * JG;
 
     // The loads go out in the order rows, h, first group of B, y, so that each wait covers only what is
@@ -860,7 +863,7 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     static_assert(kTT == 4, "the scale of an item's row is picked by name");
     auto h_item = [&](int i) {
         const int t = i & (kTT - 1), j = i >> 2;
-        const float h = h_sum(p, u.pos + min(t, u.len - 1), min(j, s.rank - 1), parts);
+        const float h = h_sum(p, u.pi, u.pos + min(t, u.len - 1), min(j, s.rank - 1), parts);
         const bool live = t < u.len && j < s.rank;
         if (save && live) h_dst[(long long)t * s.rank + j] = h;
         const float scale = t == 0 ? tsc[0] : t == 1 ? tsc[1] : t == 2 ? tsc[2] : tsc[3];
@@ -873,13 +876,13 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
     u32x4 bn[JG];
 #pragma unroll
     for (int jj = 0; jj < JG; ++jj)
-        bn[jj] = *(gconst_u32x4)(s.B + (long long)min(J_RING + jj, s.rank - 1) * p.d_out + n_ld);
+        bn[jj] = *(gconst_u32x4)(s.B + (long long)min(J_RING + jj, s.rank - 1) * pj.d_out + n_ld);
     const int safe_row = max(row[0], 0);
     u32x4 yv[kTT];
 #pragma unroll
     for (int t = 0; t < kTT; ++t) {
         if constexpr (AHEAD) yv[t] = pre.y[t];
-        else yv[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(row[t] >= 0 ? row[t] : safe_row) * p.ldy + n_ld);
+        else yv[t] = *reinterpret_cast<const u32x4*>(pj.y + (long long)(row[t] >= 0 ? row[t] : safe_row) * pj.ldy + n_ld);
     }
 
     hs[lane] = h0;
@@ -917,12 +920,12 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
         for (int jj = 0; jj < JG; ++jj) bc[jj] = bn[jj];
 #pragma unroll
         for (int jj = 0; jj < JG; ++jj)  // the next group (past the end: the last row again, unused)
-            bn[jj] = *(gconst_u32x4)(s.B + (long long)min(j0 + JG + jj, s.rank - 1) * p.d_out + n_ld);
+            bn[jj] = *(gconst_u32x4)(s.B + (long long)min(j0 + JG + jj, s.rank - 1) * pj.d_out + n_ld);
         __builtin_amdgcn_sched_barrier(0);
         fma_group(bc, j0);
         __builtin_amdgcn_sched_barrier(0);
     }
-    if (n < p.d_out) {
+    if (n < pj.d_out) {
 #pragma unroll
         for (int t = 0; t < kTT; ++t) {
             if (row[t] >= 0) {
@@ -933,7 +936,7 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
                 o.y = pack_bf16x2(yf[2] + acc[t][2], yf[3] + acc[t][3]);
                 o.z = pack_bf16x2(yf[4] + acc[t][4], yf[5] + acc[t][5]);
                 o.w = pack_bf16x2(yf[6] + acc[t][6], yf[7] + acc[t][7]);
-                *reinterpret_cast<u32x4*>(p.y + (long long)row[t] * p.ldy + n) = o;
+                *reinterpret_cast<u32x4*>(pj.y + (long long)row[t] * pj.ldy + n) = o;
             }
         }
     }
@@ -964,12 +967,24 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdP
     const ClassScan ct = scan_class(p, sg, kTallRows, tall), cr = scan_class(p, sg, kTallRows, rest),
                     cm = scan_class(p, sg, kShortRows, small);
     const int n_full = ct.total << p.ks_log2, n_tall = n_full + (cr.total << p.ks_log2), n_small = cm.total << p.ks_log2;
+    // A grouped call runs every unit once per projection.  Workgroups whose indices differ by 8 sit on the same XCD
+    // and share its L2, so the projections of one unit are handed to such workgroups (ids r, r + 8, r + 16 ... of a
+    // block of 8 n_proj ids): they run side by side and the x rows they all read cross the HBM interface once.
+    const int n_per = n_tall + n_small, n_all = p.n_proj == 1 ? n_per : ((n_per + 7) & ~7) * p.n_proj;
     LQ_STAMP(0, 2);
-    for_each_unit(p.tickets + 0, n_tall + n_small, s_slot, [&](int id, int it) {
+    for_each_unit(p.tickets + 0, n_all, s_slot, [&](int gid, int it) {
         Unit u;
         SegInfo s;
         u.it = it;
         LQ_STAMP(0, LQ_UNIT_SLOT(it, 0));
+        int id = gid;
+        u.pi = 0;
+        if (p.n_proj > 1) {
+            const int blk = small_div(gid, 8 * p.n_proj), r = gid - blk * 8 * p.n_proj;
+            u.pi = r >> 3;
+            id = blk * 8 + (r & 7);
+            if (id >= n_per) return;  // (padding of the last block)
+        }
         const bool is_tall = id < n_tall;
         const int cid = id < n_full ? id : is_tall ? id - n_full : id - n_tall;
         const int chunk = cid >> p.ks_log2, ks = cid & (p.ksplit - 1);
@@ -1012,13 +1027,35 @@ __global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
 }
 
 // What the expand phase works out from the segment tables before it touches any data: the rows per long
-// unit, the classes of units and their prefix sums.  (The fused kernel does this before its barrier.)
+// unit, the classes of units and their prefix sums, and per projection of a grouped call its column blocks and
+// how they are grouped into units.  (The fused kernel does this before its barrier.)
 struct ExpandPlan {
-    int per, long_blocks, n_chunks, short_blocks, n_short;
-    int groups, per_group, n_full, n_big, n_long;  // long units: column groups per chunk, numbering of the classes
+    int per, n_chunks, n_short;
+    int long_blocks[kMaxProj], per_group[kMaxProj], groups[kMaxProj], short_blocks[kMaxProj];
+    int sum_groups, sum_short_blocks;  // over the projections
+    int n_full, n_big, n_long;         // long units: numbering of the classes
     LenClass shorts, full, big, little;
     ClassScan cf, cb, cl, cs;
 };
+
+// a[i] for a wave-uniform i (the arrays live in registers, which cannot be indexed)
+__device__ __forceinline__ int pick(const int (&a)[kMaxProj], int i)
+{
+    static_assert(kMaxProj == 4, "the entries are picked by name");
+    return i == 0 ? a[0] : i == 1 ? a[1] : i == 2 ? a[2] : a[3];
+}
+// index i into the concatenation of n ranges of lengths len[0 .. n): the range, and the index inside it
+__device__ __forceinline__ int range_of(const int (&len)[kMaxProj], int n, int& i)
+{
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < kMaxProj - 1; ++k)
+        if (r == k && k + 1 < n && i >= len[k]) {
+            i -= len[k];
+            r = k + 1;
+        }
+    return r;
+}
 
 template <int KSTEPS, int PAIRS>
 __device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs<FwdParams>& sg)
@@ -1027,7 +1064,16 @@ __device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs
     ExpandPlan e;
     const LenClass longs{kLongMin, kBig, p.kinds};
     e.shorts = LenClass{1, kLongMin, p.kinds};
-    e.long_blocks = (p.d_out + C::UN - 1) / C::UN;
+    int sum_blocks = 0;
+    e.sum_short_blocks = 0;
+#pragma unroll
+    for (int k = 0; k < kMaxProj; ++k) {
+        const int d_out = k < p.n_proj ? p.proj[k].d_out : 0;
+        e.long_blocks[k] = (d_out + C::UN - 1) / C::UN;
+        e.short_blocks[k] = (d_out + kShortN - 1) / kShortN;
+        sum_blocks += e.long_blocks[k];
+        e.sum_short_blocks += e.short_blocks[k];
+    }
 
     // Rows per long unit: CT, halved (down to 64: the B block is staged once per unit) until the units fill two
     // rounds of the grid, or exactly one: so that a batch with few rows is still spread over the whole machine,
@@ -1039,7 +1085,7 @@ __device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs
             int chunks = 0;
 #pragma unroll
             for (int b = 0; b < kCachedBatches; ++b) chunks += wave_sum(chunks_in(sg.c[b].en - sg.c[b].st, sg.c[b].kd, per, longs));
-            const long long units = (long long)chunks * e.long_blocks;
+            const long long units = (long long)chunks * sum_blocks;
             if (units >= 2LL * grid || (units >= grid && units % grid == 0)) break;
             per >>= 1;
         }
@@ -1052,20 +1098,24 @@ __device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs
     e.cb = scan_class(p, sg, per, e.big);
     e.cl = scan_class(p, sg, per, e.little);
     e.n_chunks = e.cf.total + e.cb.total + e.cl.total;
-    // Long units: a chunk of rows x a group of column blocks.  Groups are as large as possible (the rows' h is
-    // prepared once per unit) while leaving about 4 units per workgroup.
-    e.groups = e.per_group = 1;
-    if (e.n_chunks > 0) {
-        const int groups_wanted = small_div(4 * (int)gridDim.x + e.n_chunks - 1, e.n_chunks);
-        e.per_group = max(1, small_div(e.long_blocks, max(1, min(e.long_blocks, groups_wanted))));
-        e.groups = small_div(e.long_blocks + e.per_group - 1, e.per_group);
+    // Long units: a chunk of rows x a group of column blocks of one projection.  Groups are as large as possible
+    // (the rows' h is prepared once per unit) while leaving about 4 units per workgroup.
+    e.sum_groups = 0;
+    const int groups_wanted = e.n_chunks > 0 ? small_div(4 * (int)gridDim.x + e.n_chunks - 1, e.n_chunks) : 1;  // per chunk, all projections
+#pragma unroll
+    for (int k = 0; k < kMaxProj; ++k) {
+        const int blocks = e.long_blocks[k];
+        // this projection's share of the groups, by its share of the column blocks
+        const int wanted = blocks > 0 ? max(1, small_div(groups_wanted * blocks, max(1, sum_blocks))) : 1;
+        e.per_group[k] = max(1, small_div(blocks, max(1, min(blocks, wanted))));
+        e.groups[k] = small_div(blocks + e.per_group[k] - 1, e.per_group[k]);
+        e.sum_groups += e.groups[k];
     }
-    e.n_full = e.cf.total * e.groups;
-    e.n_big = e.n_full + e.cb.total * e.groups;
-    e.n_long = e.n_chunks * e.groups;
+    e.n_full = e.cf.total * e.sum_groups;
+    e.n_big = e.n_full + e.cb.total * e.sum_groups;
+    e.n_long = e.n_chunks * e.sum_groups;
     e.cs = scan_class(p, sg, kTT, e.shorts);
-    e.short_blocks = (p.d_out + kShortN - 1) / kShortN;
-    e.n_short = e.cs.total * e.short_blocks;
+    e.n_short = e.cs.total * e.sum_short_blocks;
     return e;
 }
 
@@ -1077,11 +1127,13 @@ __device__ __forceinline__ int first_short_unit(const ExpandPlan& e)
     const int w = uniform((int)threadIdx.x / kWave);
     return e.n_chunks > 0 ? (int)blockIdx.x * kWaves + w : w * (int)gridDim.x + (int)blockIdx.x;
 }
+// short unit `id`: ids count through the row chunks, and for each chunk through the 512-column blocks of every projection
 __device__ __forceinline__ bool find_short_unit(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e, int id,
                                                 Unit& u, SegInfo& s, int& n_block)
 {
-    const int chunk = small_div(id, e.short_blocks);
-    n_block = id - chunk * e.short_blocks;
+    const int chunk = small_div(id, e.sum_short_blocks);
+    n_block = id - chunk * e.sum_short_blocks;
+    u.pi = range_of(e.short_blocks, p.n_proj, n_block);
     return find_unit(p, sg, e.cs, chunk, kTT, e.shorts, u, s);
 }
 
@@ -1095,28 +1147,33 @@ __device__ __forceinline__ ShortAhead short_request(const FwdParams& p, const Se
     a.u.it = 4;
     a.live = find_short_unit(p, sg, e, id, a.u, a.s, a.n_block);
     if (!a.live) return a;
-    const int n_ld = min(a.n_block * kShortN + lane_id() * 8, p.d_out - 8);
+    const Proj q = p.proj[a.u.pi];
+    const int n_ld = min(a.n_block * kShortN + lane_id() * 8, q.d_out - 8);
 #pragma unroll
     for (int t = 0; t < kTT; ++t) a.row[t] = t < a.u.len ? row_of(p, a.u.pos + t) : -1;
 #pragma unroll
     for (int jj = 0; jj < 2 * kShortGroup; ++jj)
-        a.b[jj] = *(gconst_u32x4)(a.s.B + (long long)min(jj, a.s.rank - 1) * p.d_out + n_ld);
+        a.b[jj] = *(gconst_u32x4)(a.s.B + (long long)min(jj, a.s.rank - 1) * q.d_out + n_ld);
     const int safe_row = max(a.row[0], 0);
 #pragma unroll
     for (int t = 0; t < kTT; ++t)
-        a.y[t] = *reinterpret_cast<const u32x4*>(p.y + (long long)(a.row[t] >= 0 ? a.row[t] : safe_row) * p.ldy + n_ld);
+        a.y[t] = *reinterpret_cast<const u32x4*>(q.y + (long long)(a.row[t] >= 0 ? a.row[t] : safe_row) * q.ldy + n_ld);
     return a;
 }
 
 // long unit `id`: large ones first so that a launch ends evenly: the even chunks of the segments with more
-// than `per` rows, the segments with per/2 to per rows, the smaller ones
+// than `per` rows, the segments with per/2 to per rows, the smaller ones; within a class ids count through the
+// row chunks, and for each chunk through the column groups of every projection
 __device__ __forceinline__ bool find_long_unit(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e, int id,
                                                Unit& u, SegInfo& s, int& nb_begin, int& nb_end)
 {
     const int cid = id < e.n_full ? id : id < e.n_big ? id - e.n_full : id - e.n_big;
-    const int chunk = small_div(cid, e.groups);
-    nb_begin = (cid - chunk * e.groups) * e.per_group;
-    nb_end = min(e.long_blocks, nb_begin + e.per_group);
+    const int chunk = small_div(cid, e.sum_groups);
+    int g = cid - chunk * e.sum_groups;
+    u.pi = range_of(e.groups, p.n_proj, g);
+    const int per_group = pick(e.per_group, u.pi);
+    nb_begin = g * per_group;
+    nb_end = min(pick(e.long_blocks, u.pi), nb_begin + per_group);
     return id < e.n_full ? find_unit(p, sg, e.cf, chunk, e.per, e.full, u, s)
            : id < e.n_big ? find_unit(p, sg, e.cb, chunk, e.per, e.big, u, s)
                           : find_unit(p, sg, e.cl, chunk, e.per, e.little, u, s);
@@ -1135,11 +1192,12 @@ __device__ __forceinline__ LongAhead<KSTEPS, PAIRS> long_request(const FwdParams
     a.u.it = 0;
     a.live = find_long_unit(p, sg, e, (int)blockIdx.x, a.u, a.s, a.nb_begin, a.nb_end);
     if (!a.live) return a;
+    const int d_out = p.proj[a.u.pi].d_out;
 #pragma unroll
     for (int i = 0; i < STAGE; ++i) {
         const int id = (int)threadIdx.x + i * kThreads;
         const int j = id / (C::UN / 8), n = a.nb_begin * C::UN + (id % (C::UN / 8)) * 8;
-        a.b[i] = *(gconst_u32x4)(a.s.B + (long long)min(j, a.s.rank - 1) * p.d_out + min(n, p.d_out - 8));
+        a.b[i] = *(gconst_u32x4)(a.s.B + (long long)min(j, a.s.rank - 1) * d_out + min(n, d_out - 8));
     }
     a.row = (int)threadIdx.x < a.u.len ? row_of(p, a.u.pos + (int)threadIdx.x) : -1;
     return a;
@@ -1288,10 +1346,9 @@ int shrink_grid()
 // enough units for the launch to draw the full HBM rate and to end evenly: d_in is cut into slices (each
 // at least four stages long) as long as that leaves less than one row chunk x slice per workgroup (more
 // slices cost the expand kernel, which adds them up).  A pure function of host arguments.
-int choose_ksplit(int n_tokens, int seg_bound, int d_in, int grid)
+int choose_ksplit(int n_tokens, int n_proj, int d_in, int grid)
 {
-    (void)seg_bound;
-    const long long chunks = (n_tokens + kTallRows - 1) / kTallRows;
+    const long long chunks = (long long)((n_tokens + kTallRows - 1) / kTallRows) * n_proj;
     int ks = 1;
     while (ks < ksplit_cap(n_tokens) && chunks * ks * 2 < grid && d_in >= ks * 2 * 4 * kStageK) ks *= 2;
     return ks;
@@ -1341,20 +1398,20 @@ size_t h_slices_bytes(int n_tokens, int max_rank)
     return (size_t)ksplit_cap(n_tokens) * (size_t)n_tokens * (size_t)rstride_for(max_rank) * sizeof(float);
 }
 
-hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream_t st)
+hipError_t run_shrink_expand(FwdParams& p, int variant, hipStream_t st)
 {
     const int nt = nt_for(p.max_rank);
     hipError_t e = hipSuccess;
     if (variant == LQ_VARIANT_FUSED) {
         const int grid_f = nt == 1 ? fused_grid<1, 1, 2>() : nt == 2 ? fused_grid<2, 1, 2>()
                          : nt == 4 ? fused_grid<4, 2, 2>() : fused_grid<8, 4, 1>();
-        p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, seg_bound, p.d_in, grid_f);
+        p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, p.n_proj, p.d_in, grid_f);
         p.ks_log2 = log2_of(p.ksplit);
         return nt == 1 ? launch_fused<1, 1, 2>(p, st) : nt == 2 ? launch_fused<2, 1, 2>(p, st)
              : nt == 4 ? launch_fused<4, 2, 2>(p, st) : launch_fused<8, 4, 1>(p, st);
     }
     const int grid_s = nt == 1 ? shrink_grid<1>() : nt == 2 ? shrink_grid<2>() : nt == 4 ? shrink_grid<4>() : shrink_grid<8>();
-    p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, seg_bound, p.d_in, grid_s);
+    p.ksplit = p.ksplit_hint > 0 ? p.ksplit_hint : choose_ksplit(p.n_tokens, p.n_proj, p.d_in, grid_s);
     p.ks_log2 = log2_of(p.ksplit);
     if (variant != LQ_VARIANT_EXPAND_ONLY) {
         e = nt == 1 ? launch_shrink<1>(p, st) : nt == 2 ? launch_shrink<2>(p, st)
@@ -1392,63 +1449,81 @@ extern "C" size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_ran
 namespace lq {
 namespace {
 
-// Host-side checks and launch shared by the entry points below.  err_word: where the kernels report device-side
-// errors (NULL: word 0 of the workspace).
-lq_status forward_checked(const void* x, int64_t ldx, void* y, int64_t ldy, int32_t d_in, int32_t d_out,
-                          const void* const* A_ptrs, const void* const* B_ptrs, const int32_t* ranks, const float* scales,
-                          const float* token_scales, int32_t n_adapters, int32_t max_rank, const int32_t* perm, int32_t n_tokens,
+// Host-side checks and launch shared by the entry points below: n_proj linear layers that read the same x.
+// err_word: where the kernels report device-side errors (NULL: word 0 of the workspace).
+lq_status forward_checked(const void* x, int64_t ldx, int32_t d_in, int32_t n_proj, const Proj* projs,
+                          const int32_t* ranks, const float* scales, const float* token_scales,
+                          int32_t n_adapters, int32_t max_rank, const int32_t* perm, int32_t n_tokens,
                           const int32_t* seg_starts, const int32_t* seg_adapter, const uint8_t* seg_kind,
-                          const int32_t* n_segments, int32_t max_segments, float* h_out, const int64_t* h_offsets,
+                          const int32_t* n_segments, int32_t max_segments, const int64_t* h_offsets,
                           int32_t variant, void* workspace, size_t workspace_bytes, int32_t* err_word, hipStream_t stream,
                           bool launch)
 {
-    if (n_tokens < 0 || d_in <= 0 || d_out <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1)
-        return LQ_ERR_INVALID_ARG;
+    if (n_proj < 1 || n_proj > kMaxProj || !projs) return LQ_ERR_INVALID_ARG;
+    if (n_tokens < 0 || d_in <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1) return LQ_ERR_INVALID_ARG;
     if (variant < LQ_VARIANT_SPLIT || variant > LQ_VARIANT_EXPAND_ONLY) return LQ_ERR_INVALID_ARG;
-    if (!A_ptrs || !B_ptrs || !ranks || !scales || !seg_starts || !seg_adapter || !seg_kind || !n_segments)
-        return LQ_ERR_INVALID_ARG;
-    if (n_tokens > 0 && (!x || !y)) return LQ_ERR_INVALID_ARG;
-    if (ldx < d_in || ldy < d_out) return LQ_ERR_INVALID_ARG;
-    if (x && x == y) return LQ_ERR_INVALID_ARG;
+    if (!ranks || !scales || !seg_starts || !seg_adapter || !seg_kind || !n_segments) return LQ_ERR_INVALID_ARG;
+    if (n_tokens > 0 && !x) return LQ_ERR_INVALID_ARG;
+    if (ldx < d_in) return LQ_ERR_INVALID_ARG;
+    for (int k = 0; k < n_proj; ++k) {
+        const Proj& q = projs[k];
+        if (q.d_out <= 0 || !q.A_ptrs || !q.B_ptrs || q.ldy < q.d_out) return LQ_ERR_INVALID_ARG;
+        if (n_tokens > 0 && !q.y) return LQ_ERR_INVALID_ARG;
+        if (x && x == static_cast<const void*>(q.y)) return LQ_ERR_INVALID_ARG;
+        for (int j = 0; j < k; ++j)
+            if (q.y && q.y == projs[j].y) return LQ_ERR_INVALID_ARG;  // two layers cannot share their output
+    }
     if (max_rank > LQ_MAX_RANK || n_adapters > LQ_MAX_ADAPTERS) return LQ_ERR_UNSUPPORTED;
-    if ((d_in % 8) || (d_out % 8) || (ldx % 8) || (ldy % 8) || !aligned16(x) || !aligned16(y)) return LQ_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) ||
-        !aligned16(workspace))
-        return LQ_ERR_WORKSPACE;
+    if ((d_in % 8) || (ldx % 8) || !aligned16(x)) return LQ_ERR_UNSUPPORTED;
+    for (int k = 0; k < n_proj; ++k)
+        if ((projs[k].d_out % 8) || (projs[k].ldy % 8) || !aligned16(projs[k].y)) return LQ_ERR_UNSUPPORTED;
+    const size_t h_bytes = (size_t)n_proj * h_slices_bytes(n_tokens, max_rank);
+    if (!workspace || workspace_bytes < (size_t)kWsHeaderBytes + h_bytes || !aligned16(workspace)) return LQ_ERR_WORKSPACE;
     // the fused variant addresses the partial-h region through a buffer descriptor with 32-bit offsets
-    if (variant == LQ_VARIANT_FUSED && h_slices_bytes(n_tokens, max_rank) > 0x7fffffffull) return LQ_ERR_UNSUPPORTED;
+    if (variant == LQ_VARIANT_FUSED && h_bytes > 0x7fffffffull) return LQ_ERR_UNSUPPORTED;
     if (n_tokens == 0 || max_segments == 0 || !launch) return LQ_OK;
 
     FwdParams p;
     p.x = static_cast<const u16*>(x); p.ldx = ldx;
-    p.y = static_cast<u16*>(y); p.ldy = ldy;
-    p.d_in = d_in; p.d_out = d_out;
-    p.A_ptrs = A_ptrs; p.B_ptrs = B_ptrs; p.ranks = ranks; p.scales = scales;
+    p.d_in = d_in;
+    p.n_proj = n_proj;
+    for (int k = 0; k < kMaxProj; ++k) p.proj[k] = projs[k < n_proj ? k : 0];
+    p.ranks = ranks; p.scales = scales;
     p.n_adapters = n_adapters; p.max_rank = max_rank;
     p.token_scales = token_scales;
     p.perm = perm; p.n_tokens = n_tokens;
     p.seg_starts = seg_starts; p.seg_adapter = seg_adapter; p.seg_kind = seg_kind;
     p.n_segments = n_segments; p.max_segments = max_segments;
-    p.h_out = h_out; p.h_offsets = reinterpret_cast<const long long*>(h_offsets);
+    p.h_offsets = reinterpret_cast<const long long*>(h_offsets);
     p.rstride = rstride_for(max_rank);
     p.header = static_cast<int*>(workspace);
     p.err = err_word ? err_word : p.header;
     p.tickets = p.header + 4;
     p.hpart = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWsHeaderBytes);
-
-    int seg_bound = max_segments;
-    if (seg_bound > n_tokens) seg_bound = n_tokens;
-    if ((long long)seg_bound > 3LL * n_adapters) seg_bound = 3 * n_adapters;
-
+    p.hproj = (long long)(h_slices_bytes(n_tokens, max_rank) / sizeof(float));
     p.ksplit_hint = 0;
     p.kinds = kAllKinds;
     p.coherent = variant == LQ_VARIANT_FUSED;
-    p.hpart_bytes = (unsigned int)h_slices_bytes(n_tokens, max_rank);
-    return run_shrink_expand(p, variant, seg_bound, stream) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    p.hpart_bytes = (unsigned int)h_bytes;
+    return run_shrink_expand(p, variant, stream) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+}
+
+Proj one_projection(void* y, int64_t ldy, int32_t d_out, const void* const* A_ptrs, const void* const* B_ptrs, float* h_out)
+{
+    Proj q;
+    q.y = static_cast<u16*>(y); q.ldy = ldy; q.d_out = d_out;
+    q.A_ptrs = A_ptrs; q.B_ptrs = B_ptrs; q.h_out = h_out;
+    return q;
 }
 
 }  // namespace
 }  // namespace lq
+
+extern "C" size_t lora_forward_group_workspace_bytes(int32_t n_proj, int32_t n_tokens, int32_t max_rank)
+{
+    if (n_proj < 1 || n_tokens < 0 || max_rank < 1) return lq::kWsHeaderBytes;
+    return (size_t)lq::kWsHeaderBytes + (size_t)n_proj * lq::h_slices_bytes(n_tokens, max_rank);
+}
 
 extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y, int64_t ldy,
                                             int32_t d_in, int32_t d_out,
@@ -1462,8 +1537,33 @@ extern "C" lq_status lora_segmented_forward(const void* x, int64_t ldx, void* y,
                                             float* h_out, const int64_t* h_offsets,
                                             int32_t variant, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return lq::forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, token_scales, n_adapters, max_rank, perm, n_tokens,
-                               seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets, variant,
+    const lq::Proj q = lq::one_projection(y, ldy, d_out, A_ptrs, B_ptrs, h_offsets ? h_out : nullptr);
+    return lq::forward_checked(x, ldx, d_in, 1, &q, ranks, scales, token_scales, n_adapters, max_rank, perm, n_tokens,
+                               seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_offsets, variant,
+                               workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream), true);
+}
+
+extern "C" lq_status lora_segmented_forward_group(const void* x, int64_t ldx, int32_t d_in, int32_t n_proj,
+                                                  void* const* host_y, const int64_t* host_ldy, const int32_t* host_d_out,
+                                                  const void* const* const* host_A_ptrs,
+                                                  const void* const* const* host_B_ptrs, float* const* host_h_out,
+                                                  const int32_t* ranks, const float* scales, const float* token_scales,
+                                                  int32_t n_adapters, int32_t max_rank,
+                                                  const int32_t* perm, int32_t n_tokens,
+                                                  const int32_t* seg_starts, const int32_t* seg_adapter,
+                                                  const uint8_t* seg_kind,
+                                                  const int32_t* n_segments, int32_t max_segments,
+                                                  const int64_t* h_offsets,
+                                                  int32_t variant, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (n_proj < 1 || n_proj > LQ_MAX_GROUP) return LQ_ERR_INVALID_ARG;
+    if (!host_y || !host_ldy || !host_d_out || !host_A_ptrs || !host_B_ptrs) return LQ_ERR_INVALID_ARG;
+    lq::Proj projs[lq::kMaxProj];
+    for (int k = 0; k < n_proj; ++k)
+        projs[k] = lq::one_projection(host_y[k], host_ldy[k], host_d_out[k], host_A_ptrs[k], host_B_ptrs[k],
+                                      host_h_out && h_offsets ? host_h_out[k] : nullptr);
+    return lq::forward_checked(x, ldx, d_in, n_proj, projs, ranks, scales, token_scales, n_adapters, max_rank, perm, n_tokens,
+                               seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_offsets, variant,
                                workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream), true);
 }
 
@@ -1527,8 +1627,9 @@ extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, v
         return LQ_ERR_WORKSPACE;
     // host-side validation with a stand-in workspace address: nothing is launched, nothing is dereferenced
     void* const stand_in = reinterpret_cast<void*>(uintptr_t{256});
-    lq_status status = forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, token_scales, n_adapters, max_rank, perm,
-                                       n_tokens, seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets,
+    const Proj q = one_projection(y, ldy, d_out, A_ptrs, B_ptrs, h_offsets ? h_out : nullptr);
+    lq_status status = forward_checked(x, ldx, d_in, 1, &q, ranks, scales, token_scales, n_adapters, max_rank, perm,
+                                       n_tokens, seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_offsets,
                                        variant, stand_in, (size_t)LQ_STATIC_WORKSPACE_BYTES, error_word, nullptr, false);
     if (status != LQ_OK || n_tokens == 0 || max_segments == 0) return status;
     void* ws = scratch_of_current_device();
@@ -1536,7 +1637,7 @@ extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, v
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(clear_header_kernel, dim3(1), dim3(1024), 0, st, static_cast<int*>(ws));
     if (hipGetLastError() != hipSuccess) return LQ_ERR_HIP;
-    return forward_checked(x, ldx, y, ldy, d_in, d_out, A_ptrs, B_ptrs, ranks, scales, token_scales, n_adapters, max_rank, perm, n_tokens,
-                           seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_out, h_offsets, variant, ws,
+    return forward_checked(x, ldx, d_in, 1, &q, ranks, scales, token_scales, n_adapters, max_rank, perm, n_tokens,
+                           seg_starts, seg_adapter, seg_kind, n_segments, max_segments, h_offsets, variant, ws,
                            (size_t)LQ_STATIC_WORKSPACE_BYTES, error_word, st, true);
 }

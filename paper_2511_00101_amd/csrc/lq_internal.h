@@ -9,18 +9,27 @@ namespace lq {
 
 // Parameter block of the shrink / expand / fused kernels.  The backward pass reuses the same kernels
 // with the roles swapped (g = dy B^T is a shrink over d_out, dx += s g A is an expand over d_in).
+// One linear layer of a call.  A grouped call has several that read the same x (the Q, K, V projections of
+// Algorithm 1, the MLP's gate and up); the batch, its tables, the ranks and the scales are common to them.
+constexpr int kMaxProj = LQ_MAX_GROUP;
+struct Proj {
+    u16* y; long long ldy; int d_out;
+    const void* const* A_ptrs; const void* const* B_ptrs;
+    float* h_out;
+};
+
 struct FwdParams {
     const u16* x; long long ldx;
-    u16* y; long long ldy;
-    int d_in, d_out;
-    const void* const* A_ptrs; const void* const* B_ptrs;
+    int d_in;
+    int n_proj; Proj proj[kMaxProj];
     const int32_t* ranks; const float* scales; int n_adapters; int max_rank;
     const float* token_scales;  // per token row; when given it replaces scales[adapter] (null: per-adapter scales)
     const int32_t* perm; int n_tokens;
     const int32_t* seg_starts; const int32_t* seg_adapter; const uint8_t* seg_kind;
     const int32_t* n_segments; int max_segments;
-    float* h_out; const long long* h_offsets;
-    float* hpart;    // [ksplit][n_tokens][rstride] h of each slice of d_in by position in segment order (unscaled)
+    const long long* h_offsets;
+    float* hpart;    // [projection][ksplit][n_tokens][rstride] h of each slice of d_in by position in segment order (unscaled)
+    long long hproj; // elements of hpart per projection
     int ksplit;      // a power of two
     int ks_log2;
     int rstride;     // 32, 64 or 128
@@ -42,7 +51,7 @@ size_t h_slices_bytes(int n_tokens, int max_rank);   // bytes of the partial-h r
 
 // Fills p.ksplit and enqueues: variant LQ_VARIANT_SPLIT / _FUSED / _SHRINK_ONLY / _EXPAND_ONLY.
 // p.ksplit_hint > 0 forces that split (the expand half of a pair must use the shrink half's value).
-hipError_t run_shrink_expand(FwdParams& p, int variant, int seg_bound, hipStream_t stream);
+hipError_t run_shrink_expand(FwdParams& p, int variant, hipStream_t stream);
 
 // ---- device-wide barrier of a launch whose workgroups are all resident (grid = occupancy x compute units) ----
 // Data that crosses it must be written and read with device-scope accesses (the XCDs' L2 caches are not

@@ -7,7 +7,8 @@
 // plan buffer or extra launch is needed and the grid can be a fixed number of resident workgroups.
 //
 // P is a kernel parameter block with the members seg_starts, seg_adapter, seg_kind, n_segments,
-// max_segments, n_adapters, max_rank, ranks, scales, A_ptrs, B_ptrs, perm, n_tokens, err.
+// max_segments, n_adapters, max_rank, ranks, scales, perm, n_tokens, err (and, for the adapter lookups,
+// proj[].A_ptrs / B_ptrs).
 #pragma once
 
 #include "lq_common.h"
@@ -64,7 +65,7 @@ __device__ __forceinline__ SegLane seg_batch(const P& p, int n_seg, const SegCac
     return load_seg_lane(p, n_seg, s0 + lane_id());
 }
 
-struct Unit { int seg, pos, len, first, seg_len, ad, kd, it; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len); it: loop count (tracing)
+struct Unit { int seg, pos, len, first, seg_len, ad, kd, it, pi; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len); it: loop count (tracing); pi: projection of a grouped call (set by the caller of the lookup)
 
 // A class of chunks: those of the segments with lo <= rows < hi whose kind's bit is set in `kinds`.  A
 // segment is cut into ceil(rows / per) chunks; with `even` set they all get ceil(rows / chunks) rows
@@ -152,8 +153,8 @@ __device__ __forceinline__ SegInfo load_adapter(const P& p, const Unit& u)
     if (s.ok) {
         s.rank = p.ranks[u.ad];
         s.scale = p.scales[u.ad];
-        s.A = (gconst_u16)(p.A_ptrs[u.ad]);
-        s.B = (gconst_u16)(p.B_ptrs[u.ad]);
+        s.A = (gconst_u16)(p.proj[u.pi].A_ptrs[u.ad]);
+        s.B = (gconst_u16)(p.proj[u.pi].B_ptrs[u.ad]);
         s.ok = s.rank >= 1 && s.rank <= p.max_rank && s.A && s.B;
     }
     if (!s.ok && threadIdx.x == 0) atomicOr(p.err, kErrBadSegment);
@@ -192,8 +193,8 @@ __device__ __forceinline__ Segs<P> load_segs(const P& p)
 #pragma unroll
     for (int b = 0; b < kCachedBatches; ++b) {
         const int ad = min(b * kWave + lane_id(), p.n_adapters - 1);
-        const unsigned long long pa = reinterpret_cast<unsigned long long>(p.A_ptrs[ad]);
-        const unsigned long long pb = reinterpret_cast<unsigned long long>(p.B_ptrs[ad]);
+        const unsigned long long pa = reinterpret_cast<unsigned long long>(p.proj[0].A_ptrs[ad]);
+        const unsigned long long pb = reinterpret_cast<unsigned long long>(p.proj[0].B_ptrs[ad]);
         sg.a[b].a_lo = (unsigned int)pa; sg.a[b].a_hi = (unsigned int)(pa >> 32);
         sg.a[b].b_lo = (unsigned int)pb; sg.a[b].b_hi = (unsigned int)(pb >> 32);
         sg.a[b].rank = p.ranks[ad];
@@ -209,11 +210,11 @@ __device__ __forceinline__ Segs<P> load_segs(const P& p)
     return sg;
 }
 
-// the adapter of a unit: from the registers if it is one of the first 128, else loaded
+// the adapter of a unit: from the registers if it is one of the first 128 (of the call's first projection), else loaded
 template <class P>
 __device__ __forceinline__ SegInfo cached_adapter(const P& p, const Segs<P>& sg, const Unit& u)
 {
-    if (u.ad < 0 || u.ad >= kCachedBatches * kWave) return load_adapter(p, u);
+    if (u.pi != 0 || u.ad < 0 || u.ad >= kCachedBatches * kWave) return load_adapter(p, u);
     const bool hi = u.ad >= kWave;  // wave uniform
     const int l = u.ad & (kWave - 1);
     const AdLane& a = hi ? sg.a[1] : sg.a[0];

@@ -107,3 +107,43 @@ def long_batch_problem(seed, with_dy, y0_zero=False):
     ranks = rng.choice([8, 16, 32], size=n_ad)
     return synth.make_problem("long_batch", synth.Batch(ta[order], tk[order]), 512, 384, ranks, rng.uniform(0.5, 1.5, n_ad),
                               seed + 1, with_dy=with_dy, w_std=0.03, y0_zero=y0_zero)
+
+
+def group_of(base: synth.Problem, d_outs, seed):
+    """Linear layers that read base.x over base.batch (a grouped call's projections): the first is `base`, the others
+    get their own A, B and y0 (own seeds) and their own d_out; ranks and scales are base's."""
+    out = [base]
+    for k, d_out in enumerate(d_outs):
+        q = synth.make_problem(f"{base.name}_proj{k + 1}", base.batch, base.d_in, d_out, base.ranks, base.scales, seed + k,
+                               w_std=0.03)
+        q.x = base.x
+        out.append(q)
+    return out
+
+
+def check_forward_group(oracle_mod, problems, variant, token_scales=None):
+    """The grouped call on `problems` (same x, same batch) against the oracle's result for every layer on its own."""
+    base = problems[0]
+    dev = "cuda"
+    d = DeviceProblem(base)
+    d.build()
+    refs = [oracle_mod.forward(q.x, q.y0, q.A, q.B, q.ranks, q.scales, q.batch.token_adapter, q.batch.token_kind,
+                               token_scales=token_scales) for q in problems]
+    assert_tables_equal(d.seg.to_host(), refs[0].segments)
+    ys = [lq.bf16_from_bits(q.y0, dev) for q in problems]
+    ads = [lq.AdapterTable.from_tensors([lq.bf16_from_bits(a, dev) for a in q.A], [lq.bf16_from_bits(b, dev) for b in q.B],
+                                        q.scales, dev) for q in problems]
+    h_elems = refs[0].segments.h_elems
+    hs = [torch.full((max(h_elems, 1),), float("nan"), dtype=torch.float32, device=dev) for _ in problems]
+    ws = lq.workspace(lq.lora_forward_group_workspace_bytes(len(problems), base.n_tokens, ads[0].max_rank), dev)
+    ts = None if token_scales is None else torch.from_numpy(np.ascontiguousarray(token_scales, np.float32)).to(dev)
+    lq.lora_segmented_forward_group(d.x, ys, ads, d.seg, hs, ws, variant, token_scales=ts)
+    torch.cuda.synchronize()
+    assert int(ws[0].item() & 0xffffffff) == 0
+    live = np.zeros(base.n_tokens, bool)
+    live[refs[0].segments.perm] = True
+    for q, y, h, ref in zip(problems, ys, hs, refs):
+        y_bits = lq.bits_from_bf16(y)
+        assert_close(synth.bf16_bits_to_f64(y_bits), ref.y, f"{q.name} y")
+        assert_close(h[:h_elems].cpu().numpy(), ref.h, f"{q.name} h_out")
+        assert np.array_equal(y_bits[~live], q.y0[~live])

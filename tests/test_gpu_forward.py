@@ -6,7 +6,8 @@ import torch
 from paper_2511_00101_amd import binding as lq
 from paper_2511_00101_amd import synth
 
-from gpu_util import long_batch_problem, DeviceProblem, assert_close, assert_tables_equal, check_forward
+from gpu_util import (long_batch_problem, DeviceProblem, assert_close, assert_tables_equal, check_forward,
+                      check_forward_group, group_of)
 
 pytestmark = pytest.mark.gpu
 
@@ -211,6 +212,57 @@ def test_dynamic_per_token_scale(oracle_mod, variant, y0_zero):
               synth.config2(y0_zero=y0_zero), synth.config3(y0_zero=y0_zero)):
         p.scales = np.full_like(p.scales, 1000.0)       # must be ignored
         check_forward(oracle_mod, p, variant, token_scales=request_scales(p, 7))
+
+
+# ---------------------------------------------------------------------------------------------------
+# grouped call: several linear layers that read the same x (Algorithm 1: Q, K, V from one X)
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("n_proj", [1, 2, 3, 4])
+def test_group_small_mixed(oracle_mod, variant, n_proj):
+    """Ragged shapes, ranks 3..128, rows without adapter; every layer of the group against the oracle's result for
+    that layer alone; also with the dynamic per-token scale."""
+    base = synth.small_mixed(71, 300, 1032, 776, [16, 128, 5, 24, 33], drop_frac=0.1, w_std=0.03)
+    group = group_of(base, [264, 1544, 8][: n_proj - 1], 700)
+    check_forward_group(oracle_mod, group, variant)
+    if n_proj == 3:
+        check_forward_group(oracle_mod, group, variant, token_scales=request_scales(base, 11))
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_group_unified_batch(oracle_mod, variant):
+    """Long fine-tune segments with a k split, prefill and decode segments, saved h per layer."""
+    base = synth.config3()
+    check_forward_group(oracle_mod, group_of(base, [1024, 2048], 800), variant)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("which", ["qkv", "gate_up"])
+def test_group_layer_stack_shapes(oracle_mod, variant, which):
+    """The two groups of the layer stack at full size: q, k, v (4096 -> 4096, 1024, 1024) and gate, up (4096 -> 14336)."""
+    if which == "qkv":
+        group = group_of(synth.config5(3, 0, with_dy=False), [1024, 1024], 900)
+    else:
+        group = group_of(synth.config5(3, 4, with_dy=False), [14336], 910)
+    check_forward_group(oracle_mod, group, variant)
+
+
+def test_group_rejects_bad_arguments():
+    p = synth.config1()
+    d = DeviceProblem(p)
+    d.build()
+    ws = lq.workspace(lq.lora_forward_group_workspace_bytes(2, p.n_tokens, 8))
+    y2 = d.y.clone()
+    with pytest.raises(lq.LqError) as e:
+        lq.lora_segmented_forward_group(d.x, [d.y, d.y], [d.adapters, d.adapters], d.seg, None, ws)     # the same y twice
+    assert e.value.status == lq.LQ_ERR_INVALID_ARG
+    small = lq.workspace(lq.lora_forward_group_workspace_bytes(1, p.n_tokens, 8))
+    if small.numel() < ws.numel():
+        with pytest.raises(lq.LqError) as e:
+            lq.lora_segmented_forward_group(d.x, [d.y, y2], [d.adapters, d.adapters], d.seg, None, small)
+        assert e.value.status == lq.LQ_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert np.array_equal(lq.bits_from_bf16(d.y), p.y0)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
