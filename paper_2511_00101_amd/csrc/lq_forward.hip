@@ -123,7 +123,7 @@ __device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const
 {
     HDest d;
     d.base = p.hpart + u.pi * p.hproj + ((long long)ks * p.n_tokens + u.pos) * p.rstride;
-    float* h_out = p.proj[u.pi].h_out;
+    float* h_out = proj_of(p, u.pi).h_out;
     const bool save = nsplit == 1 && u.kd == LQ_SEG_FINETUNE && h_out && p.h_offsets;
     d.save = save ? h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
     d.save_ld = s.rank;
@@ -510,7 +510,7 @@ __device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit&
     using C = ExpandCfg<KSTEPS, PAIRS>;
     constexpr int STAGE = C::ROWS * (C::UN / 8) / kThreads;  // 16-byte pieces of the B block per thread
     static_assert(C::ROWS * (C::UN / 8) % kThreads == 0, "staging loop assumes an even split");
-    const Proj pj = p.proj[u.pi];  // this unit's linear layer: y, d_out (B comes with s)
+    const Proj pj = proj_of(p, u.pi);  // this unit's linear layer: y, d_out (B comes with s)
     u16* lds_b = reinterpret_cast<u16*>(lds);
     u32x4* lds_h = reinterpret_cast<u32x4*>(lds + C::B_BYTES);
     int* lds_row = reinterpret_cast<int*>(lds + C::B_BYTES + C::H_BYTES);
@@ -836,7 +836,7 @@ __device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit
 {
     constexpr int JG = kShortGroup;
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
-    const Proj pj = p.proj[u.pi];  // this unit's linear layer: y, d_out (B comes with s)
+    const Proj pj = proj_of(p, u.pi);  // this unit's linear layer: y, d_out (B comes with s)
     float* hs = &sh.hs[w][0][0];  // hs[j][t] at j * kTT + t
     const int parts = p.ksplit;
     const bool save = u.kd == LQ_SEG_FINETUNE && pj.h_out && p.h_offsets && n_block == 0 && parts > 1;
@@ -1147,7 +1147,7 @@ __device__ __forceinline__ ShortAhead short_request(const FwdParams& p, const Se
     a.u.it = 4;
     a.live = find_short_unit(p, sg, e, id, a.u, a.s, a.n_block);
     if (!a.live) return a;
-    const Proj q = p.proj[a.u.pi];
+    const Proj q = proj_of(p, a.u.pi);
     const int n_ld = min(a.n_block * kShortN + lane_id() * 8, q.d_out - 8);
 #pragma unroll
     for (int t = 0; t < kTT; ++t) a.row[t] = t < a.u.len ? row_of(p, a.u.pos + t) : -1;
@@ -1192,7 +1192,7 @@ __device__ __forceinline__ LongAhead<KSTEPS, PAIRS> long_request(const FwdParams
     a.u.it = 0;
     a.live = find_long_unit(p, sg, e, (int)blockIdx.x, a.u, a.s, a.nb_begin, a.nb_end);
     if (!a.live) return a;
-    const int d_out = p.proj[a.u.pi].d_out;
+    const int d_out = proj_of(p, a.u.pi).d_out;
 #pragma unroll
     for (int i = 0; i < STAGE; ++i) {
         const int id = (int)threadIdx.x + i * kThreads;

@@ -42,6 +42,24 @@ struct FwdParams {
     int* tickets;    // workspace header words 4..: unit tickets ([0,1] shrink phase, [2,3] expand phase); the barrier's words: kBar*
 };
 
+// projection pi of a call (pi wave uniform).  Every member is picked by value: a run-time index into the kernel's
+// parameter block (or a choice between references into it) would make the compiler keep a copy of the whole block
+// in scratch memory.
+__device__ __forceinline__ Proj proj_of(const FwdParams& p, int pi)
+{
+    static_assert(kMaxProj == 4, "the entries are picked by name");
+#define LQ_PICK(member) (pi == 0 ? p.proj[0].member : pi == 1 ? p.proj[1].member : pi == 2 ? p.proj[2].member : p.proj[3].member)
+    Proj q;
+    { u16* const v = LQ_PICK(y); q.y = v; }
+    { const long long v = LQ_PICK(ldy); q.ldy = v; }
+    { const int v = LQ_PICK(d_out); q.d_out = v; }
+    { const void* const* const v = LQ_PICK(A_ptrs); q.A_ptrs = v; }
+    { const void* const* const v = LQ_PICK(B_ptrs); q.B_ptrs = v; }
+    { float* const v = LQ_PICK(h_out); q.h_out = v; }
+#undef LQ_PICK
+    return q;
+}
+
 constexpr int kAllKinds = 7;
 constexpr int kFinetuneOnly = 1 << LQ_SEG_FINETUNE;
 

@@ -153,8 +153,9 @@ __device__ __forceinline__ SegInfo load_adapter(const P& p, const Unit& u)
     if (s.ok) {
         s.rank = p.ranks[u.ad];
         s.scale = p.scales[u.ad];
-        s.A = (gconst_u16)(p.proj[u.pi].A_ptrs[u.ad]);
-        s.B = (gconst_u16)(p.proj[u.pi].B_ptrs[u.ad]);
+        const auto pj = proj_of(p, u.pi);
+        s.A = (gconst_u16)(pj.A_ptrs[u.ad]);
+        s.B = (gconst_u16)(pj.B_ptrs[u.ad]);
         s.ok = s.rank >= 1 && s.rank <= p.max_rank && s.A && s.B;
     }
     if (!s.ok && threadIdx.x == 0) atomicOr(p.err, kErrBadSegment);
