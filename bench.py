@@ -2,9 +2,10 @@
 """Benchmark of the segmented multi-LoRA hot path on one MI355X.
 
 Headline (`value`, `roofline`, `cpu_baseline`): the forward of the 8B-shaped 32-layer stack, the largest
-configuration (benchmark configs[4]): a step = segment-metadata builder + the 224 forward calls (7 LoRA
-projections x 32 layers; shrink, h-save, expand in one launch each) over one mixed batch of 5632 tokens; `value`
-= tokens of the batch / step time.  `configs` carries the single-call workloads (a step = builder + forward,
+configuration (benchmark configs[4]): a step = segment-metadata builder + the forward of the 224 LoRA linears
+(7 projections x 32 layers; shrink, h-save, expand in one launch per call; q, k, v and gate, up as grouped calls
+that read their common x once, so 4 launches per layer) over one mixed batch of 5632 tokens; `value` = tokens of
+the batch / step time.  `configs` carries the single-call workloads (a step = builder + forward,
 operands rotated over > 1 GiB of replicas) and the layer stack's backward.  Inputs are synthetic, resident in HBM
 before the timed region, and no two calls share an operand, so that nothing the accounting counts is served from L2
 or the Infinity Cache.
@@ -102,7 +103,8 @@ class Replicas:
 
 PROFILE_FILES = dict(cfg2_decode_heavy="forward_cfg2_decode_heavy.txt", cfg3_unified="forward_cfg3_unified.txt",
                      cfg4_mlp_up="forward_cfg4_mlp_up.txt", cfg4_mlp_down="forward_cfg4_mlp_down.txt",
-                     cfg5_layer_stack="forward_cfg5_layer_stack.txt")
+                     cfg5_layer_stack="forward_cfg5_layer_stack.txt",
+                     cfg5_layer_stack_single_calls="forward_cfg5_layer_stack_single_calls.txt")
 
 
 def traffic_source(workload):
@@ -162,19 +164,22 @@ LAYER_STACK_NAME = "cfg5_layer_stack"
 
 
 class LayerStack:
-    """The 8B-shaped 32-layer stack (benchmark configs[4]): 7 LoRA projections per layer with their own
-    adapter weights, one batch structure for all 224 calls.  Every call has its OWN x, y (and dx) tensor, so no
-    byte that the accounting counts can come from the Infinity Cache left there by a neighbouring call (in a
-    real layer q, k, v and gate, up read the same x: that sharing is not exploited and not counted here).
+    """The 8B-shaped 32-layer stack (benchmark configs[4]): 7 LoRA linears per layer with their own adapter
+    weights, one batch structure for all 224.  grouped: q, k, v read one x and gate, up read one x, as in a real
+    decoder layer (Algorithm 1), and each such group is one lora_segmented_forward_group call; x is then counted
+    once per group.  Not grouped: one call per linear, and every call has its OWN x.  Either way no two launches share an
+    operand, so no byte that the accounting counts can come from the Infinity Cache left there by a neighbouring launch.
     Activations and weights are drawn on the GPU with torch's generator (same distributions as the seeded
-    generators; the parity tests run the seeded ones on sampled calls, this loop is timed, not checked)."""
+    generators; the parity tests run the seeded ones on sampled calls and groups, this loop is timed, not checked)."""
 
-    def __init__(self, variant, with_backward, n_layers=None):
+    GROUPS = ((0, 1, 2), (3,), (4, 5), (6,))   # q+k+v read one x, o its own, gate+up one x, down its own (Algorithm 1; the MLP)
+
+    def __init__(self, variant, with_backward, grouped=True, n_layers=None):
         import numpy as np
         import torch
         from paper_2511_00101_amd import binding as lq
         from paper_2511_00101_amd import synth
-        self.lq, self.torch, self.variant, self.with_backward = lq, torch, variant, with_backward
+        self.lq, self.torch, self.variant, self.with_backward, self.grouped = lq, torch, variant, with_backward, grouped
         self.n_layers = n_layers or synth.N_LAYERS
         dev = "cuda"
         b = synth.config5_batch()
@@ -196,11 +201,16 @@ class LayerStack:
         self.calls = []
         max_ws = 0
         for layer in range(self.n_layers):
+            shared_x = {}
             for pi, (name, d_in, d_out) in enumerate(synth.LAYER_PROJECTIONS):
                 A = [(torch.randn(r, d_in, generator=gen, device=dev) * 0.02).to(bf) for _ in range(n_ad)]
                 B = [(torch.randn(r, d_out, generator=gen, device=dev) * 0.02).to(bf) for _ in range(n_ad)]
                 ad = lq.AdapterTable.from_tensors(A, B, [2.0] * n_ad, dev)
-                c = dict(name=name, x=act(d_in), y=act(d_out), ad=ad, d_in=d_in, d_out=d_out,  # y: y0; later it doubles as dy
+                # grouped: the projections of a group read the group's x; else every call has its own
+                gi = [g for g in self.GROUPS if pi in g][0]
+                if not grouped or gi not in shared_x:
+                    shared_x[gi] = act(d_in)
+                c = dict(name=name, x=shared_x[gi], y=act(d_out), ad=ad, d_in=d_in, d_out=d_out,  # y: y0; later it doubles as dy
                          h_out=torch.zeros(4096 * r, dtype=torch.float32, device=dev))
                 if with_backward:
                     c["dx"] = act(d_in)
@@ -210,11 +220,20 @@ class LayerStack:
                     c["dB_ptrs"] = torch.tensor([t.data_ptr() if t is not None else 0 for t in c["dB"]], dtype=torch.int64, device=dev)
                 self.calls.append(c)
                 max_ws = max(max_ws, lq.lora_workspace_bytes(T, n_ad, r, d_in, d_out) if with_backward
-                             else lq.lora_forward_workspace_bytes(T, r, d_in, d_out, variant))
+                             else lq.lora_forward_workspace_bytes(T, r, d_in, d_out, variant),
+                             lq.lora_forward_group_workspace_bytes(lq.LQ_MAX_GROUP, T, r))
         self.ws = lq.workspace(max_ws, dev)
         self.ranks = self.calls[0]["ad"].ranks
         self.build = lq.prepare_build_segments(self.ta, self.tk, self.ranks, self.seg, self.bws)
-        self.fwd = [lq.prepare_forward(c["x"], c["y"], c["ad"], self.seg, c["h_out"], self.ws, variant) for c in self.calls]
+        if grouped:
+            self.fwd = []
+            for base in range(0, len(self.calls), len(synth.LAYER_PROJECTIONS)):
+                for g in self.GROUPS:
+                    cs = [self.calls[base + pi] for pi in g]
+                    self.fwd.append(lq.prepare_forward_group(cs[0]["x"], [c["y"] for c in cs], [c["ad"] for c in cs], self.seg,
+                                                             [c["h_out"] for c in cs], self.ws, variant))
+        else:
+            self.fwd = [lq.prepare_forward(c["x"], c["y"], c["ad"], self.seg, c["h_out"], self.ws, variant) for c in self.calls]
         self.build()
         torch.cuda.synchronize()
 
@@ -224,15 +243,19 @@ class LayerStack:
         n_live, n_ft = b.n_tokens, int((b.token_kind == 0).sum())
         r, used, used_ft = self.rank, self.n_adapters, 2
         fwd_b = bwd_b = fwd_f = bwd_f = 0
+        seen_x = set()
         for c in self.calls:
             di, do = c["d_in"], c["d_out"]
-            fwd_b += n_live * di * 2 + n_live * do * 4 + used * r * (di + do) * 2 + n_ft * r * 4
+            # (x is counted once per tensor: the projections of a grouped call read it together)
+            fwd_b += (0 if c["x"].data_ptr() in seen_x else n_live * di * 2) + n_live * do * 4 + used * r * (di + do) * 2 + n_ft * r * 4
+            seen_x.add(c["x"].data_ptr())
             fwd_f += 2 * r * (di + do) * n_live
             # backward: dy and x of the fine-tune rows read once, dx read + written, A and B of the fine-tune adapters,
             # dA and dB read + written, the saved h read
             bwd_b += n_ft * do * 2 + n_ft * di * 2 + n_ft * di * 4 + used_ft * r * (di + do) * 2 + used_ft * r * (di + do) * 8 + n_ft * r * 4
             bwd_f += 2 * r * (di + do) * n_ft * 2
-        return dict(fwd_bytes=fwd_b, bwd_bytes=bwd_b, fwd_flops=fwd_f, bwd_flops=bwd_f, tokens=n_live, calls=len(self.calls))
+        return dict(fwd_bytes=fwd_b, bwd_bytes=bwd_b, fwd_flops=fwd_f, bwd_flops=bwd_f, tokens=n_live, calls=len(self.calls),
+                    launches=len(self.fwd))
 
     def step(self, i=0):
         """Headline step: the segment builder once (all calls share the batch structure), then every call's forward."""
@@ -278,36 +301,38 @@ def profiled(lq, torch, run):
     return {name: dict(avg_us=total / n, launches=n) for name, (total, n) in prof.items() if n}
 
 
-def measure_layer_stack(variant, steps, warmup, with_backward):
-    """Headline: builder + the 224 forward calls.  With `with_backward`, the backward of the fine-tune rows of all
-    calls is measured as well (its own entry)."""
+def measure_layer_stack(variant, steps, warmup, with_backward, grouped=True):
+    """Headline: builder + the forward of the 224 linear layers.  grouped: the projections that read the same x
+    (q, k, v; gate, up) go through lora_segmented_forward_group, 4 launches per decoder layer; else 7 single calls.
+    With `with_backward`, the backward of the fine-tune rows of all calls is measured as well (its own entry)."""
     import torch
-    st = LayerStack(variant, with_backward)
+    st = LayerStack(variant, with_backward, grouped)
     w = st.work()
     s_per_step, per_step = timed_steps(torch, st.step, steps, warmup)
     kern = profiled(st.lq, torch, lambda: [st.step(i) for i in range(max(1, min(steps, 3)))])
     dom = "forward_fused" if "forward_fused" in kern else "expand"
     n_steps_prof = max(1, min(steps, 3))
     fwd_us = sum(k["avg_us"] * k["launches"] for name, k in kern.items() if name != "build") / n_steps_prof   # per step
-    per_launch = w["fwd_bytes"] / w["calls"]
+    per_launch = w["fwd_bytes"] / w["launches"]
     if dom == "forward_fused":
         dom_bytes = per_launch
     else:   # two launches: the expand kernel carries y, B and the saved h
         n_ft = int((st.batch.token_kind == 0).sum())
-        dom_bytes = sum(st.T * c["d_out"] * 4 + st.n_adapters * st.rank * c["d_out"] * 2 + n_ft * st.rank * 4 for c in st.calls) / w["calls"]
+        dom_bytes = sum(st.T * c["d_out"] * 4 + st.n_adapters * st.rank * c["d_out"] * 2 + n_ft * st.rank * 4 for c in st.calls) / w["launches"]
     dom_gbps = dom_bytes / (kern[dom]["avg_us"] * 1e-6) / 1e9
-    traffic = counter_traffic(LAYER_STACK_NAME, dom)
+    name = LAYER_STACK_NAME if grouped else LAYER_STACK_NAME + "_single_calls"
+    traffic = counter_traffic(name, dom)
     head = dict(
-        workload=LAYER_STACK_NAME, tokens=w["tokens"], calls=w["calls"], ms_per_step=s_per_step * 1e3, per_step=per_step,
+        workload=name, tokens=w["tokens"], calls=w["calls"], launches=w["launches"], ms_per_step=s_per_step * 1e3, per_step=per_step,
         tokens_per_s=w["tokens"] / s_per_step, forward_us=fwd_us,
         forward_gbps=w["fwd_bytes"] / (fwd_us * 1e-6) / 1e9, forward_tflops=w["fwd_flops"] / (fwd_us * 1e-6) / 1e12,
         forward_hbm_frac=w["fwd_bytes"] / (fwd_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
         forward_mfma_frac=w["fwd_flops"] / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         algorithmic_bytes=w["fwd_bytes"], flops=w["fwd_flops"], kernels=kern,
         roofline=dict(bound="hbm", kernel=dom, achieved=dom_gbps, peak=HBM_PEAK_GBPS, unit="GB/s", frac=dom_gbps / HBM_PEAK_GBPS,
-                      traffic=traffic, traffic_source=traffic_source(LAYER_STACK_NAME) if traffic else None,
+                      traffic=traffic, traffic_source=traffic_source(name) if traffic else None,
                       algorithmic_bytes=dom_bytes, avg_launch_us=kern[dom]["avg_us"],
-                      note="average over the step's 224 launches of 4 shapes: bytes and duration are both per launch"),
+                      note=f"average over the step's {w['launches']} launches of 4 shapes: bytes and duration are both per launch"),
         error_word=st.error_word())
     bwd = None
     if with_backward:
@@ -389,8 +414,11 @@ def main():
     ap.add_argument("--workload", default="cfg5",
                     help="headline workload: cfg5 (the 32-layer stack's forward, the largest configuration), or one of the "
                          "single-call ones cfg1, cfg2, cfg3, cfg4up, cfg4down")
-    ap.add_argument("--others", default="cfg2,cfg3,cfg4up,cfg4down,cfg5bwd",
-                    help="comma list of further workloads for the `configs` list ('' = none); cfg5bwd: the layer stack's backward")
+    ap.add_argument("--others", default="cfg2,cfg3,cfg4up,cfg4down,cfg5single,cfg5bwd",
+                    help="comma list of further workloads for the `configs` list ('' = none); cfg5single: the layer stack as 224 "
+                         "single calls; cfg5bwd: the layer stack's backward")
+    ap.add_argument("--single-calls", action="store_true",
+                    help="headline cfg5 with one call per linear layer (224 launches) instead of grouped calls (128 launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of known size (256 MiB read + 256 MiB written, 8 times) so that "
@@ -426,14 +454,18 @@ def main():
 
     others = []
     if args.workload == "cfg5":
-        head, bwd = measure_layer_stack(variant, args.steps, args.warmup, with_backward="cfg5bwd" in other_names)
+        head, bwd = measure_layer_stack(variant, args.steps, args.warmup, with_backward="cfg5bwd" in other_names,
+                                        grouped=not args.single_calls)
         cpu = None if args.no_cpu_baseline else layer_stack_cpu_baseline()
-        workload = (f"{head['workload']} forward: 32 layers x 7 projections = {head['calls']} calls (q,o 4096->4096; k,v 4096->1024; "
+        workload = (f"{head['workload']} forward: 32 layers x 7 LoRA linears = {head['calls']} (q,o 4096->4096; k,v 4096->1024; "
                     f"gate,up 4096->14336; down 14336->4096), {head['tokens']} tokens (4096 fine-tune + 1024 prefill + 512 decode), "
                     f"16 adapters rank 32")
-        step = f"segment builder + {head['calls']} forward calls (the calls share the batch structure, so the tables are built once)"
-        extra = dict(calls=head["calls"], inputs="drawn on the GPU by torch's generator, every call with its own x, y and weights; "
-                                                 "timed, not checked (the parity tests check sampled calls with the seeded generators)")
+        step = (f"segment builder + the forward of the {head['calls']} linears in {head['launches']} launches "
+                + ("(q,k,v and gate,up as grouped calls that read their x once; o and down single)" if not args.single_calls
+                   else "(one call per linear)") + "; the calls share the batch structure, so the tables are built once")
+        extra = dict(calls=head["calls"], launches=head["launches"],
+                     inputs="drawn on the GPU by torch's generator, every call (group) with its own x, y and weights; "
+                            "timed, not checked (the parity tests check sampled calls and groups with the seeded generators)")
         if bwd:
             others.append(bwd)
     else:
@@ -445,8 +477,10 @@ def main():
         extra = dict(replicas=head["replicas"], timed_steps=head["steps"])
         del p
     for name in other_names:
-        if name in ("cfg5bwd", "cfg5"):
-            if name == "cfg5" or args.workload != "cfg5":
+        if name in ("cfg5bwd", "cfg5", "cfg5single"):
+            if name == "cfg5single":
+                others.append(measure_layer_stack(variant, 5, 1, with_backward=False, grouped=False)[0])
+            elif name == "cfg5" or args.workload != "cfg5":
                 h5, b5 = measure_layer_stack(variant, 3, 1, with_backward=name == "cfg5bwd")
                 others.append(b5 if name == "cfg5bwd" else h5)
             continue

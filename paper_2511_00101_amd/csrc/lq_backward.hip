@@ -376,7 +376,8 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     const bool want_w = dA_ptrs || dB_ptrs;
     q.h_out = want_w ? gsum : nullptr; s1.h_offsets = want_w ? reinterpret_cast<const long long*>(h_offsets) : nullptr;
     s1.n_proj = 1;
-    for (int k = 0; k < kMaxProj; ++k) s1.proj[k] = q;
+    s1.proj0 = q;
+    for (int k = 1; k < kMaxProj; ++k) s1.more[k - 1] = q;
     s1.hpart = reinterpret_cast<float*>(ws + kWsHeaderBytes);
     s1.hproj = 0;
     s1.ksplit = 1; s1.rstride = rstride_for(max_rank);

@@ -27,6 +27,7 @@
 // row-contiguous pattern as long as nothing else competes for the address path, which is why A_a, B_a
 // and h reach the MFMA through LDS instead.
 #include "lq_internal.h"
+#include <algorithm>
 #include <mutex>
 #include <type_traits>
 
@@ -101,7 +102,8 @@ __device__ __forceinline__ float h_load(const float* ptr, bool coherent)
 }
 // eight consecutive floats of hpart (16-byte aligned).  The device-scope form is a buffer load with the sc1
 // cache policy: plain C++ has no 16-byte atomic load.
-__device__ __forceinline__ void h_load8(const FwdParams& p, const float* ptr, f32x4& a, f32x4& b)
+template <class PP>
+__device__ __forceinline__ void h_load8(const PP& p, const float* ptr, f32x4& a, f32x4& b)
 {
     if (!p.coherent) {
         a = *reinterpret_cast<const f32x4*>(ptr);
@@ -119,7 +121,8 @@ __device__ __forceinline__ void h_load8(const FwdParams& p, const float* ptr, f3
 // the finished h, and fine-tune segments store it to h_out as well; with ksplit > 1 the expand kernel
 // adds the slices in order (and stores h_out), so no workgroup ever waits for another.
 struct HDest { float* base; float* save; int save_ld; };
-__device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, int nsplit)
+template <class PP>
+__device__ __forceinline__ HDest h_dest(const PP& p, const Unit& u, const SegInfo& s, int ks, int nsplit)
 {
     HDest d;
     d.base = p.hpart + u.pi * p.hproj + ((long long)ks * p.n_tokens + u.pos) * p.rstride;
@@ -131,7 +134,8 @@ __device__ __forceinline__ HDest h_dest(const FwdParams& p, const Unit& u, const
 }
 
 // finished h of one element: the slices added in order
-__device__ __forceinline__ float h_sum(const FwdParams& p, int pi, long long pos, int j, int parts)
+template <class PP>
+__device__ __forceinline__ float h_sum(const PP& p, int pi, long long pos, int j, int parts)
 {
     // the first four slices are requested together (a slice that does not exist re-reads the last one and is
     // not added): one round trip instead of one per slice
@@ -156,8 +160,8 @@ __device__ __forceinline__ float h_sum(const FwdParams& p, int pi, long long pos
 // ROWWISE: x is loaded row-wise (an instruction covers 2 rows x 512 contiguous bytes, which streams from HBM
 // up to a quarter faster than the MFMA layout's 16 rows x 64 bytes when few units share a compute unit) and
 // reaches the MFMA layout through a slab of LDS that belongs to the wave (`slabs`: 8 x 16 rows).
-template <int NT, bool ROWWISE>  // 16-rank tiles: ranks up to 16 * NT
-__device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, u16* lds,
+template <int NT, bool ROWWISE, class PP>  // 16-rank tiles: ranks up to 16 * NT
+__device__ __forceinline__ void shrink_tall_unit(const PP& p, const Unit& u, const SegInfo& s, int ks, u16* lds,
                                                  u16* slabs)
 {
     constexpr int PITCH = kStageK + 8;           // elements per staged A row or slab row (16-byte aligned, bank spread)
@@ -312,8 +316,8 @@ __device__ __forceinline__ void shrink_tall_unit(const FwdParams& p, const Unit&
 // shrink, short unit: <= 32 rows; the 8 waves take alternate 64-wide k blocks (block b belongs to slice
 // (b / 8) % ksplit and wave b % 8) and tree-reduce their accumulators through LDS in a fixed order.
 // =================================================================================================
-template <int NT>
-__device__ __forceinline__ void shrink_short_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int ks, float* lds)
+template <int NT, class PP>
+__device__ __forceinline__ void shrink_short_unit(const PP& p, const Unit& u, const SegInfo& s, int ks, float* lds)
 {
     constexpr int MT = kShortRows / 16;
     const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, kg = lane >> 4;
@@ -503,8 +507,8 @@ struct LongAhead {
     u32x4 b[C::ROWS * (C::UN / 8) / kThreads];
 };
 
-template <int KSTEPS, int PAIRS, bool AHEAD>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, a block 8 waves
-__device__ __forceinline__ void expand_long_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int nb_begin,
+template <int KSTEPS, int PAIRS, bool AHEAD, class PP>  // ranks up to 32 * KSTEPS; a wave covers 32 * PAIRS columns, a block 8 waves
+__device__ __forceinline__ void expand_long_unit(const PP& p, const Unit& u, const SegInfo& s, int nb_begin,
                                                  int nb_end, unsigned char* lds, const LongAhead<KSTEPS, PAIRS>& pre)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
@@ -830,8 +834,8 @@ struct ShortAhead {
     u32x4 y[kTT], b[2 * kShortGroup];
 };
 
-template <bool AHEAD>  // AHEAD: rows, y and the first 16 rows of B come from `pre`
-__device__ __forceinline__ void expand_short_unit(const FwdParams& p, const Unit& u, const SegInfo& s, int n_block,
+template <bool AHEAD, class PP>  // AHEAD: rows, y and the first 16 rows of B come from `pre`
+__device__ __forceinline__ void expand_short_unit(const PP& p, const Unit& u, const SegInfo& s, int n_block,
                                                   ShortLds& sh, const ShortAhead& pre)
 {
     constexpr int JG = kShortGroup;
@@ -957,8 +961,8 @@ constexpr size_t shrink_lds_bytes()
     return tall > small ? tall : small;
 }
 
-template <int NT>
-__device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdParams>& sg, unsigned char* lds_raw,
+template <int NT, class PP>
+__device__ __forceinline__ void shrink_phase(const PP& p, const Segs<PP>& sg, unsigned char* lds_raw,
                                              int* s_slot)
 {
     // hand-out order, large units first so that a launch ends evenly: the even chunks (65 to 128 rows) of
@@ -970,7 +974,7 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdP
     // A grouped call runs every unit once per projection.  Workgroups whose indices differ by 8 sit on the same XCD
     // and share its L2, so the projections of one unit are handed to such workgroups (ids r, r + 8, r + 16 ... of a
     // block of 8 n_proj ids): they run side by side and the x rows they all read cross the HBM interface once.
-    const int n_per = n_tall + n_small, n_all = p.n_proj == 1 ? n_per : ((n_per + 7) & ~7) * p.n_proj;
+    const int n_per = n_tall + n_small, n_all = n_proj_of(p) == 1 ? n_per : ((n_per + 7) & ~7) * n_proj_of(p);
     LQ_STAMP(0, 2);
     for_each_unit(p.tickets + 0, n_all, s_slot, [&](int gid, int it) {
         Unit u;
@@ -979,8 +983,8 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdP
         LQ_STAMP(0, LQ_UNIT_SLOT(it, 0));
         int id = gid;
         u.pi = 0;
-        if (p.n_proj > 1) {
-            const int blk = small_div(gid, 8 * p.n_proj), r = gid - blk * 8 * p.n_proj;
+        if (n_proj_of(p) > 1) {
+            const int blk = small_div(gid, 8 * n_proj_of(p)), r = gid - blk * 8 * n_proj_of(p);
             u.pi = r >> 3;
             id = blk * 8 + (r & 7);
             if (id >= n_per) return;  // (padding of the last block)
@@ -1015,13 +1019,18 @@ __device__ __forceinline__ void shrink_phase(const FwdParams& p, const Segs<FwdP
     LQ_STAMP_WAIT(0, 3);
 }
 
-template <int NT>
-__global__ __launch_bounds__(kThreads) void shrink_kernel(FwdParams p)
+// GROUP = false: the instantiation for a call with one linear layer.  The compiler is told so, and everything
+// that sorts units by projection folds away (a decode batch's start is bound by its instruction count).
+// The argument of a kernel: the whole block for a grouped call, its core for a single call.
+template <bool GROUP> using KernelArg = std::conditional_t<GROUP, FwdParams, FwdCore>;
+
+template <int NT, bool GROUP>
+__global__ __launch_bounds__(kThreads) void shrink_kernel(KernelArg<GROUP> p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ int s_slot[2];
     LQ_STAMP(0, 0);
-    const Segs<FwdParams> sg = load_segs(p);
+    const auto sg = load_segs(p);
     LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
 }
@@ -1057,8 +1066,8 @@ __device__ __forceinline__ int range_of(const int (&len)[kMaxProj], int n, int& 
     return r;
 }
 
-template <int KSTEPS, int PAIRS>
-__device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs<FwdParams>& sg)
+template <int KSTEPS, int PAIRS, class PP>
+__device__ __forceinline__ ExpandPlan plan_expand(const PP& p, const Segs<PP>& sg)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
     ExpandPlan e;
@@ -1068,7 +1077,7 @@ __device__ __forceinline__ ExpandPlan plan_expand(const FwdParams& p, const Segs
     e.sum_short_blocks = 0;
 #pragma unroll
     for (int k = 0; k < kMaxProj; ++k) {
-        const int d_out = k < p.n_proj ? p.proj[k].d_out : 0;
+        const int d_out = k < n_proj_of(p) ? proj_of(p, k).d_out : 0;
         e.long_blocks[k] = (d_out + C::UN - 1) / C::UN;
         e.short_blocks[k] = (d_out + kShortN - 1) / kShortN;
         sum_blocks += e.long_blocks[k];
@@ -1128,17 +1137,19 @@ __device__ __forceinline__ int first_short_unit(const ExpandPlan& e)
     return e.n_chunks > 0 ? (int)blockIdx.x * kWaves + w : w * (int)gridDim.x + (int)blockIdx.x;
 }
 // short unit `id`: ids count through the row chunks, and for each chunk through the 512-column blocks of every projection
-__device__ __forceinline__ bool find_short_unit(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e, int id,
+template <class PP>
+__device__ __forceinline__ bool find_short_unit(const PP& p, const Segs<PP>& sg, const ExpandPlan& e, int id,
                                                 Unit& u, SegInfo& s, int& n_block)
 {
     const int chunk = small_div(id, e.sum_short_blocks);
     n_block = id - chunk * e.sum_short_blocks;
-    u.pi = range_of(e.short_blocks, p.n_proj, n_block);
+    u.pi = range_of(e.short_blocks, n_proj_of(p), n_block);
     return find_unit(p, sg, e.cs, chunk, kTT, e.shorts, u, s);
 }
 
 // requests the loads of this wave's first short unit that do not depend on h
-__device__ __forceinline__ ShortAhead short_request(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e)
+template <class PP>
+__device__ __forceinline__ ShortAhead short_request(const PP& p, const Segs<PP>& sg, const ExpandPlan& e)
 {
     ShortAhead a;
     a.live = false;
@@ -1164,13 +1175,14 @@ __device__ __forceinline__ ShortAhead short_request(const FwdParams& p, const Se
 // long unit `id`: large ones first so that a launch ends evenly: the even chunks of the segments with more
 // than `per` rows, the segments with per/2 to per rows, the smaller ones; within a class ids count through the
 // row chunks, and for each chunk through the column groups of every projection
-__device__ __forceinline__ bool find_long_unit(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e, int id,
+template <class PP>
+__device__ __forceinline__ bool find_long_unit(const PP& p, const Segs<PP>& sg, const ExpandPlan& e, int id,
                                                Unit& u, SegInfo& s, int& nb_begin, int& nb_end)
 {
     const int cid = id < e.n_full ? id : id < e.n_big ? id - e.n_full : id - e.n_big;
     const int chunk = small_div(cid, e.sum_groups);
     int g = cid - chunk * e.sum_groups;
-    u.pi = range_of(e.groups, p.n_proj, g);
+    u.pi = range_of(e.groups, n_proj_of(p), g);
     const int per_group = pick(e.per_group, u.pi);
     nb_begin = g * per_group;
     nb_end = min(pick(e.long_blocks, u.pi), nb_begin + per_group);
@@ -1180,8 +1192,8 @@ __device__ __forceinline__ bool find_long_unit(const FwdParams& p, const Segs<Fw
 }
 
 // requests the loads of this workgroup's first long unit that do not depend on h
-template <int KSTEPS, int PAIRS>
-__device__ __forceinline__ LongAhead<KSTEPS, PAIRS> long_request(const FwdParams& p, const Segs<FwdParams>& sg,
+template <int KSTEPS, int PAIRS, class PP>
+__device__ __forceinline__ LongAhead<KSTEPS, PAIRS> long_request(const PP& p, const Segs<PP>& sg,
                                                                   const ExpandPlan& e)
 {
     using C = ExpandCfg<KSTEPS, PAIRS>;
@@ -1204,8 +1216,8 @@ __device__ __forceinline__ LongAhead<KSTEPS, PAIRS> long_request(const FwdParams
 }
 
 // AHEAD: this wave's first short unit and this workgroup's first long unit were requested into `ahead`, `lahead`
-template <int KSTEPS, int PAIRS, bool AHEAD>
-__device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdParams>& sg, const ExpandPlan& e,
+template <int KSTEPS, int PAIRS, bool AHEAD, class PP>
+__device__ __forceinline__ void expand_phase(const PP& p, const Segs<PP>& sg, const ExpandPlan& e,
                                              unsigned char* lds_raw, ShortLds& sh, int* s_slot, const ShortAhead ahead,
                                              const LongAhead<KSTEPS, PAIRS> lahead)
 {
@@ -1254,14 +1266,14 @@ __device__ __forceinline__ void expand_phase(const FwdParams& p, const Segs<FwdP
     LQ_STAMP_WAIT(1, 3);
 }
 
-template <int KSTEPS, int PAIRS>
-__global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
+template <int KSTEPS, int PAIRS, bool GROUP>
+__global__ __launch_bounds__(kThreads) void expand_kernel(KernelArg<GROUP> p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
     __shared__ int s_slot[2];
     LQ_STAMP(1, 0);
-    const Segs<FwdParams> sg = load_segs(p);
+    const auto sg = load_segs(p);
     LQ_STAMP(1, 1);
     const ExpandPlan plan = plan_expand<KSTEPS, PAIRS>(p, sg);
     ShortAhead none;
@@ -1279,14 +1291,14 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(FwdParams p)
 // workspace error word instead of hanging.
 //   (header words: see kBarGen, kBarTop, kBarSub)
 // =================================================================================================
-template <int NT, int KSTEPS, int PAIRS>
-__global__ __launch_bounds__(kThreads) void fused_kernel(FwdParams p)
+template <int NT, int KSTEPS, int PAIRS, bool GROUP>
+__global__ __launch_bounds__(kThreads) void fused_kernel(KernelArg<GROUP> p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
     __shared__ int s_slot[2];
     LQ_STAMP(0, 0);
-    const Segs<FwdParams> sg = load_segs(p);
+    const auto sg = load_segs(p);
     // The generation is read before this workgroup arrives, hence before the last arrival can change it;
     // and after the table loads, so that their results need not wait for this slower, uncached load.
     const int gen0 = __hip_atomic_load(p.header + kBarGen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1334,11 +1346,15 @@ int resident_grid(K kernel, size_t dyn_lds)
     return cus * per_cu;
 }
 
+// (the two instantiations of a kernel, for single and for grouped calls, use the same registers and LDS, hence the same grid)
 template <int NT>
 int shrink_grid()
 {
     static int grid = 0;
-    if (!grid) grid = resident_grid(shrink_kernel<NT>, shrink_lds_bytes<NT>());
+    if (!grid) {
+        grid = resident_grid(shrink_kernel<NT, false>, shrink_lds_bytes<NT>());
+        grid = std::min(grid, resident_grid(shrink_kernel<NT, true>, shrink_lds_bytes<NT>()));
+    }
     return grid;
 }
 
@@ -1357,7 +1373,9 @@ int choose_ksplit(int n_tokens, int n_proj, int d_in, int grid)
 template <int NT>
 hipError_t launch_shrink(const FwdParams& p, hipStream_t st)
 {
-    return launch_kernel(kKernelShrink, shrink_kernel<NT>, dim3(shrink_grid<NT>()), dim3(kThreads), shrink_lds_bytes<NT>(), st, p);
+    if (p.n_proj == 1)
+        return launch_kernel(kKernelShrink, shrink_kernel<NT, false>, dim3(shrink_grid<NT>()), dim3(kThreads), shrink_lds_bytes<NT>(), st, static_cast<const FwdCore&>(p));
+    return launch_kernel(kKernelShrink, shrink_kernel<NT, true>, dim3(shrink_grid<NT>()), dim3(kThreads), shrink_lds_bytes<NT>(), st, p);
 }
 
 template <int KSTEPS, int PAIRS>
@@ -1365,8 +1383,12 @@ hipError_t launch_expand(const FwdParams& p, hipStream_t st)
 {
     static int grid = 0;
     const size_t lds = ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
-    if (!grid) grid = resident_grid(expand_kernel<KSTEPS, PAIRS>, lds);
-    return launch_kernel(kKernelExpand, expand_kernel<KSTEPS, PAIRS>, dim3(grid), dim3(kThreads), lds, st, p);
+    if (!grid) {
+        grid = resident_grid(expand_kernel<KSTEPS, PAIRS, false>, lds);
+        grid = std::min(grid, resident_grid(expand_kernel<KSTEPS, PAIRS, true>, lds));
+    }
+    if (p.n_proj == 1) return launch_kernel(kKernelExpand, expand_kernel<KSTEPS, PAIRS, false>, dim3(grid), dim3(kThreads), lds, st, static_cast<const FwdCore&>(p));
+    return launch_kernel(kKernelExpand, expand_kernel<KSTEPS, PAIRS, true>, dim3(grid), dim3(kThreads), lds, st, p);
 }
 
 template <int NT, int KSTEPS, int PAIRS>
@@ -1375,7 +1397,10 @@ int fused_grid()
     static int grid = 0;
     const size_t lds = shrink_lds_bytes<NT>() > ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES ? shrink_lds_bytes<NT>()
                                                                                    : ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
-    if (!grid) grid = resident_grid(fused_kernel<NT, KSTEPS, PAIRS>, lds);
+    if (!grid) {
+        grid = resident_grid(fused_kernel<NT, KSTEPS, PAIRS, false>, lds);
+        grid = std::min(grid, resident_grid(fused_kernel<NT, KSTEPS, PAIRS, true>, lds));
+    }
     return grid;
 }
 
@@ -1384,7 +1409,9 @@ hipError_t launch_fused(const FwdParams& p, hipStream_t st)
 {
     const size_t lds = shrink_lds_bytes<NT>() > ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES ? shrink_lds_bytes<NT>()
                                                                                    : ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
-    return launch_kernel(kKernelFused, fused_kernel<NT, KSTEPS, PAIRS>, dim3(fused_grid<NT, KSTEPS, PAIRS>()), dim3(kThreads), lds, st, p);
+    if (p.n_proj == 1)
+        return launch_kernel(kKernelFused, fused_kernel<NT, KSTEPS, PAIRS, false>, dim3(fused_grid<NT, KSTEPS, PAIRS>()), dim3(kThreads), lds, st, static_cast<const FwdCore&>(p));
+    return launch_kernel(kKernelFused, fused_kernel<NT, KSTEPS, PAIRS, true>, dim3(fused_grid<NT, KSTEPS, PAIRS>()), dim3(kThreads), lds, st, p);
 }
 
 }  // namespace
@@ -1487,7 +1514,8 @@ lq_status forward_checked(const void* x, int64_t ldx, int32_t d_in, int32_t n_pr
     p.x = static_cast<const u16*>(x); p.ldx = ldx;
     p.d_in = d_in;
     p.n_proj = n_proj;
-    for (int k = 0; k < kMaxProj; ++k) p.proj[k] = projs[k < n_proj ? k : 0];
+    p.proj0 = projs[0];
+    for (int k = 1; k < kMaxProj; ++k) p.more[k - 1] = projs[k < n_proj ? k : 0];
     p.ranks = ranks; p.scales = scales;
     p.n_adapters = n_adapters; p.max_rank = max_rank;
     p.token_scales = token_scales;

@@ -18,10 +18,14 @@ struct Proj {
     float* h_out;
 };
 
-struct FwdParams {
+// FwdCore is the parameter block of a call with one linear layer, FwdParams (below) that of a grouped call; the
+// device functions are templates over the two (n_proj_of and proj_of tell them apart).  The kernels are short of
+// scalar registers: the larger block as the argument of every kernel makes a single call re-read its arguments
+// from memory over and over (measured: + 1.2 us per call); and a local copy of a block ends up in scratch memory.
+struct FwdCore {
     const u16* x; long long ldx;
     int d_in;
-    int n_proj; Proj proj[kMaxProj];
+    int n_proj; Proj proj0;  // the first (or only) linear layer
     const int32_t* ranks; const float* scales; int n_adapters; int max_rank;
     const float* token_scales;  // per token row; when given it replaces scales[adapter] (null: per-adapter scales)
     const int32_t* perm; int n_tokens;
@@ -42,13 +46,21 @@ struct FwdParams {
     int* tickets;    // workspace header words 4..: unit tickets ([0,1] shrink phase, [2,3] expand phase); the barrier's words: kBar*
 };
 
-// projection pi of a call (pi wave uniform).  Every member is picked by value: a run-time index into the kernel's
+struct FwdParams : FwdCore {
+    Proj more[kMaxProj - 1];  // the other linear layers of a grouped call
+};
+
+__device__ __forceinline__ int n_proj_of(const FwdCore&) { return 1; }
+__device__ __forceinline__ int n_proj_of(const FwdParams& p) { return p.n_proj; }
+__device__ __forceinline__ Proj proj_of(const FwdCore& p, int) { return p.proj0; }
+
+// linear layer pi of a call (pi wave uniform).  Every member is picked by value: a run-time index into the kernel's
 // parameter block (or a choice between references into it) would make the compiler keep a copy of the whole block
-// in scratch memory.
+// in scratch memory (measured: + 20 us per launch).
 __device__ __forceinline__ Proj proj_of(const FwdParams& p, int pi)
 {
     static_assert(kMaxProj == 4, "the entries are picked by name");
-#define LQ_PICK(member) (pi == 0 ? p.proj[0].member : pi == 1 ? p.proj[1].member : pi == 2 ? p.proj[2].member : p.proj[3].member)
+#define LQ_PICK(member) (pi == 0 ? p.proj0.member : pi == 1 ? p.more[0].member : pi == 2 ? p.more[1].member : p.more[2].member)
     Proj q;
     { u16* const v = LQ_PICK(y); q.y = v; }
     { const long long v = LQ_PICK(ldy); q.ldy = v; }

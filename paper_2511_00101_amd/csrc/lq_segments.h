@@ -8,7 +8,7 @@
 //
 // P is a kernel parameter block with the members seg_starts, seg_adapter, seg_kind, n_segments,
 // max_segments, n_adapters, max_rank, ranks, scales, perm, n_tokens, err (and, for the adapter lookups,
-// proj[].A_ptrs / B_ptrs).
+// proj0.A_ptrs / B_ptrs and proj_of).
 #pragma once
 
 #include "lq_common.h"
@@ -194,8 +194,8 @@ __device__ __forceinline__ Segs<P> load_segs(const P& p)
 #pragma unroll
     for (int b = 0; b < kCachedBatches; ++b) {
         const int ad = min(b * kWave + lane_id(), p.n_adapters - 1);
-        const unsigned long long pa = reinterpret_cast<unsigned long long>(p.proj[0].A_ptrs[ad]);
-        const unsigned long long pb = reinterpret_cast<unsigned long long>(p.proj[0].B_ptrs[ad]);
+        const unsigned long long pa = reinterpret_cast<unsigned long long>(p.proj0.A_ptrs[ad]);
+        const unsigned long long pb = reinterpret_cast<unsigned long long>(p.proj0.B_ptrs[ad]);
         sg.a[b].a_lo = (unsigned int)pa; sg.a[b].a_hi = (unsigned int)(pa >> 32);
         sg.a[b].b_lo = (unsigned int)pb; sg.a[b].b_hi = (unsigned int)(pb >> 32);
         sg.a[b].rank = p.ranks[ad];
