@@ -233,8 +233,14 @@ lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int
  *            variant; falls back to two launches where the partial-g region would reach 2 GiB);
  *            LQ_VARIANT_SPLIT: two launches, no device-wide wait.  Other values: LQ_ERR_INVALID_ARG.
  *   workspace lora_backward_workspace_bytes(...) bytes; its first 4096 bytes zero as for the forward.
- *   Then the weight-gradient partials and their reduction (two more launches).
- *   The order of every sum is fixed, so results are reproducible run to run.
+ *   Then the weight gradients: a fine-tune segment of up to 512 rows is accumulated straight into dA / dB;
+ *   a longer one is cut into row chunks whose partial sums go to the workspace and are added in chunk
+ *   order by one more launch (skipped for batches of up to 512 tokens).
+ *   dA / dB are accumulated with fp32 additions in memory (plain device allocations, not fine-grained
+ *   host-visible memory), one addition per element and fine-tune segment, and every other sum has a fixed
+ *   order: results are reproducible run to run when every adapter has at most one fine-tune segment
+ *   (always true of lora_build_segments' tables); two fine-tune segments of one adapter are both added,
+ *   in either order.
  * ------------------------------------------------------------------------------------------- */
 size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in,
                                      int32_t d_out);

@@ -10,12 +10,18 @@
 //                          (for dA, with g).  32 rows at a time are staged in LDS with coalesced loads
 //                          (four steps in flight in registers, two LDS buffers) and read back
 //                          transposed into 16x16x32 bf16 MFMA fragments; h and g are split into bf16
-//                          high and low parts.  The unit stores its [rank x 256] partial to the
-//                          workspace.
-//   reduce unit          : one segment x 512 columns x 8 ranks: adds the segment's partials in chunk
+//                          high and low parts.  A segment of up to 512 rows is one unit per column block,
+//                          which adds its [rank x 256] result straight into dA / dB; a longer segment is
+//                          cut into row chunks whose units store their partials to the workspace.
+//   reduce unit          : one cut segment x 512 columns x 8 ranks: adds the segment's partials in chunk
 //                          order, applies the scale and accumulates into dA / dB.  Fixed order, so
 //                          reproducible.
+// (Tried: the unit that stores the last partial of a (segment, column block) adds the partials up, so that no
+// reduction launch is needed.  The partials then have to be stored and read with device-scope accesses, and
+// every unit ends with a wait for its stores, an arrival and, for the last one, a round of loads: the
+// weight-gradient launch went from 28 to 44 us on the layer stack, against 8 us for the reduction launch.)
 #include "lq_internal.h"
+#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 #include <type_traits>
 #include <utility>
 
@@ -48,7 +54,7 @@ struct BwdParams {
     const float* h_saved; const long long* h_offsets;
     const float* g;      // g = dy B^T of the fine-tune rows, laid out like h_saved
     int rstride;
-    float* wpart;        // [chunk][rstride][d_out + d_in] partial weight gradients
+    float* wpart;        // [chunk of a segment with more than 512 rows][rstride][d_out + d_in] partial weight gradients
     int* err;
 };
 
@@ -73,8 +79,10 @@ __device__ __forceinline__ void for_each_slot(std::integer_sequence<int, Js...>,
 // D[rank][col] = sum_t H[t][rank] Y[t][col] over the unit's rows; H = h_saved (for dB, Y = dy) or g (for
 // dA, Y = x).  MFMA: lane (c = lane % 16, kg = lane / 16) supplies H[8 kg ..][rank c] and Y[8 kg ..][col c]
 // of a 32-row step and receives D[rank 4 kg + v][col c].
+// chunk_id < 0: the unit covers its whole segment and accumulates into dA / dB (times scale); else it stores its
+// partial to slot chunk_id of wpart
 template <int NT>
-__device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, int rank, int chunk_id, bool for_b,
+__device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, int rank, float scale, int chunk_id, bool for_b,
                                            int col_block, unsigned char* lds)
 {
     using C = WgCfg<NT>;
@@ -182,6 +190,22 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
         });
 
     LQ_STAMP(0, 30);
+    if (chunk_id < 0) {
+        // Accumulation with the hardware's fp32 addition in memory: every element receives exactly one addition per
+        // segment, so the result does not depend on timing as long as an adapter has one fine-tune segment (always
+        // true of the builder's tables); two segments of one adapter are both added, in either order.
+        float* dst = for_b ? p.dB_ptrs[u.ad] : p.dA_ptrs[u.ad];
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt)
+#pragma unroll
+            for (int nt = 0; nt < kWgTiles; ++nt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int j = jt * 16 + 4 * kg + v, n = n0 + w * (16 * kWgTiles) + nt * 16 + c;
+                    if (j < rank && n < d) unsafeAtomicAdd(dst + (long long)j * d + n, scale * acc[jt][nt][v]);
+                }
+        return;
+    }
     const int dsum = p.d_out + p.d_in;
     float* out = p.wpart + (long long)chunk_id * p.rstride * dsum + (for_b ? 0 : p.d_out);
 #pragma unroll
@@ -197,6 +221,11 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
 
 // (ranks up to 32: at most 128 registers, so that two workgroups share a compute unit and one's loads
 // overlap the other's barriers)
+// the fine-tune segments with more than 512 rows are cut into chunks (partials, then the reduction); the shorter
+// ones are one unit per column block
+__device__ __forceinline__ LenClass cut_class() { return LenClass{kWgRows + 1, kBig, 1 << LQ_SEG_FINETUNE}; }
+__device__ __forceinline__ LenClass whole_class() { return LenClass{1, kWgRows + 1, 1 << LQ_SEG_FINETUNE}; }
+
 template <int NT>
 __global__ __launch_bounds__(kThreads, NT <= 2 ? 4 : 2) void wgrad_kernel(BwdParams p)
 {
@@ -204,42 +233,47 @@ __global__ __launch_bounds__(kThreads, NT <= 2 ? 4 : 2) void wgrad_kernel(BwdPar
     LQ_STAMP(0, 0);
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegCache c0 = load_seg_cache(p, n_seg);
-    const LenClass ft{1, kBig, 1 << LQ_SEG_FINETUNE};
+    const LenClass cut = cut_class(), whole = whole_class();
     const int blocks_b = (p.d_out + kWgCols - 1) / kWgCols, blocks_a = (p.d_in + kWgCols - 1) / kWgCols;
     const int per_chunk = blocks_b + blocks_a;
-    const int n_units = count_chunks(p, n_seg, c0, kWgRows, ft) * per_chunk;
+    const int n_cut = count_chunks(p, n_seg, c0, kWgRows, cut) * per_chunk;  // the (larger) chunks first
+    const int n_units = n_cut + count_chunks(p, n_seg, c0, kWgRows, whole) * per_chunk;
     for (int id = (int)blockIdx.x; id < n_units; id += (int)gridDim.x) {
         Unit u;
-        const int chunk_id = small_div(id, per_chunk), cb = id - chunk_id * per_chunk;
-        if (!find_chunk(p, n_seg, c0, chunk_id, kWgRows, ft, u)) continue;
+        const bool is_cut = id < n_cut;
+        const int chunk_id = small_div(is_cut ? id : id - n_cut, per_chunk), cb = (is_cut ? id : id - n_cut) - chunk_id * per_chunk;
+        if (!(is_cut ? find_chunk(p, n_seg, c0, chunk_id, kWgRows, cut, u) : find_chunk(p, n_seg, c0, chunk_id, kWgRows, whole, u)))
+            continue;
         if (u.ad < 0 || u.ad >= p.n_adapters) continue;  // flagged by the forward kernels already
         const int rank = p.ranks[u.ad];
         if (rank < 1 || rank > p.max_rank) continue;
         const bool for_b = cb < blocks_b;
         if (for_b ? (p.dB_ptrs == nullptr || p.dB_ptrs[u.ad] == nullptr) : (p.dA_ptrs == nullptr || p.dA_ptrs[u.ad] == nullptr))
             continue;
-        wgrad_unit<NT>(p, u, rank, chunk_id, for_b, for_b ? cb : cb - blocks_b, lds_raw);
+        const float scale = p.token_scales ? 1.f : p.scales[u.ad];  // (per-token scales were applied row by row)
+        wgrad_unit<NT>(p, u, rank, scale, is_cut ? chunk_id : -1, for_b, for_b ? cb : cb - blocks_b, lds_raw);
     }
 }
 
-// dA / dB += scale * (sum of the segment's chunk partials, in chunk order).  One unit = the first chunk of
+// dA / dB += scale * (sum of a cut segment's chunk partials, in chunk order).  One unit = the first chunk of
 // a segment x 512 columns of [dB | dA] x 8 ranks; a thread owns one column and keeps the 8 sums in
-// registers, so the loads of a chunk's partials are independent of each other.
+// registers, so the loads of a chunk's partials are independent of each other.  The accumulation is the
+// hardware's fp32 addition in memory, one per element and segment (see wgrad_unit).
 constexpr int kRedRanks = 8;
 __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
 {
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegCache c0 = load_seg_cache(p, n_seg);
-    const LenClass ft{1, kBig, 1 << LQ_SEG_FINETUNE};
+    const LenClass cut = cut_class();
     const int dsum = p.d_out + p.d_in;
     const int col_blocks = (dsum + kThreads - 1) / kThreads;
     const int rank_groups = (p.max_rank + kRedRanks - 1) / kRedRanks;
     const int per_chunk = col_blocks * rank_groups;
-    const int n_units = count_chunks(p, n_seg, c0, kWgRows, ft) * per_chunk;
+    const int n_units = count_chunks(p, n_seg, c0, kWgRows, cut) * per_chunk;
     for (int id = (int)blockIdx.x; id < n_units; id += (int)gridDim.x) {
         Unit u;
         const int chunk_id = small_div(id, per_chunk), sub = id - chunk_id * per_chunk;
-        if (!find_chunk(p, n_seg, c0, chunk_id, kWgRows, ft, u)) continue;
+        if (!find_chunk(p, n_seg, c0, chunk_id, kWgRows, cut, u)) continue;
         if (u.pos != u.first) continue;  // only the segment's first chunk adds up the segment
         if (u.ad < 0 || u.ad >= p.n_adapters) continue;
         const int rank = p.ranks[u.ad];
@@ -254,12 +288,9 @@ __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
         if (!dst) continue;
         const int d = for_b ? p.d_out : p.d_in, n = for_b ? col : col - p.d_out;
         const float* __restrict__ part = p.wpart + ((long long)chunk_id * p.rstride + j0) * dsum + col;
-        float sum[kRedRanks], old[kRedRanks];
+        float sum[kRedRanks];
 #pragma unroll
-        for (int jj = 0; jj < kRedRanks; ++jj) {
-            sum[jj] = 0.f;
-            old[jj] = dst[(long long)min(j0 + jj, rank - 1) * d + n];
-        }
+        for (int jj = 0; jj < kRedRanks; ++jj) sum[jj] = 0.f;
         for (int cc = 0; cc < n_chunks; ++cc) {
             float v[kRedRanks];
 #pragma unroll
@@ -270,16 +301,18 @@ __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
         }
 #pragma unroll
         for (int jj = 0; jj < kRedRanks; ++jj)
-            if (j0 + jj < rank) dst[(long long)(j0 + jj) * d + n] = old[jj] + scale * sum[jj];
+            if (j0 + jj < rank) unsafeAtomicAdd(dst + (long long)(j0 + jj) * d + n, scale * sum[jj]);
     }
 }
 
 // finished g of the fine-tune rows: at most n_tokens x max_rank floats (a multiple of 16 bytes)
 size_t gsum_bytes(int n_tokens, int max_rank) { return ((size_t)n_tokens * (size_t)max_rank * sizeof(float) + 15) / 16 * 16; }
 
-size_t wpart_bytes(int n_tokens, int n_adapters, int max_rank, int d_in, int d_out)
+// Only segments with more than 512 rows keep partials: n such segments have at most n_tokens / 512 + n chunks
+// and n <= n_tokens / 513, whatever tables the caller passes.
+size_t wpart_bytes(int n_tokens, int max_rank, int d_in, int d_out)
 {
-    const size_t chunks = (size_t)(n_tokens + kWgRows - 1) / kWgRows + (size_t)(n_tokens < n_adapters ? n_tokens : n_adapters);
+    const size_t chunks = 2 * ((size_t)(n_tokens + kWgRows - 1) / kWgRows);
     return chunks * (size_t)rstride_for(max_rank) * ((size_t)d_in + d_out) * sizeof(float);
 }
 
@@ -321,9 +354,10 @@ extern "C" int lq_trace_read_backward(unsigned long long* host, int n_words)
 extern "C" size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in,
                                                 int32_t d_out)
 {
-    if (n_tokens < 0 || n_adapters < 0 || max_rank < 1 || d_in < 0 || d_out < 0) return lq::kWsHeaderBytes;
+    (void)n_adapters;
+    if (n_tokens < 0 || max_rank < 1 || d_in < 0 || d_out < 0) return lq::kWsHeaderBytes;
     return (size_t)lq::kWsHeaderBytes + lq::h_slices_bytes(n_tokens, max_rank) + lq::gsum_bytes(n_tokens, max_rank) +
-           lq::wpart_bytes(n_tokens, n_adapters, max_rank, d_in, d_out);
+           lq::wpart_bytes(n_tokens, max_rank, d_in, d_out);
 }
 
 extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const void* dy, int64_t lddy, void* dx,
@@ -415,7 +449,9 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
         const hipError_t e = max_rank <= 16 ? launch_wgrad<1>(b, st) : max_rank <= 32 ? launch_wgrad<2>(b, st)
                            : max_rank <= 64 ? launch_wgrad<4>(b, st) : launch_wgrad<8>(b, st);
         if (e != hipSuccess) return LQ_ERR_HIP;
-        if (launch_kernel(kKernelWreduce, wreduce_kernel, dim3(512), dim3(kThreads), 0, st, b) != hipSuccess) return LQ_ERR_HIP;
+        // (no segment of a batch of up to 512 tokens is cut into chunks: nothing to reduce)
+        if (n_tokens > kWgRows && launch_kernel(kKernelWreduce, wreduce_kernel, dim3(512), dim3(kThreads), 0, st, b) != hipSuccess)
+            return LQ_ERR_HIP;
     }
     return LQ_OK;
 }

@@ -137,3 +137,47 @@ def test_backward_many_tokens(oracle_mod):
     """40000 tokens, two fine-tune segments of thousands of rows: weight gradients from many row chunks."""
     for variant in VARIANTS:
         run_backward(oracle_mod, long_batch_problem(901, with_dy=True), variant)
+
+
+def test_backward_caller_tables_with_repeated_finetune_adapter(oracle_mod):
+    """Tables written by the caller may hold several fine-tune segments of one adapter (two fine-tune requests that
+    share an adapter) and more fine-tune segments than adapters: every segment's weight gradient must be added (the
+    accumulation is an atomic fp32 addition per element), and nothing may be written out of bounds."""
+    rng = np.random.default_rng(8)
+    lens = [600, 10, 700, 10, 10, 10, 10, 10, 30, 10, 10, 10]     # two segments longer than one 512-row chunk
+    ads = [0, 1, 0, 1, 0, 1, 0, 1, 0, 1, 0, 1]                    # n_adapters = 2, twelve fine-tune segments
+    ta = np.concatenate([np.full(l, a, np.int32) for l, a in zip(lens, ads)])
+    tk = np.zeros(len(ta), np.uint8)
+    p = synth.make_problem("repeated", synth.Batch(ta, tk), 520, 264, [8, 24], [1.0, 0.5], 99, with_dy=True, w_std=0.03)
+    dx0 = synth.normal_bf16(rng, (p.n_tokens, p.d_in), 1.0)
+    ref = oracle_mod.backward(p.x, p.dy, dx0, p.A, p.B, p.ranks, p.scales, ta, tk)
+    d = DeviceProblem(p)
+    seg = lq.SegmentTables.empty(p.n_tokens, p.n_adapters, max_segments=len(lens))
+    starts = np.cumsum([0] + lens)
+    seg.perm[:] = torch.arange(p.n_tokens, dtype=torch.int32)
+    seg.seg_starts[:] = torch.tensor(starts, dtype=torch.int32)
+    seg.seg_adapter[:] = torch.tensor(ads, dtype=torch.int32)
+    seg.seg_kind[:] = 0
+    seg.h_offsets[:] = torch.tensor(np.cumsum([0] + [l * int(p.ranks[a]) for l, a in zip(lens, ads)]), dtype=torch.int64)
+    seg.n_segments[0] = len(lens)
+    d.seg = seg
+    h_elems = int(seg.h_offsets[-1].item())
+    for variant in VARIANTS:
+        y_bits, h, err = d.forward(variant, h_elems=h_elems)
+        assert err == 0
+        dx = lq.bf16_from_bits(dx0)
+        dA = [torch.zeros(int(r), p.d_in, dtype=torch.float32, device="cuda") for r in p.ranks]
+        dB = [torch.zeros(int(r), p.d_out, dtype=torch.float32, device="cuda") for r in p.ranks]
+        dA_ptrs = torch.tensor([t.data_ptr() for t in dA], dtype=torch.int64, device="cuda")
+        dB_ptrs = torch.tensor([t.data_ptr() for t in dB], dtype=torch.int64, device="cuda")
+        ws = lq.workspace(lq.lora_backward_workspace_bytes(p.n_tokens, p.n_adapters, d.adapters.max_rank, p.d_in, p.d_out))
+        lq.lora_segmented_backward(d.x, d.dy, dx, d.adapters, dA_ptrs, dB_ptrs, seg, d.h_out, ws, variant)
+        torch.cuda.synchronize()
+        assert int(ws[0].item() & 0xffffffff) == 0
+        assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(dx)), ref.dx, "dx")
+        for a in range(p.n_adapters):
+            for got, want, what in ((dA[a].cpu().numpy(), ref.dA[a], "dA"), (dB[a].cpu().numpy(), ref.dB[a], "dB")):
+                scale = float(np.abs(want).max())
+                assert rel_frobenius(got, want) <= WGRAD_REL_FROBENIUS, f"{what}[{a}]"
+                assert float(np.abs(got - want).max()) <= WGRAD_REL_MAX * scale, f"{what}[{a}]"
+        d.y.copy_(lq.bf16_from_bits(p.y0))
