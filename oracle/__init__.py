@@ -45,6 +45,17 @@ def _load():
         L.lq_oracle_backward.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, vp, i32,
                                          vp, vp, vp, vp, vp, vp, vp, vp]
         L.lq_oracle_num_threads.restype = i32
+        u32 = ctypes.c_uint32
+        L.lq_oracle_dropout_keep.restype = i32
+        L.lq_oracle_dropout_keep.argtypes = [u32, i32, i32, u32]
+        L.lq_oracle_dropout_rows.restype = None
+        L.lq_oracle_dropout_rows.argtypes = [vp, i64, vp, i64, i32, i32, vp, vp, i32, u32, u32]
+        L.lq_oracle_kind_offsets.restype = None
+        L.lq_oracle_kind_offsets.argtypes = [vp, vp, i32, vp]
+        L.lq_oracle_split_rows.restype = None
+        L.lq_oracle_split_rows.argtypes = [vp, i64, i32, vp, i32, vp]
+        L.lq_oracle_concat_rows.restype = None
+        L.lq_oracle_concat_rows.argtypes = [vp, i32, vp, i32, vp, i64]
         _lib = L
     return _lib
 
@@ -176,3 +187,51 @@ def backward(x, dy, dx0, A, B, ranks, scales, token_adapter, token_kind, token_s
                                _p(rk), _p(sc), rk.shape[0], _p(ta), _p(tk), _p(hoff), _p(ts),
                                _ptr_table(dA), _ptr_table(dB), _p(dx), _p(g))
     return BackwardResult(dA, dB, dx, g[:seg.h_elems])
+
+
+# ---- LoRA dropout on the fine-tuning rows, row split / concatenation of Algorithm 1 ------------------------------
+def dropout_threshold(p: float) -> int:
+    """The 16-bit threshold of the dropout contract: an element is kept iff its 16-bit field is >= round(p * 65536)."""
+    return int(round(p * 65536.0))
+
+
+def dropout_keep(seed: int, t: int, k: int, threshold: int) -> bool:
+    return bool(_load().lq_oracle_dropout_keep(seed & 0xffffffff, t, k, threshold))
+
+
+def dropout_rows(x, token_adapter, token_kind, n_adapters: int, seed: int, p: float) -> np.ndarray:
+    """m * x on the live fine-tuning rows (bf16 bit patterns), every other row copied."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    ta = np.ascontiguousarray(token_adapter, dtype=np.int32)
+    tk = np.ascontiguousarray(token_kind, dtype=np.uint8)
+    out = np.empty_like(x)
+    T, d = x.shape
+    _load().lq_oracle_dropout_rows(_p(x), d, _p(out), d, T, d, _p(ta), _p(tk), n_adapters, seed & 0xffffffff, dropout_threshold(p))
+    return out
+
+
+def kind_offsets(seg: Segments) -> np.ndarray:
+    """int32[4]: where the fine-tune, prefill and decode rows start in the segment order, and the number of live rows."""
+    out = np.zeros(4, np.int32)
+    starts = np.ascontiguousarray(seg.seg_starts, np.int32)
+    kinds = np.ascontiguousarray(seg.seg_kind, np.uint8) if seg.n_segments else np.zeros(1, np.uint8)
+    _load().lq_oracle_kind_offsets(_p(starts), _p(kinds), seg.n_segments, _p(out))
+    return out
+
+
+def split_rows(src, seg: Segments) -> np.ndarray:
+    """The live rows of src in segment order (the three kinds back to back), uint16[n_live, d]."""
+    src = np.ascontiguousarray(src, dtype=np.uint16)
+    perm = np.ascontiguousarray(seg.perm, np.int32)
+    out = np.zeros((perm.shape[0], src.shape[1]), np.uint16)
+    _load().lq_oracle_split_rows(_p(src), src.shape[1], src.shape[1], _p(perm), perm.shape[0], _p(out))
+    return out
+
+
+def concat_rows(parts, seg: Segments, dst) -> np.ndarray:
+    """dst with its live rows replaced by the rows of parts (inverse of split_rows); other rows untouched."""
+    parts = np.ascontiguousarray(parts, dtype=np.uint16)
+    perm = np.ascontiguousarray(seg.perm, np.int32)
+    out = np.ascontiguousarray(dst, dtype=np.uint16).copy()
+    _load().lq_oracle_concat_rows(_p(parts), parts.shape[1], _p(perm), perm.shape[0], _p(out), out.shape[1])
+    return out

@@ -247,3 +247,86 @@ int32_t lq_oracle_num_threads(void)
     return 1;
 #endif
 }
+
+/* ------------------------------------------------------------------------------------------
+ * LoRA dropout on the fine-tuning rows and the row split / concatenation of Algorithm 1.
+ *
+ * Dropout.  The paper's training configurations use LoRA dropout 0.05 (Appendix, LoRA
+ * configuration tables): in the LoRA branch of a fine-tuning token the input x is replaced by
+ * m * x / (1 - p), where the elements of m are independent and 1 with probability 1 - p.  The
+ * paper fixes no generator, so the draw is a CONTRACT of this library (both sides implement
+ * it): m[t,k] depends only on (seed, token row t, column k), through the 32-bit integer hash
+ * of Jarzynski and Olano ("Hash Functions for GPU Rendering", JCGT 2020: one step of a linear
+ * congruential generator followed by the PCG output permutation):
+ *     hash(v)   = let s = v * 747796405 + 2891336453,
+ *                     w = ((s >> ((s >> 28) + 4)) ^ s) * 277803737  in  (w >> 22) ^ w
+ *     key(t)    = hash(seed ^ hash(t))
+ *     word(t,q) = hash(key(t) + q)                 one word per pair of columns, q = k / 2
+ *     field     = low 16 bits of word for even k, high 16 bits for odd k
+ *     m[t,k]    = field >= threshold,   threshold = round(p * 65536)   (p in steps of 2^-16)
+ * The factor 1 / (1 - p) is NOT applied to x (m * x is exact in bf16, x / (1 - p) is not): it
+ * travels with the scale, s' = s / (1 - p) for the token (the per-token scale above), so the
+ * saved h of a fine-tuning token is (m * x) A.  The gradient with respect to x through the LoRA
+ * branch is m * (s' g A): the same mask applied to the rows of dx.
+ * What the mathematics fixes, and the pins check: keep rate 1 - p, independence across
+ * columns, rows and seeds; rows that are not fine-tuning rows are copied unchanged.
+ * ------------------------------------------------------------------------------------------ */
+static uint32_t lqo_hash(uint32_t v)
+{
+    uint32_t s = v * 747796405u + 2891336453u;
+    uint32_t w = ((s >> ((s >> 28) + 4u)) ^ s) * 277803737u;
+    return (w >> 22) ^ w;
+}
+
+int32_t lq_oracle_dropout_keep(uint32_t seed, int32_t t, int32_t k, uint32_t threshold)
+{
+    uint32_t key = lqo_hash(seed ^ lqo_hash((uint32_t)t));
+    uint32_t word = lqo_hash(key + (uint32_t)(k >> 1));
+    uint32_t field = (k & 1) ? (word >> 16) : (word & 0xffffu);
+    return field >= threshold;
+}
+
+/* out[t,:] = m[t,:] * in[t,:] for live fine-tuning tokens, in[t,:] for every other token (bf16 bit patterns). */
+void lq_oracle_dropout_rows(const uint16_t* in, int64_t ld_in, uint16_t* out, int64_t ld_out,
+                            int32_t n_tokens, int32_t d, const int32_t* token_adapter, const uint8_t* token_kind,
+                            int32_t n_adapters, uint32_t seed, uint32_t threshold)
+{
+    for (int32_t t = 0; t < n_tokens; ++t) {
+        int ft = token_is_live(token_adapter[t], token_kind[t], n_adapters) && token_kind[t] == LQO_FINETUNE;
+        for (int32_t k = 0; k < d; ++k) {
+            uint16_t v = in[(int64_t)t * ld_in + k];
+            out[(int64_t)t * ld_out + k] = (!ft || lq_oracle_dropout_keep(seed, t, k, threshold)) ? v : 0;
+        }
+    }
+}
+
+/* Row split of Algorithm 1: the attention layer takes the fine-tuning rows, the prefill (and
+ * evaluation) rows and the decode rows out of Q, K, V by offsets that follow from the batch
+ * order fine-tune | prefill | decode, runs a different attention implementation on each, and
+ * concatenates the outputs again.  With the segment tables the rows of kind c are
+ * perm[kind_offsets[c] .. kind_offsets[c+1]) (kind_offsets = where the segments of each kind
+ * start in the segment order: Algorithm 1's Offset_p and Offset_d), so
+ *     split :  part_c[i, :] = src[perm[kind_offsets[c] + i], :]
+ *     concat:  dst[perm[kind_offsets[c] + i], :] = part_c[i, :]      (rows without adapter untouched)
+ * kind_offsets has 4 entries; parts is the three parts back to back ([n_live, d]). */
+void lq_oracle_kind_offsets(const int32_t* seg_starts, const uint8_t* seg_kind, int32_t n_segments, int32_t* kind_offsets)
+{
+    /* kind c starts at the first segment whose kind is >= c (the segments are ordered by kind), or at the end */
+    for (int c = 0; c <= 3; ++c) {
+        kind_offsets[c] = seg_starts[n_segments];
+        for (int32_t s = n_segments - 1; s >= 0; --s)
+            if (seg_kind[s] >= c) kind_offsets[c] = seg_starts[s];
+    }
+}
+
+void lq_oracle_split_rows(const uint16_t* src, int64_t ld, int32_t d, const int32_t* perm, int32_t n_live, uint16_t* parts)
+{
+    for (int32_t i = 0; i < n_live; ++i)
+        for (int32_t k = 0; k < d; ++k) parts[(int64_t)i * d + k] = src[(int64_t)perm[i] * ld + k];
+}
+
+void lq_oracle_concat_rows(const uint16_t* parts, int32_t d, const int32_t* perm, int32_t n_live, uint16_t* dst, int64_t ld)
+{
+    for (int32_t i = 0; i < n_live; ++i)
+        for (int32_t k = 0; k < d; ++k) dst[(int64_t)perm[i] * ld + k] = parts[(int64_t)i * d + k];
+}

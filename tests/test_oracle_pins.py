@@ -379,3 +379,87 @@ def test_backward_token_scale_single_adapter_dense_form(oracle_mod):
     np.testing.assert_allclose(bw.dB[0], (X @ Af.T).T @ S @ DY, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(bw.dA[0], G.T @ S @ X, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(bw.dx, f64(dx0) + S @ G @ Af, rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
+# LoRA dropout on the fine-tuning rows (training configurations of the appendix: lora_dropout 0.05); the mask is a
+# contract of this library (a counter-based hash), so what is pinned is what the mathematics fixes: independent
+# Bernoulli(1 - p) elements, the same for the same (seed, row, column), and rows of other kinds untouched
+# ---------------------------------------------------------------------------------------------
+def test_dropout_mask_statistics(oracle_mod):
+    T, d, p = 400, 1024, 0.05
+    x = np.full((T, d), 0x3F80, np.uint16)                      # 1.0 everywhere
+    ta, tk = np.zeros(T, np.int32), np.zeros(T, np.uint8)
+    m = oracle_mod.dropout_rows(x, ta, tk, 1, seed=1234, p=p) != 0
+    n = T * d
+    sigma = np.sqrt(p * (1 - p) / n)
+    assert abs((1.0 - m.mean()) - oracle_mod.dropout_threshold(p) / 65536.0) < 5 * sigma
+    # every row and every column has about the same rate (no dead or stuck rows / columns)
+    assert np.abs((1 - m.mean(axis=1)) - p).max() < 6 * np.sqrt(p * (1 - p) / d)
+    assert np.abs((1 - m.mean(axis=0)) - p).max() < 6 * np.sqrt(p * (1 - p) / T)
+    # neighbours are uncorrelated: along a row (also across the two 16-bit fields of a word), down a column, diagonally
+    z = (m.astype(np.float64) - m.mean()) / m.std()
+    for a, b in ((z[:, :-1], z[:, 1:]), (z[:, :-2], z[:, 2:]), (z[:-1, :], z[1:, :]), (z[:-1, :-1], z[1:, 1:]),
+                 (z[:, 0::2], z[:, 1::2])):
+        assert abs(float((a * b).mean())) < 5.0 / np.sqrt(a.size)
+    # another seed gives another, equally uncorrelated mask
+    m2 = oracle_mod.dropout_rows(x, ta, tk, 1, seed=1235, p=p) != 0
+    z2 = (m2.astype(np.float64) - m2.mean()) / m2.std()
+    assert abs(float((z * z2).mean())) < 5.0 / np.sqrt(n)
+    assert (m != m2).mean() > p                                   # (about 2 p (1 - p) of the elements differ)
+
+
+def test_dropout_rates_and_determinism(oracle_mod):
+    T, d = 64, 4096
+    x = np.full((T, d), 0x3F80, np.uint16)
+    ta, tk = np.zeros(T, np.int32), np.zeros(T, np.uint8)
+    for p in (0.0, 0.01, 0.05, 0.5, 0.9):
+        m = oracle_mod.dropout_rows(x, ta, tk, 1, seed=7, p=p) != 0
+        assert abs((1.0 - m.mean()) - p) < 5 * np.sqrt(max(p * (1 - p), 1e-9) / (T * d)) + 1.0 / 65536
+        if p == 0.0:
+            assert m.all()
+        assert np.array_equal(m, oracle_mod.dropout_rows(x, ta, tk, 1, seed=7, p=p) != 0)
+        # the element-wise entry point is the same function
+        for (t, k) in ((0, 0), (3, 1), (17, 4095), (63, 2048)):
+            assert oracle_mod.dropout_keep(7, t, k, oracle_mod.dropout_threshold(p)) == bool(m[t, k])
+    # the mask of a row does not depend on what else is in the batch: row t of a longer batch
+    big = oracle_mod.dropout_rows(np.full((2 * T, d), 0x3F80, np.uint16), np.zeros(2 * T, np.int32), np.zeros(2 * T, np.uint8),
+                                  1, seed=7, p=0.05) != 0
+    assert np.array_equal(big[:T], oracle_mod.dropout_rows(x, ta, tk, 1, seed=7, p=0.05) != 0)
+
+
+def test_dropout_touches_fine_tune_rows_only_and_keeps_values(oracle_mod):
+    p = synth.small_mixed(5, T=60, d_in=64, d_out=8, ranks=[4, 4], drop_frac=0.2)
+    out = oracle_mod.dropout_rows(p.x, p.batch.token_adapter, p.batch.token_kind, p.n_adapters, seed=99, p=0.3)
+    ft = (p.batch.token_kind == 0) & (p.batch.token_adapter >= 0)
+    assert np.array_equal(out[~ft], p.x[~ft])
+    kept = out[ft] != 0
+    assert np.array_equal(out[ft][kept], p.x[ft][kept])           # kept elements are bit-identical
+    assert 0.15 < 1.0 - kept.mean() < 0.45
+
+
+# ---------------------------------------------------------------------------------------------
+# Algorithm 1's row split by kind and concatenation
+# ---------------------------------------------------------------------------------------------
+def test_kind_offsets_split_and_concat(oracle_mod):
+    rng = np.random.default_rng(2)
+    ta = np.array([1, 0, -1, 2, 0, 1, 2, 2, 0, -1, 1], np.int32)
+    tk = np.array([2, 0, 0, 1, 2, 0, 1, 2, 0, 1, 2], np.uint8)
+    seg = oracle_mod.build_segments(ta, tk, np.array([4, 4, 4], np.int32))
+    off = oracle_mod.kind_offsets(seg)
+    live = ta >= 0
+    assert off.tolist() == [0, int((live & (tk == 0)).sum()), int((live & (tk <= 1)).sum()), int(live.sum())]
+    src = rng.integers(0, 65536, size=(len(ta), 6)).astype(np.uint16)
+    parts = oracle_mod.split_rows(src, seg)
+    # every kind's part holds exactly the rows of that kind (by hand: numpy masks), in (adapter, token) order
+    for c in range(3):
+        want_rows = sorted(np.flatnonzero(live & (tk == c)), key=lambda t: (ta[t], t))
+        assert np.array_equal(parts[off[c]: off[c + 1]], src[want_rows])
+    # concatenation is the inverse on the live rows and leaves the other rows alone
+    dst0 = rng.integers(0, 65536, size=src.shape).astype(np.uint16)
+    back = oracle_mod.concat_rows(parts, seg, dst0)
+    assert np.array_equal(back[live], src[live]) and np.array_equal(back[~live], dst0[~live])
+    # a batch without prefill rows: the prefill part is empty and starts where the decode part starts
+    seg2 = oracle_mod.build_segments(ta, np.where(tk == 1, 2, tk).astype(np.uint8), np.array([4, 4, 4], np.int32))
+    off2 = oracle_mod.kind_offsets(seg2)
+    assert off2[1] == off2[2] and off2[3] == int(live.sum())
