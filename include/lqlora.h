@@ -258,6 +258,54 @@ lq_status lora_segmented_backward(const void* x, int64_t ldx, const void* dy, in
                                   int32_t variant, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * LoRA dropout on the fine-tuning rows.  The paper's training configurations use lora_dropout = 0.05
+ * (Appendix, LoRA configuration tables): in the LoRA branch of a fine-tuning token x is replaced by
+ * m * x / (1 - p), the elements of m independent and 1 with probability 1 - p.  This call computes
+ *     out[t, :] = m[t, :] * in[t, :]   for live fine-tuning tokens t,   in[t, :] for every other token
+ * (in == out is allowed: in place).  The factor 1 / (1 - p) is left to the caller's scale (pass
+ * token_scales[t] = s / (1 - p) for those tokens to the forward and the backward): m * x is exact in bf16,
+ * x / (1 - p) is not, so the saved h of a fine-tuning token is (m * x) A.  The same call applied to the
+ * LoRA branch's dx gives the gradient with respect to x (the mask is the same function of seed, row, column).
+ *
+ * The paper fixes no generator; the mask is this library's CONTRACT: with the 32-bit hash of Jarzynski
+ * and Olano (JCGT 2020)   hash(v): s = v * 747796405 + 2891336453;
+ *                                   w = ((s >> ((s >> 28) + 4)) ^ s) * 277803737;  return (w >> 22) ^ w
+ *   key(t) = hash(seed ^ hash(t)),  word(t, q) = hash(key(t) + q) for the column pair q = k / 2,
+ *   field = low 16 bits of the word for even k, high 16 bits for odd k,
+ *   m[t, k] = field >= (uint32)(p * 65536 + 0.5), computed in fp32   (so p acts in steps of 2^-16; p = 0 keeps everything)
+ *   in / out  bf16 [n_tokens, d], leading dimensions ld_in / ld_out; d, ld multiples of 8, 16-byte aligned
+ *   token_adapter, token_kind  as for lora_build_segments (a row is a fine-tuning row iff its adapter id
+ *             lies in [0, n_adapters) and its kind is LQ_SEG_FINETUNE)
+ *   p         in [0, 1), else LQ_ERR_INVALID_ARG
+ * ------------------------------------------------------------------------------------------- */
+lq_status lora_dropout_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int32_t d,
+                            const int32_t* token_adapter, const uint8_t* token_kind, int32_t n_tokens,
+                            int32_t n_adapters, uint32_t seed, float p, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Row split by kind and concatenation (Algorithm 1).  The attention layer takes the fine-tuning,
+ * the prefill (and evaluation) and the decode rows out of Q, K, V by offsets that follow from the
+ * batch order fine-tune | prefill | decode, runs a different attention implementation on each part
+ * and concatenates the outputs again.  With the segment tables the rows of kind c are
+ * perm[kind_offsets[c] .. kind_offsets[c + 1]):
+ *   lora_kind_offsets  kind_offsets int32[4] (device): where the fine-tune, prefill and decode rows start
+ *                      in the segment order (Algorithm 1's Offset_p and Offset_d are entries 1 and 2), and
+ *                      the number of live rows; a kind without rows starts where the next one starts
+ *   lora_split_rows    parts[i, :] = src[perm[i], :] for the live positions i: the three kinds back to
+ *                      back, dense [n_live, d] bf16 (capacity n_tokens rows); perm NULL = identity
+ *   lora_concat_rows   dst[perm[i], :] = parts[i, :]; rows of dst without adapter are untouched
+ *   d and ld multiples of 8, 16-byte aligned pointers; parts must not alias src / dst.
+ * ------------------------------------------------------------------------------------------- */
+lq_status lora_kind_offsets(const int32_t* seg_starts, const uint8_t* seg_kind, const int32_t* n_segments,
+                            int32_t max_segments, int32_t* kind_offsets, void* stream);
+lq_status lora_split_rows(const void* src, int64_t ld, int32_t d, const int32_t* perm, int32_t n_tokens,
+                          const int32_t* seg_starts, const int32_t* n_segments, int32_t max_segments,
+                          void* parts, void* stream);
+lq_status lora_concat_rows(const void* parts, int32_t d, const int32_t* perm, int32_t n_tokens,
+                           const int32_t* seg_starts, const int32_t* n_segments, int32_t max_segments,
+                           void* dst, int64_t ld, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Timing of the library's own kernel launches, for benchmarks (not part of the paper's method).
  * While enabled, every launch gets a pair of events that receive the dispatch's start and end time
  * stamps, i.e. the duration a kernel trace reports, without the gaps between launches.

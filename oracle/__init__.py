@@ -191,8 +191,9 @@ def backward(x, dy, dx0, A, B, ranks, scales, token_adapter, token_kind, token_s
 
 # ---- LoRA dropout on the fine-tuning rows, row split / concatenation of Algorithm 1 ------------------------------
 def dropout_threshold(p: float) -> int:
-    """The 16-bit threshold of the dropout contract: an element is kept iff its 16-bit field is >= round(p * 65536)."""
-    return int(round(p * 65536.0))
+    """The 16-bit threshold of the dropout contract: an element is kept iff its 16-bit field is >= p * 65536 rounded
+    to the nearest integer, the product and the rounding (add one half, truncate) taken in fp32."""
+    return int(np.float32(p) * np.float32(65536.0) + np.float32(0.5))
 
 
 def dropout_keep(seed: int, t: int, k: int, threshold: int) -> bool:

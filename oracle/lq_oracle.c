@@ -263,7 +263,7 @@ int32_t lq_oracle_num_threads(void)
  *     key(t)    = hash(seed ^ hash(t))
  *     word(t,q) = hash(key(t) + q)                 one word per pair of columns, q = k / 2
  *     field     = low 16 bits of word for even k, high 16 bits for odd k
- *     m[t,k]    = field >= threshold,   threshold = round(p * 65536)   (p in steps of 2^-16)
+ *     m[t,k]    = field >= threshold,   threshold = (uint32)(p * 65536 + 0.5) in fp32   (p in steps of 2^-16)
  * The factor 1 / (1 - p) is NOT applied to x (m * x is exact in bf16, x / (1 - p) is not): it
  * travels with the scale, s' = s / (1 - p) for the token (the per-token scale above), so the
  * saved h of a fine-tuning token is (m * x) A.  The gradient with respect to x through the LoRA

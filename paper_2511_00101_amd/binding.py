@@ -43,6 +43,10 @@ _SIGNATURES = {
     "lora_segmented_backward": (ctypes.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp,
                                                _vp, _vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _i32,
                                                _vp, _vp, _i32, _vp, _sz, _vp]),
+    "lora_dropout_rows": (ctypes.c_int, [_vp, _i64, _vp, _i64, _i32, _vp, _vp, _i32, _i32, ctypes.c_uint32, ctypes.c_float, _vp]),
+    "lora_kind_offsets": (ctypes.c_int, [_vp, _vp, _vp, _i32, _vp, _vp]),
+    "lora_split_rows": (ctypes.c_int, [_vp, _i64, _i32, _vp, _i32, _vp, _vp, _i32, _vp, _vp]),
+    "lora_concat_rows": (ctypes.c_int, [_vp, _i32, _vp, _i32, _vp, _vp, _i32, _vp, _i64, _vp]),
     "lora_profile_enable": (ctypes.c_int, [_i32]),
     "lora_profile_read": (ctypes.c_int, [_vp, _vp, _i32]),
 }
@@ -326,6 +330,44 @@ def lora_segmented_backward(x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor,
         _stream(stream))
     if st != LQ_OK:
         raise LqError(st, "lora_segmented_backward")
+
+
+def lora_dropout_rows(x: torch.Tensor, out: torch.Tensor, token_adapter: torch.Tensor, token_kind: torch.Tensor,
+                      n_adapters: int, seed: int, p: float, stream=None) -> None:
+    """out = mask * x on the fine-tuning rows (copy elsewhere); out may be x itself."""
+    assert x.dtype == torch.bfloat16 and out.dtype == torch.bfloat16 and x.shape == out.shape
+    assert x.stride(1) == 1 and out.stride(1) == 1
+    st = lib().lora_dropout_rows(_ptr(x), x.stride(0), _ptr(out), out.stride(0), int(x.shape[1]), _ptr(token_adapter),
+                                 _ptr(token_kind), int(x.shape[0]), n_adapters, seed & 0xffffffff, float(p), _stream(stream))
+    if st != LQ_OK:
+        raise LqError(st, "lora_dropout_rows")
+
+
+def lora_kind_offsets(seg: SegmentTables, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    out = torch.zeros(4, dtype=torch.int32, device=seg.perm.device) if out is None else out
+    st = lib().lora_kind_offsets(_ptr(seg.seg_starts), _ptr(seg.seg_kind), _ptr(seg.n_segments), seg.max_segments, _ptr(out),
+                                 _stream(stream))
+    if st != LQ_OK:
+        raise LqError(st, "lora_kind_offsets")
+    return out
+
+
+def lora_split_rows(src: torch.Tensor, seg: SegmentTables, parts: torch.Tensor, use_perm: bool = True, stream=None) -> None:
+    assert src.dtype == torch.bfloat16 and parts.dtype == torch.bfloat16 and parts.is_contiguous() and src.stride(1) == 1
+    st = lib().lora_split_rows(_ptr(src), src.stride(0), int(src.shape[1]), _ptr(seg.perm) if use_perm else None,
+                               int(src.shape[0]), _ptr(seg.seg_starts), _ptr(seg.n_segments), seg.max_segments, _ptr(parts),
+                               _stream(stream))
+    if st != LQ_OK:
+        raise LqError(st, "lora_split_rows")
+
+
+def lora_concat_rows(parts: torch.Tensor, seg: SegmentTables, dst: torch.Tensor, use_perm: bool = True, stream=None) -> None:
+    assert dst.dtype == torch.bfloat16 and parts.dtype == torch.bfloat16 and parts.is_contiguous() and dst.stride(1) == 1
+    st = lib().lora_concat_rows(_ptr(parts), int(dst.shape[1]), _ptr(seg.perm) if use_perm else None, int(dst.shape[0]),
+                                _ptr(seg.seg_starts), _ptr(seg.n_segments), seg.max_segments, _ptr(dst), dst.stride(0),
+                                _stream(stream))
+    if st != LQ_OK:
+        raise LqError(st, "lora_concat_rows")
 
 
 # ---- plumbing between numpy bf16 bit patterns and device tensors ------------------------------------------------
