@@ -5,6 +5,7 @@
 
 namespace lq {
 namespace {
+// (process-wide and not thread-safe, as the header says: benchmarks call this from one thread)
 struct Record { int id; hipEvent_t e0, e1; };
 bool g_profile = false;
 std::vector<Record> g_records;

@@ -36,10 +36,6 @@ constexpr int kWgTiles = kWgCols / (8 * 16);  // 16-column MFMA tiles per wave
 constexpr int kStepRows = 32;   // token rows per MFMA k step
 constexpr int kBig = 0x7fffffff;
 
-#ifdef LQ_TRACE
-__device__ unsigned long long g_trace[2 * kTraceGroups * kTraceSlots];  // this file's stamp table
-#endif
-
 struct BwdParams {
     const u16* x; long long ldx;
     const u16* dy; long long lddy;
@@ -94,12 +90,10 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
     const int n0 = col_block * kWgCols;
     int* lds_row = reinterpret_cast<int*>(lds + 2 * C::BUF_BYTES);
 
-    LQ_STAMP(0, 4);
     __syncthreads();  // the previous unit's LDS reads are done
     for (int i = (int)threadIdx.x; i < kWgRows; i += kThreads) lds_row[i] = i < u.len ? row_of(p, u.pos + i) : -1;
     __syncthreads();
     const int safe_row = max(lds_row[0], 0);
-    LQ_STAMP(0, 5);
 
     // staging assignment: 16 threads cover 128 columns (256 bytes) of one row per pass
     const int y_row = (int)threadIdx.x / 16, y_piece = (int)threadIdx.x % 16;
@@ -173,10 +167,8 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
     const int n_steps = (u.len + kStepRows - 1) / kStepRows;
 #pragma unroll
     for (int dd = 0; dd < DEPTH; ++dd) stage_load(min(dd, n_steps - 1), gy[dd], gh[dd]);
-    LQ_STAMP(0, 6);
     auto step_fn = [&](int step, auto slot) {
         constexpr int J = decltype(slot)::value;
-        if (step < 16) LQ_STAMP(0, 8 + step);
         stage_store(step, step & 1, gy[J], gh[J]);
         stage_load(min(step + DEPTH, n_steps - 1), gy[J], gh[J]);  // unconditional; past the end it re-reads
         __syncthreads();
@@ -189,7 +181,6 @@ __device__ __forceinline__ void wgrad_unit(const BwdParams& p, const Unit& u, in
             if (step + decltype(slot)::value < n_steps) step_fn(step + decltype(slot)::value, slot);
         });
 
-    LQ_STAMP(0, 30);
     if (chunk_id < 0) {
         // Accumulation with the hardware's fp32 addition in memory: every element receives exactly one addition per
         // segment, so the result does not depend on timing as long as an adapter has one fine-tune segment (always
@@ -230,7 +221,6 @@ template <int NT>
 __global__ __launch_bounds__(kThreads, NT <= 2 ? 4 : 2) void wgrad_kernel(BwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    LQ_STAMP(0, 0);
     const int n_seg = uniform(min(*p.n_segments, p.max_segments));
     const SegCache c0 = load_seg_cache(p, n_seg);
     const LenClass cut = cut_class(), whole = whole_class();
@@ -319,9 +309,9 @@ size_t wpart_bytes(int n_tokens, int max_rank, int d_in, int d_out)
 template <int NT>
 hipError_t launch_wgrad(const BwdParams& p, hipStream_t st)
 {
-    static int grid = 0;
-    const size_t lds = WgCfg<NT>::LDS_BYTES;
-    if (!grid) {
+    static DeviceGrid cache;
+    constexpr size_t lds = WgCfg<NT>::LDS_BYTES;
+    const int grid = cache.get([] {
         int dev = 0, cus = 0, per_cu = 0;
         if (lds > 48 * 1024)
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<NT>),
@@ -330,25 +320,13 @@ hipError_t launch_wgrad(const BwdParams& p, hipStream_t st)
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, wgrad_kernel<NT>, kThreads, lds) != hipSuccess || per_cu <= 0)
             per_cu = 1;
-        grid = cus * per_cu;
-    }
+        return cus * per_cu;
+    });
     return launch_kernel(kKernelWgrad, wgrad_kernel<NT>, dim3(grid), dim3(kThreads), lds, st, p);
 }
 
 }  // namespace
 }  // namespace lq
-
-#ifdef LQ_TRACE
-extern "C" int lq_trace_read_backward(unsigned long long* host, int n_words)
-{
-    const size_t bytes = sizeof(unsigned long long) * 2 * lq::kTraceGroups * lq::kTraceSlots;
-    if ((size_t)n_words * sizeof(unsigned long long) < bytes) return -1;
-    void* dev = nullptr;
-    if (hipGetSymbolAddress(&dev, HIP_SYMBOL(lq::g_trace)) != hipSuccess) return -2;
-    if (hipMemcpy(host, dev, bytes, hipMemcpyDeviceToHost) != hipSuccess) return -3;
-    return hipMemset(dev, 0, bytes) == hipSuccess ? 0 : -4;
-}
-#endif
 
 // workspace: [header 4096 B][g slices: like the forward's partial h][finished g][partial weight gradients]
 extern "C" size_t lora_backward_workspace_bytes(int32_t n_tokens, int32_t n_adapters, int32_t max_rank, int32_t d_in,

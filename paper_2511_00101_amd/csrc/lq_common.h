@@ -114,36 +114,4 @@ __device__ __forceinline__ int small_div(int n, int d)
     return q;
 }
 
-// Optional in-kernel time stamps (a build with -DLQ_TRACE): thread 0 of every workgroup records the
-// 100 MHz wall clock at a few points of its first units into the table g_trace that the translation
-// unit defines ([2 kernels][kTraceGroups workgroups][kTraceSlots]); an lq_trace_read* function copies it out.
-#ifdef LQ_TRACE
-constexpr int kTraceSlots = 40, kTraceGroups = 1024;
-#define LQ_STAMP(k, id)                                                                                   \
-    do {                                                                                                  \
-        if (threadIdx.x == 0 && blockIdx.x < kTraceGroups && (id) < kTraceSlots)                          \
-            g_trace[((k) * kTraceGroups + blockIdx.x) * kTraceSlots + (id)] = wall_clock64();             \
-    } while (0)
-#ifdef LQ_TRACE_NOWAIT  // stamps never wait for outstanding memory operations: the flow as it is
-#define LQ_STAMP_WAIT(k, id) LQ_STAMP(k, id)
-#else
-#define LQ_STAMP_WAIT(k, id)                                                                              \
-    do {                                                                                                  \
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                       \
-        LQ_STAMP(k, id);                                                                                  \
-    } while (0)
-#endif
-#define LQ_UNIT_SLOT(it, j) (4 + 7 * (it) + (j))
-#define LQ_STAMP_VALUE(k, id, value)                                                                      \
-    do {                                                                                                  \
-        if (threadIdx.x == 0 && blockIdx.x < kTraceGroups && (id) < kTraceSlots)                          \
-            g_trace[((k) * kTraceGroups + blockIdx.x) * kTraceSlots + (id)] = (unsigned long long)(value); \
-    } while (0)
-#else
-#define LQ_STAMP_VALUE(k, id, value) ((void)0)
-#define LQ_STAMP(k, id) ((void)0)
-#define LQ_STAMP_WAIT(k, id) ((void)0)
-#define LQ_UNIT_SLOT(it, j) 0
-#endif
-
 }  // namespace lq

@@ -47,10 +47,6 @@ constexpr int kShortN = 512;     // expand, short unit: columns (64 lanes x 8)
 constexpr int kMaxKSplit = 8;
 constexpr int kBig = 0x7fffffff;
 
-#ifdef LQ_TRACE
-__device__ unsigned long long g_trace[2 * kTraceGroups * kTraceSlots];  // this file's stamp table
-#endif
-
 
 // ---- unit hand-out --------------------------------------------------------------------------------
 // A workgroup's first two units are fixed: its own index and that plus the grid size.  Units differ in
@@ -269,14 +265,12 @@ __device__ __forceinline__ void shrink_tall_unit(const PP& p, const Unit& u, con
     // the wait for A at the top of an iteration leaves the newest x stage in flight.  All loads are
     // unconditional (past the end they re-read the last stage), so the count in flight is static.
     constexpr int XB = NT <= 2 ? 3 : 2;
-    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 3));
     u32x4 ga[NT], xr[XB][NB][2];
     if (n_my > 0) {
         stage_load(stage_of(0), ga);
 #pragma unroll
         for (int b = 0; b < XB - 1; ++b) xload(stage_of(min(b, n_my - 1)), xr[b]);
     }
-    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 4));
     auto step = [&](int i, auto slot) {
         constexpr int J = decltype(slot)::value;
         stage_store(i & 1, ga);
@@ -297,7 +291,6 @@ __device__ __forceinline__ void shrink_tall_unit(const PP& p, const Unit& u, con
         }
     }
 
-    LQ_STAMP(0, LQ_UNIT_SLOT(u.it, 5));
     const HDest d = h_dest(p, u, s, ks, p.ksplit);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -309,7 +302,6 @@ __device__ __forceinline__ void shrink_tall_unit(const PP& p, const Unit& u, con
                 if (d.save) d.save[(long long)i * d.save_ld + j] = acc[nt][v];
             }
         }
-    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 6));
 }
 
 // =================================================================================================
@@ -370,7 +362,6 @@ __device__ __forceinline__ void shrink_short_unit(const PP& p, const Unit& u, co
                                                                           acc[mt][nt], 0, 0, 0);
     };
 
-    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 3));
     const int stride = kWaves * p.ksplit;
     int blk = ks * kWaves + w;
     if constexpr (NT <= 4) {
@@ -427,7 +418,6 @@ __device__ __forceinline__ void shrink_short_unit(const PP& p, const Unit& u, co
         mma(xa, aa);
     }
 
-    LQ_STAMP(0, LQ_UNIT_SLOT(u.it, 5));
     // Sum over the 8 waves in a fixed order: every wave parks its accumulators in LDS ([wave][register]
     // [lane]); after one barrier the 512 threads share the (register, lane) values, add the eight partial
     // sums as a balanced tree and store the result.
@@ -457,7 +447,6 @@ __device__ __forceinline__ void shrink_short_unit(const PP& p, const Unit& u, co
             if (d.save) d.save[(long long)i * d.save_ld + jj] = sum;
         }
     }
-    LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(u.it, 6));
 }
 
 // =================================================================================================
@@ -547,7 +536,6 @@ __device__ __forceinline__ void expand_long_unit(const PP& p, const Unit& u, con
     } else {
         if ((int)threadIdx.x < C::CT) lds_row[threadIdx.x] = (int)threadIdx.x < u.len ? row_of(p, u.pos + (int)threadIdx.x) : -1;
     }
-    LQ_STAMP(1, LQ_UNIT_SLOT(u.it, 1));
     const int parts = p.ksplit;
     const bool save = u.kd == LQ_SEG_FINETUNE && pj.h_out && p.h_offsets && nb_begin == 0 && parts > 1;
     float* h_dst = save ? pj.h_out + p.h_offsets[u.seg] + (long long)(u.pos - u.first) * s.rank : nullptr;
@@ -609,7 +597,6 @@ __device__ __forceinline__ void expand_long_unit(const PP& p, const Unit& u, con
             lds_h[(slot + 1) * kWave + ln] = lo;
         }
     }
-    LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 3));
     // 2. per column block: stage B, then stream y
     for (int n_block = nb_begin; n_block < nb_end; ++n_block) {
     const int n_unit = n_block * C::UN;
@@ -646,7 +633,6 @@ __device__ __forceinline__ void expand_long_unit(const PP& p, const Unit& u, con
             for (int ks = 0; ks < KSTEPS; ++ks)
                 bfrag[q][m][ks] = lds_read_transposed_16x32(lds_b + 32 * ks * C::BPITCH + w * C::WN + 32 * q + 4 * m, C::BPITCH, 8);
         }
-    if (n_block == nb_begin) LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 4));
     if constexpr (PAIRS == 2) __syncthreads();  // every wave has its fragments: the B block's LDS becomes scratch
     if (n_wave >= pj.d_out) continue;
 
@@ -806,9 +792,7 @@ __device__ __forceinline__ void expand_long_unit(const PP& p, const Unit& u, con
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    if (n_block == nb_begin) LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 5));
     }  // column blocks
-    LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(u.it, 6));
 }
 
 // =================================================================================================
@@ -975,12 +959,9 @@ __device__ __forceinline__ void shrink_phase(const PP& p, const Segs<PP>& sg, un
     // and share its L2, so the projections of one unit are handed to such workgroups (ids r, r + 8, r + 16 ... of a
     // block of 8 n_proj ids): they run side by side and the x rows they all read cross the HBM interface once.
     const int n_per = n_tall + n_small, n_all = n_proj_of(p) == 1 ? n_per : ((n_per + 7) & ~7) * n_proj_of(p);
-    LQ_STAMP(0, 2);
-    for_each_unit(p.tickets + 0, n_all, s_slot, [&](int gid, int it) {
+    for_each_unit(p.tickets + 0, n_all, s_slot, [&](int gid, int) {
         Unit u;
         SegInfo s;
-        u.it = it;
-        LQ_STAMP(0, LQ_UNIT_SLOT(it, 0));
         int id = gid;
         u.pi = 0;
         if (n_proj_of(p) > 1) {
@@ -996,8 +977,6 @@ __device__ __forceinline__ void shrink_phase(const PP& p, const Segs<PP>& sg, un
                         : is_tall   ? find_unit(p, sg, cr, chunk, kTallRows, rest, u, s)
                                     : find_unit(p, sg, cm, chunk, kShortRows, small, u, s);
         if (!ok) return;
-        LQ_STAMP_VALUE(0, LQ_UNIT_SLOT(it, 1), 1ull << 40 | (unsigned long long)(id < n_full ? 2 : is_tall ? 1 : 0) << 32 | (unsigned)u.len << 16 | (unsigned)s.rank);
-        LQ_STAMP_WAIT(0, LQ_UNIT_SLOT(it, 2));
         // the unit runs with as many 16-rank tiles as its adapter needs (at most NT, the launch's maximum)
         u16* lds_a = reinterpret_cast<u16*>(lds_raw);
         float* lds_r = reinterpret_cast<float*>(lds_raw);
@@ -1016,7 +995,6 @@ __device__ __forceinline__ void shrink_phase(const PP& p, const Segs<PP>& sg, un
             else shrink_short_unit<1>(p, u, s, ks, lds_r);
         }
     });
-    LQ_STAMP_WAIT(0, 3);
 }
 
 // GROUP = false: the instantiation for a call with one linear layer.  The compiler is told so, and everything
@@ -1029,9 +1007,7 @@ __global__ __launch_bounds__(kThreads) void shrink_kernel(KernelArg<GROUP> p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ int s_slot[2];
-    LQ_STAMP(0, 0);
     const auto sg = load_segs(p);
-    LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
 }
 
@@ -1155,7 +1131,6 @@ __device__ __forceinline__ ShortAhead short_request(const PP& p, const Segs<PP>&
     a.live = false;
     const int id = first_short_unit(e);
     if (id >= e.n_short) return a;
-    a.u.it = 4;
     a.live = find_short_unit(p, sg, e, id, a.u, a.s, a.n_block);
     if (!a.live) return a;
     const Proj q = proj_of(p, a.u.pi);
@@ -1201,7 +1176,6 @@ __device__ __forceinline__ LongAhead<KSTEPS, PAIRS> long_request(const PP& p, co
     LongAhead<KSTEPS, PAIRS> a;
     a.live = false;
     if ((int)blockIdx.x >= e.n_long) return a;
-    a.u.it = 0;
     a.live = find_long_unit(p, sg, e, (int)blockIdx.x, a.u, a.s, a.nb_begin, a.nb_end);
     if (!a.live) return a;
     const int d_out = proj_of(p, a.u.pi).d_out;
@@ -1240,30 +1214,23 @@ __device__ __forceinline__ void expand_phase(const PP& p, const Segs<PP>& sg, co
             Unit u;
             SegInfo s;
             int n_block;
-            u.it = 4;
             if (!find_short_unit(p, sg, e, id, u, s, n_block)) continue;
             expand_short_unit<false>(p, u, s, n_block, sh, unused);
         }
     }
-    LQ_STAMP_WAIT(1, 39);
 
     // long units, one per workgroup iteration
     if (e.n_chunks > 0) {
-        LQ_STAMP(1, 2);
         LongAhead<KSTEPS, PAIRS> none;
         none.live = false;
-        for_each_unit(p.tickets + 2, e.n_long, s_slot, [&](int id, int it) {
+        for_each_unit(p.tickets + 2, e.n_long, s_slot, [&](int id, int) {
             Unit u;
             SegInfo s;
             int nb_begin, nb_end;
-            u.it = it;
-            LQ_STAMP(1, LQ_UNIT_SLOT(it, 0));
             if (!find_long_unit(p, sg, e, id, u, s, nb_begin, nb_end)) return;
-            LQ_STAMP_WAIT(1, LQ_UNIT_SLOT(it, 2));
             expand_long_unit<KSTEPS, PAIRS, false>(p, u, s, nb_begin, nb_end, lds_raw, none);
         }, AHEAD ? 1 : 0);
     }
-    LQ_STAMP_WAIT(1, 3);
 }
 
 template <int KSTEPS, int PAIRS, bool GROUP>
@@ -1272,9 +1239,7 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(KernelArg<GROUP> p)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
     __shared__ int s_slot[2];
-    LQ_STAMP(1, 0);
     const auto sg = load_segs(p);
-    LQ_STAMP(1, 1);
     const ExpandPlan plan = plan_expand<KSTEPS, PAIRS>(p, sg);
     ShortAhead none;
     none.live = false;
@@ -1297,14 +1262,11 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(KernelArg<GROUP> p)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     __shared__ ShortLds sh;
     __shared__ int s_slot[2];
-    LQ_STAMP(0, 0);
     const auto sg = load_segs(p);
     // The generation is read before this workgroup arrives, hence before the last arrival can change it;
     // and after the table loads, so that their results need not wait for this slower, uncached load.
     const int gen0 = __hip_atomic_load(p.header + kBarGen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    LQ_STAMP(0, 1);
     shrink_phase<NT>(p, sg, lds_raw, s_slot);
-    LQ_STAMP(1, 0);
     // What the expand phase needs and h does not: worked out, and requested, while the workgroup waits: the plan
     // and, for every wave's first short unit, its row indices, y and the first rows of B.
     ExpandPlan plan;
@@ -1317,7 +1279,6 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(KernelArg<GROUP> p)
     });
     // The wait ran out (somewhere): h is incomplete, so y is left as it is; bit 1 of the error word says so.
     if (!opened) return;
-    LQ_STAMP(1, 1);
     expand_phase<KSTEPS, PAIRS, true>(p, sg, plan, lds_raw, sh, s_slot, ahead, lahead);
 }
 
@@ -1350,12 +1311,11 @@ int resident_grid(K kernel, size_t dyn_lds)
 template <int NT>
 int shrink_grid()
 {
-    static int grid = 0;
-    if (!grid) {
-        grid = resident_grid(shrink_kernel<NT, false>, shrink_lds_bytes<NT>());
-        grid = std::min(grid, resident_grid(shrink_kernel<NT, true>, shrink_lds_bytes<NT>()));
-    }
-    return grid;
+    static DeviceGrid cache;
+    return cache.get([] {
+        return std::min(resident_grid(shrink_kernel<NT, false>, shrink_lds_bytes<NT>()),
+                        resident_grid(shrink_kernel<NT, true>, shrink_lds_bytes<NT>()));
+    });
 }
 
 // A 128-row shrink unit streams its rows at the rate of one compute unit, so a batch has to be cut into
@@ -1381,12 +1341,11 @@ hipError_t launch_shrink(const FwdParams& p, hipStream_t st)
 template <int KSTEPS, int PAIRS>
 hipError_t launch_expand(const FwdParams& p, hipStream_t st)
 {
-    static int grid = 0;
-    const size_t lds = ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
-    if (!grid) {
-        grid = resident_grid(expand_kernel<KSTEPS, PAIRS, false>, lds);
-        grid = std::min(grid, resident_grid(expand_kernel<KSTEPS, PAIRS, true>, lds));
-    }
+    static DeviceGrid cache;
+    constexpr size_t lds = ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
+    const int grid = cache.get([] {
+        return std::min(resident_grid(expand_kernel<KSTEPS, PAIRS, false>, lds), resident_grid(expand_kernel<KSTEPS, PAIRS, true>, lds));
+    });
     if (p.n_proj == 1) return launch_kernel(kKernelExpand, expand_kernel<KSTEPS, PAIRS, false>, dim3(grid), dim3(kThreads), lds, st, static_cast<const FwdCore&>(p));
     return launch_kernel(kKernelExpand, expand_kernel<KSTEPS, PAIRS, true>, dim3(grid), dim3(kThreads), lds, st, p);
 }
@@ -1394,14 +1353,12 @@ hipError_t launch_expand(const FwdParams& p, hipStream_t st)
 template <int NT, int KSTEPS, int PAIRS>
 int fused_grid()
 {
-    static int grid = 0;
-    const size_t lds = shrink_lds_bytes<NT>() > ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES ? shrink_lds_bytes<NT>()
-                                                                                   : ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
-    if (!grid) {
-        grid = resident_grid(fused_kernel<NT, KSTEPS, PAIRS, false>, lds);
-        grid = std::min(grid, resident_grid(fused_kernel<NT, KSTEPS, PAIRS, true>, lds));
-    }
-    return grid;
+    static DeviceGrid cache;
+    constexpr size_t lds = shrink_lds_bytes<NT>() > ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES ? shrink_lds_bytes<NT>()
+                                                                                       : ExpandCfg<KSTEPS, PAIRS>::LDS_BYTES;
+    return cache.get([] {
+        return std::min(resident_grid(fused_kernel<NT, KSTEPS, PAIRS, false>, lds), resident_grid(fused_kernel<NT, KSTEPS, PAIRS, true>, lds));
+    });
 }
 
 template <int NT, int KSTEPS, int PAIRS>
@@ -1450,19 +1407,6 @@ hipError_t run_shrink_expand(FwdParams& p, int variant, hipStream_t st)
 }
 
 }  // namespace lq
-
-#ifdef LQ_TRACE
-// copies the stamp table [kernel 0 = shrink, 1 = expand][workgroup][slot] to the host and clears it
-extern "C" int lq_trace_read(unsigned long long* host, int n_words)
-{
-    const size_t bytes = sizeof(unsigned long long) * 2 * lq::kTraceGroups * lq::kTraceSlots;
-    if ((size_t)n_words * sizeof(unsigned long long) < bytes) return -1;
-    void* dev = nullptr;
-    if (hipGetSymbolAddress(&dev, HIP_SYMBOL(lq::g_trace)) != hipSuccess) return -2;
-    if (hipMemcpy(host, dev, bytes, hipMemcpyDeviceToHost) != hipSuccess) return -3;
-    return hipMemset(dev, 0, bytes) == hipSuccess ? 0 : -4;
-}
-#endif
 
 // workspace: [header 4096 B][hpart: cap x n_tokens x rstride floats]
 extern "C" size_t lora_forward_workspace_bytes(int32_t n_tokens, int32_t max_rank, int32_t d_in, int32_t d_out,
@@ -1605,7 +1549,6 @@ namespace {
 
 static __device__ __align__(256) unsigned char scratch[LQ_STATIC_WORKSPACE_BYTES];
 
-constexpr int kMaxDevices = 64;
 void* g_scratch_ptr[kMaxDevices];  // per device: address of that device's copy of `scratch` (null: not looked up yet)
 std::mutex g_scratch_mutex;
 

@@ -3,6 +3,8 @@
 
 #include <hip/hip_ext.h>
 
+#include <atomic>
+
 #include "lq_segments.h"
 
 namespace lq {
@@ -74,6 +76,25 @@ __device__ __forceinline__ Proj proj_of(const FwdParams& p, int pi)
 
 constexpr int kAllKinds = 7;
 constexpr int kFinetuneOnly = 1 << LQ_SEG_FINETUNE;
+
+// A launch grid that depends on the device (resident workgroups), worked out once per device: `compute` runs on
+// the first call on a device (two threads that race there store the same value).
+constexpr int kMaxDevices = 64;
+struct DeviceGrid {
+    std::atomic<int> grid[kMaxDevices];
+    template <class F>
+    int get(F&& compute)
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return compute();
+        int g = grid[dev].load(std::memory_order_relaxed);
+        if (g <= 0) {
+            g = compute();
+            grid[dev].store(g, std::memory_order_relaxed);
+        }
+        return g;
+    }
+};
 
 bool aligned16(const void* p);
 int rstride_for(int max_rank);

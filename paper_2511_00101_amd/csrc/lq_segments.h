@@ -65,7 +65,7 @@ __device__ __forceinline__ SegLane seg_batch(const P& p, int n_seg, const SegCac
     return load_seg_lane(p, n_seg, s0 + lane_id());
 }
 
-struct Unit { int seg, pos, len, first, seg_len, ad, kd, it, pi; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len); it: loop count (tracing); pi: projection of a grouped call (set by the caller of the lookup)
+struct Unit { int seg, pos, len, first, seg_len, ad, kd, pi; };  // chunk [pos, pos + len) of segment seg = [first, first + seg_len); pi: projection of a grouped call (set by the caller of the lookup)
 
 // A class of chunks: those of the segments with lo <= rows < hi whose kind's bit is set in `kinds`.  A
 // segment is cut into ceil(rows / per) chunks; with `even` set they all get ceil(rows / chunks) rows
