@@ -24,7 +24,12 @@
  * linearity in the scale, central differences for the gradient, a hand-written expected
  * segment table and a library stable sort for the metadata; the per-token scale by the dense
  * form with a diagonal matrix, by row-wise linearity, by its agreement with the per-adapter
- * scale when the values coincide, and by exact differences.  No function here is unpinned.
+ * scale when the values coincide, and by exact differences; the row split / concatenation by
+ * hand-built row sets; the dropout mask by its drop rates (overall, per row, per column), by the
+ * absence of correlation between columns, rows and seeds, and by what it must leave untouched.
+ * The individual BITS of the dropout mask have no outside reference (the paper fixes no
+ * generator, the mask is a contract of this code base): for them, parity unpinned.  No other
+ * function here is unpinned.
  *
  * Inputs are bfloat16 bit patterns (uint16) decoded here, independently of any other code.
  */
