@@ -137,8 +137,9 @@ def measure(p, variant, steps, warmup):
     kern = profiled(rep.lq, torch, lambda: [rep.step(warmup + i) for i in range(steps)])
     fwd_names = [k for k in kern if k != "build"]
     fwd_us = sum(kern[k]["avg_us"] for k in fwd_names)
-    if "forward_fused" in kern:
-        dom, dom_bytes = "forward_fused", work["total"]
+    one = [k for k in ONE_LAUNCH if k in kern]
+    if one:
+        dom, dom_bytes = one[0], work["total"]
     else:
         dom = "expand" if work["expand"] >= work["shrink"] else "shrink"
         dom_bytes = work[dom]
@@ -161,6 +162,7 @@ def measure(p, variant, steps, warmup):
 
 
 LAYER_STACK_NAME = "cfg5_layer_stack"
+ONE_LAUNCH = ("forward_fused", "forward_slab")   # kernel names of the variants that run a forward as one launch
 
 
 class LayerStack:
@@ -310,11 +312,11 @@ def measure_layer_stack(variant, steps, warmup, with_backward, grouped=True):
     w = st.work()
     s_per_step, per_step = timed_steps(torch, st.step, steps, warmup)
     kern = profiled(st.lq, torch, lambda: [st.step(i) for i in range(max(1, min(steps, 3)))])
-    dom = "forward_fused" if "forward_fused" in kern else "expand"
+    dom = ([k for k in ONE_LAUNCH if k in kern] or ["expand"])[0]
     n_steps_prof = max(1, min(steps, 3))
     fwd_us = sum(k["avg_us"] * k["launches"] for name, k in kern.items() if name != "build") / n_steps_prof   # per step
     per_launch = w["fwd_bytes"] / w["launches"]
-    if dom == "forward_fused":
+    if dom in ONE_LAUNCH:
         dom_bytes = per_launch
     else:   # two launches: the expand kernel carries y, B and the saved h
         n_ft = int((st.batch.token_kind == 0).sum())
@@ -408,7 +410,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--variant", choices=["auto", "split", "fused"], default="auto",
+    ap.add_argument("--variant", choices=["auto", "split", "fused", "slab"], default="auto",
                     help="auto: the single-launch (fused) variant, which is at least as fast as two launches on every "
                          "workload here; split: two launches, with the shrink / expand breakdown")
     ap.add_argument("--workload", default="cfg5",
@@ -445,7 +447,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps(dict(copy_bytes_read=src.numel(), copy_bytes_written=dst.numel(), copies=8)))
         return
-    variant = lq.LQ_VARIANT_SPLIT if args.variant == "split" else lq.LQ_VARIANT_FUSED
+    variant = dict(split=lq.LQ_VARIANT_SPLIT, slab=lq.LQ_VARIANT_SLAB).get(args.variant, lq.LQ_VARIANT_FUSED)
     makers = dict(cfg1=synth.config1, cfg2=synth.config2, cfg3=synth.config3,
                   cfg4up=lambda: synth.config4("up"), cfg4down=lambda: synth.config4("down"))
     # single-call workloads take microseconds per step: they are timed over more steps than a layer-stack step needs
@@ -492,7 +494,7 @@ def main():
         metric=METRIC, value=head["tokens_per_s"], unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
         ms_per_step=head["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
         data="synthetic",
-        config=dict(workload=workload, variant="fused" if variant == lq.LQ_VARIANT_FUSED else "split", step=step, **extra),
+        config=dict(workload=workload, variant={lq.LQ_VARIANT_FUSED: "fused", lq.LQ_VARIANT_SPLIT: "split", lq.LQ_VARIANT_SLAB: "slab"}[variant], step=step, **extra),
         roofline=head["roofline"], cpu_baseline=cpu,
         forward=dict(us=head["forward_us"], gbps=head["forward_gbps"], tflops=head["forward_tflops"],
                      hbm_frac=head["forward_hbm_frac"], mfma_frac=head["forward_mfma_frac"], kernels=head["kernels"],

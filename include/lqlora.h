@@ -61,8 +61,14 @@ enum { LQ_SEG_FINETUNE = 0, LQ_SEG_PREFILL = 1, LQ_SEG_DECODE = 2 };
  * call uses the same kind of launch for its first two steps.
  * LQ_VARIANT_SHRINK_ONLY / LQ_VARIANT_EXPAND_ONLY: the two halves of the split variant as separate
  * calls (same arguments, same workspace, shrink first), for callers that put other work between
- * them and for timing each kernel on its own. */
-enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1, LQ_VARIANT_SHRINK_ONLY = 2, LQ_VARIANT_EXPAND_ONLY = 3 };
+ * them and for timing each kernel on its own.
+ * LQ_VARIANT_SLAB: one launch in which every workgroup takes a slab of at most 32 rows of one segment
+ * through both products, so that h stays on the compute unit: no partial-h traffic and no device-wide wait
+ * (hence no residency requirement); every slab re-reads its adapter's matrices, which come from the L2 cache
+ * when slabs of one segment run side by side.  The faster variant on batches whose segments are long compared
+ * with the adapters' rank (fine-tuning and prefill rows); same results up to fp32 summation order. */
+enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1, LQ_VARIANT_SHRINK_ONLY = 2, LQ_VARIANT_EXPAND_ONLY = 3,
+       LQ_VARIANT_SLAB = 4 };
 
 #define LQ_MAX_RANK 128
 #define LQ_MAX_GROUP 4      /* linear layers per grouped call */
@@ -130,7 +136,7 @@ lq_status lora_build_segments(const int32_t* token_adapter, const uint8_t* token
  *   h_out    float, receives the UNSCALED h rows of fine-tune segments, segment g at
  *            h_out + h_offsets[g], row-major [len_g, r_a]; h_out / h_offsets may be NULL, then
  *            nothing is saved (inference-only batches)
- *   variant  one of LQ_VARIANT_*; split and fused give the same y and h_out up to fp32 summation
+ *   variant  one of LQ_VARIANT_*; split, fused and slab give the same y and h_out up to fp32 summation
  *            order; h_out may be written by either half of the split variant
  *            (LQ_VARIANT_FUSED: LQ_ERR_UNSUPPORTED if the workspace's partial-h region would reach 2 GiB,
  *            i.e. beyond about 4 million tokens at rank 128)
@@ -192,7 +198,7 @@ lq_status lora_segmented_forward_group(const void* x, int64_t ldx, int32_t d_in,
  * device array that belongs to the library (LQ_STATIC_WORKSPACE_BYTES, held by every GPU the
  * library runs on until the process ends).  The call allocates nothing and enqueues only kernels
  * (one small fill kernel that clears the counters, then the forward's).
- *   variant     LQ_VARIANT_SPLIT or LQ_VARIANT_FUSED (else LQ_ERR_INVALID_ARG)
+ *   variant     LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED or LQ_VARIANT_SLAB (else LQ_ERR_INVALID_ARG)
  *   error_word  device int32, may be NULL: receives (ORed in) the bits the workspace's word 0 would;
  *               with NULL those bits are not visible to the caller
  *   LQ_ERR_WORKSPACE if lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) exceeds
@@ -231,7 +237,8 @@ lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int
  *            either table may be NULL; with both NULL only dx is computed
  *   variant  LQ_VARIANT_FUSED: g and dx in one launch (same residency requirement as the forward's fused
  *            variant; falls back to two launches where the partial-g region would reach 2 GiB);
- *            LQ_VARIANT_SPLIT: two launches, no device-wide wait.  Other values: LQ_ERR_INVALID_ARG.
+ *            LQ_VARIANT_SPLIT: two launches, no device-wide wait; LQ_VARIANT_SLAB: g and dx in one launch of the
+ *            forward's slab variant, no device-wide wait.  Other values: LQ_ERR_INVALID_ARG.
  *   workspace lora_backward_workspace_bytes(...) bytes; its first 4096 bytes zero as for the forward.
  *   Then the weight gradients: a fine-tune segment of up to 512 rows is accumulated straight into dA / dB;
  *   a longer one is cut into row chunks whose partial sums go to the workspace and are added in chunk
@@ -318,7 +325,7 @@ lq_status lora_concat_rows(const void* parts, int32_t d, const int32_t* perm, in
  * ------------------------------------------------------------------------------------------- */
 typedef enum {
     LQ_KERNEL_BUILD = 0, LQ_KERNEL_SHRINK = 1, LQ_KERNEL_EXPAND = 2, LQ_KERNEL_FUSED = 3,
-    LQ_KERNEL_WGRAD = 4, LQ_KERNEL_WREDUCE = 5, LQ_KERNEL_IDS = 6
+    LQ_KERNEL_WGRAD = 4, LQ_KERNEL_WREDUCE = 5, LQ_KERNEL_SLAB = 6, LQ_KERNEL_IDS = 7
 } lq_kernel_id;
 
 lq_status lora_profile_enable(int32_t on);

@@ -16,7 +16,7 @@ import torch
 
 LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, LQ_ERR_HIP = range(5)
 LQ_SEG_FINETUNE, LQ_SEG_PREFILL, LQ_SEG_DECODE = 0, 1, 2
-LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED, LQ_VARIANT_SHRINK_ONLY, LQ_VARIANT_EXPAND_ONLY = 0, 1, 2, 3
+LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED, LQ_VARIANT_SHRINK_ONLY, LQ_VARIANT_EXPAND_ONLY, LQ_VARIANT_SLAB = 0, 1, 2, 3, 4
 LQ_MAX_RANK = 128
 LQ_MAX_GROUP = 4
 LQ_STATIC_WORKSPACE_BYTES = 4096 + (32 << 20)
@@ -50,7 +50,7 @@ _SIGNATURES = {
     "lora_profile_enable": (ctypes.c_int, [_i32]),
     "lora_profile_read": (ctypes.c_int, [_vp, _vp, _i32]),
 }
-KERNEL_NAMES = ("build", "shrink", "expand", "forward_fused", "wgrad", "wreduce")
+KERNEL_NAMES = ("build", "shrink", "expand", "forward_fused", "wgrad", "wreduce", "forward_slab")
 
 
 class LqError(RuntimeError):

@@ -28,7 +28,6 @@
 namespace lq {
 namespace {
 
-constexpr int kThreads = 512;
 constexpr int kWgRows = 512;    // token rows per weight-gradient unit
 constexpr int kWgCols = 256;    // columns per unit (8 waves x 32)
 constexpr int kWgTiles = kWgCols / (8 * 16);  // 16-column MFMA tiles per wave
@@ -352,7 +351,7 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     using namespace lq;
     if (n_tokens < 0 || d_in <= 0 || d_out <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1)
         return LQ_ERR_INVALID_ARG;
-    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED) return LQ_ERR_INVALID_ARG;
+    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED && variant != LQ_VARIANT_SLAB) return LQ_ERR_INVALID_ARG;
     if (!A_ptrs || !B_ptrs || !ranks || !scales || !seg_starts || !seg_adapter || !seg_kind || !n_segments)
         return LQ_ERR_INVALID_ARG;
     if (n_tokens > 0 && (!x || !dy || !dx)) return LQ_ERR_INVALID_ARG;
@@ -400,7 +399,9 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     // Whichever phase finishes g (the shrink without a split, the expand with one) also stores it to gsum.
     const bool one_launch = variant == LQ_VARIANT_FUSED && h_slices_bytes(n_tokens, max_rank) <= 0x7fffffffull;
     s1.coherent = one_launch; s1.hpart_bytes = one_launch ? (unsigned int)h_slices_bytes(n_tokens, max_rank) : 0;
-    if (one_launch) {
+    if (variant == LQ_VARIANT_SLAB) {
+        if (run_slab(s1, st) != hipSuccess) return LQ_ERR_HIP;
+    } else if (one_launch) {
         if (run_shrink_expand(s1, LQ_VARIANT_FUSED, st) != hipSuccess) return LQ_ERR_HIP;
     } else {
         if (run_shrink_expand(s1, LQ_VARIANT_SHRINK_ONLY, st) != hipSuccess) return LQ_ERR_HIP;

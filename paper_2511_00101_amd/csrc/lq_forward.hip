@@ -34,8 +34,6 @@
 namespace lq {
 namespace {
 
-constexpr int kThreads = 512;
-constexpr int kWaves = kThreads / kWave;
 constexpr int kTallMin = 33;     // shrink: segments with at least this many rows take the row-split path
 constexpr int kTallRows = 128;   // shrink, tall unit: rows (8 waves x 16)
 constexpr int kStageK = 256;     // shrink, tall unit: k elements of A staged per step
@@ -47,41 +45,6 @@ constexpr int kShortN = 512;     // expand, short unit: columns (64 lanes x 8)
 constexpr int kMaxKSplit = 8;
 constexpr int kBig = 0x7fffffff;
 
-
-// ---- unit hand-out --------------------------------------------------------------------------------
-// A workgroup's first two units are fixed: its own index and that plus the grid size.  Units differ in
-// size by more than 10x, so the later ones are drawn from a counter instead of striding; the draw is
-// issued when a unit starts and read when it ends.  (Not for the first unit: all workgroups start
-// together, 256 draws on one address take microseconds, and the loads behind a draw cannot be used
-// before it returns.)  Relaxed device-scope atomics: no data depends on the counters.  The last
-// workgroup to leave puts both counters back to zero, so they are zero between launches.  One barrier
-// per unit, which also separates the units' uses of the LDS.
-//   ctr[0] draws so far, ctr[1] workgroups that left; slot: two ints of LDS
-//   it0 = 1: the workgroup's first unit has been run already; start with the second
-template <class Body>
-__device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, Body&& body, int it0 = 0)
-{
-    const int grid = (int)gridDim.x;
-    const bool more = n_units > grid, draws = n_units > 2 * grid;
-    int id = (int)blockIdx.x + it0 * grid;
-    for (int it = it0; id < n_units; ++it) {
-        int next = id + grid;
-        if (it > 0 && threadIdx.x == 0)
-            next = draws ? 2 * grid + __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : n_units;
-        body(id, it);
-        if (!more) break;
-        if (threadIdx.x == 0) slot[it & 1] = next;
-        __syncthreads();
-        id = uniform(slot[it & 1]);
-    }
-    if (draws && threadIdx.x == 0) {
-        const int left = __hip_atomic_fetch_add(ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (left == grid - 1) {
-            __hip_atomic_store(ctr + 0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-}
 
 // In the fused variant the h slices cross the barrier between workgroups on different XCDs, whose L2
 // caches are not coherent with each other.  There they are written and read with device-scope accesses,
@@ -997,11 +960,6 @@ __device__ __forceinline__ void shrink_phase(const PP& p, const Segs<PP>& sg, un
     });
 }
 
-// GROUP = false: the instantiation for a call with one linear layer.  The compiler is told so, and everything
-// that sorts units by projection folds away (a decode batch's start is bound by its instruction count).
-// The argument of a kernel: the whole block for a grouped call, its core for a single call.
-template <bool GROUP> using KernelArg = std::conditional_t<GROUP, FwdParams, FwdCore>;
-
 template <int NT, bool GROUP>
 __global__ __launch_bounds__(kThreads) void shrink_kernel(KernelArg<GROUP> p)
 {
@@ -1289,23 +1247,7 @@ int log2_of(int v)  // v is a power of two
     return l;
 }
 int ksplit_cap(int n_tokens) { return n_tokens <= 32768 ? kMaxKSplit : 1; }
-int nt_for(int max_rank) { return max_rank <= 16 ? 1 : max_rank <= 32 ? 2 : max_rank <= 64 ? 4 : 8; }
 
-
-// number of workgroups of `kernel` that are resident at once on the current device
-template <typename K>
-int resident_grid(K kernel, size_t dyn_lds)
-{
-    int dev = 0, cus = 0, per_cu = 0;
-    if (dyn_lds > 48 * 1024)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)dyn_lds);
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, dyn_lds) != hipSuccess || per_cu <= 0)
-        per_cu = 1;
-    return cus * per_cu;
-}
 
 // (the two instantiations of a kernel, for single and for grouped calls, use the same registers and LDS, hence the same grid)
 template <int NT>
@@ -1432,7 +1374,7 @@ lq_status forward_checked(const void* x, int64_t ldx, int32_t d_in, int32_t n_pr
 {
     if (n_proj < 1 || n_proj > kMaxProj || !projs) return LQ_ERR_INVALID_ARG;
     if (n_tokens < 0 || d_in <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1) return LQ_ERR_INVALID_ARG;
-    if (variant < LQ_VARIANT_SPLIT || variant > LQ_VARIANT_EXPAND_ONLY) return LQ_ERR_INVALID_ARG;
+    if (variant < LQ_VARIANT_SPLIT || variant > LQ_VARIANT_SLAB) return LQ_ERR_INVALID_ARG;
     if (!ranks || !scales || !seg_starts || !seg_adapter || !seg_kind || !n_segments) return LQ_ERR_INVALID_ARG;
     if (n_tokens > 0 && !x) return LQ_ERR_INVALID_ARG;
     if (ldx < d_in) return LQ_ERR_INVALID_ARG;
@@ -1477,6 +1419,10 @@ lq_status forward_checked(const void* x, int64_t ldx, int32_t d_in, int32_t n_pr
     p.kinds = kAllKinds;
     p.coherent = variant == LQ_VARIANT_FUSED;
     p.hpart_bytes = (unsigned int)h_bytes;
+    if (variant == LQ_VARIANT_SLAB) {
+        p.ksplit = 1; p.ks_log2 = 0;
+        return run_slab(p, stream) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
+    }
     return run_shrink_expand(p, variant, stream) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }
 
@@ -1591,7 +1537,7 @@ extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, v
 {
     using namespace lq;
     static_assert(kWsHeaderBytes == 1024 * sizeof(int), "clear_header_kernel clears one word per thread");
-    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED) return LQ_ERR_INVALID_ARG;
+    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED && variant != LQ_VARIANT_SLAB) return LQ_ERR_INVALID_ARG;
     // (sizes first: a batch beyond the array's capacity is refused whatever else is wrong with the call)
     if (n_tokens > 0 && max_rank >= 1 && max_rank <= LQ_MAX_RANK &&
         lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) > (size_t)LQ_STATIC_WORKSPACE_BYTES)

@@ -4,6 +4,7 @@
 #include <hip/hip_ext.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "lq_segments.h"
 
@@ -73,6 +74,70 @@ __device__ __forceinline__ Proj proj_of(const FwdParams& p, int pi)
 #undef LQ_PICK
     return q;
 }
+
+constexpr int kThreads = 512;              // threads of a workgroup of the forward kernels
+constexpr int kWaves = kThreads / kWave;
+
+// ---- unit hand-out --------------------------------------------------------------------------------
+// A workgroup's first two units are fixed: its own index and that plus the grid size.  Units differ in
+// size by more than 10x, so the later ones are drawn from a counter instead of striding; the draw is
+// issued when a unit starts and read when it ends.  (Not for the first unit: all workgroups start
+// together, 256 draws on one address take microseconds, and the loads behind a draw cannot be used
+// before it returns.)  Relaxed device-scope atomics: no data depends on the counters.  The last
+// workgroup to leave puts both counters back to zero, so they are zero between launches.  One barrier
+// per unit, which also separates the units' uses of the LDS.
+//   ctr[0] draws so far, ctr[1] workgroups that left; slot: two ints of LDS
+//   it0 = 1: the workgroup's first unit has been run already; start with the second
+template <class Body>
+__device__ __forceinline__ void for_each_unit(int* ctr, int n_units, int* slot, Body&& body, int it0 = 0)
+{
+    const int grid = (int)gridDim.x;
+    const bool more = n_units > grid, draws = n_units > 2 * grid;
+    int id = (int)blockIdx.x + it0 * grid;
+    for (int it = it0; id < n_units; ++it) {
+        int next = id + grid;
+        if (it > 0 && threadIdx.x == 0)
+            next = draws ? 2 * grid + __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : n_units;
+        body(id, it);
+        if (!more) break;
+        if (threadIdx.x == 0) slot[it & 1] = next;
+        __syncthreads();
+        id = uniform(slot[it & 1]);
+    }
+    if (draws && threadIdx.x == 0) {
+        const int left = __hip_atomic_fetch_add(ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left == grid - 1) {
+            __hip_atomic_store(ctr + 0, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// GROUP = false: the instantiation for a call with one linear layer.  The compiler is told so, and everything
+// that sorts units by projection folds away (a decode batch's start is bound by its instruction count).
+// The argument of a kernel: the whole block for a grouped call, its core for a single call.
+template <bool GROUP> using KernelArg = std::conditional_t<GROUP, FwdParams, FwdCore>;
+
+
+// number of workgroups of `kernel` that are resident at once on the current device
+template <typename K>
+inline int resident_grid(K kernel, size_t dyn_lds)
+{
+    int dev = 0, cus = 0, per_cu = 0;
+    if (dyn_lds > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)dyn_lds);
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, dyn_lds) != hipSuccess || per_cu <= 0)
+        per_cu = 1;
+    return cus * per_cu;
+}
+
+inline int nt_for(int max_rank) { return max_rank <= 16 ? 1 : max_rank <= 32 ? 2 : max_rank <= 64 ? 4 : 8; }  // 16-rank tiles
+
+// The row-slab variant (LQ_VARIANT_SLAB): one launch, no partial-h buffer, no device-wide wait.
+hipError_t run_slab(const FwdParams& p, hipStream_t stream);
 
 constexpr int kAllKinds = 7;
 constexpr int kFinetuneOnly = 1 << LQ_SEG_FINETUNE;
@@ -175,7 +240,7 @@ __device__ __forceinline__ bool grid_barrier(int* header, int* err, int gen0, Ov
 // ---- optional timing of the library's own launches (lora_profile_enable / lora_profile_read) ----------------
 // When enabled, a launch goes through hipExtLaunchKernelGGL with a pair of events that receive the
 // dispatch's own start and end time stamps (what a kernel trace reports), and is filed under its id.
-enum KernelId { kKernelBuild = 0, kKernelShrink, kKernelExpand, kKernelFused, kKernelWgrad, kKernelWreduce, kKernelIds };
+enum KernelId { kKernelBuild = 0, kKernelShrink, kKernelExpand, kKernelFused, kKernelWgrad, kKernelWreduce, kKernelSlab, kKernelIds };
 bool profile_on();
 void profile_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);  // a fresh pair (null, null when full)
 
