@@ -123,7 +123,7 @@ def counter_traffic(workload, phase):
         return None
     for line in open(path):
         f = line.split()
-        if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == phase:
+        if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and (f[1] == phase or (phase in ONE_LAUNCH and (f[1] == "forward" or f[1] in ONE_LAUNCH))):
             return int(f[2])
     return None
 
@@ -312,18 +312,23 @@ def measure_layer_stack(variant, steps, warmup, with_backward, grouped=True):
     w = st.work()
     s_per_step, per_step = timed_steps(torch, st.step, steps, warmup)
     kern = profiled(st.lq, torch, lambda: [st.step(i) for i in range(max(1, min(steps, 3)))])
-    dom = ([k for k in ONE_LAUNCH if k in kern] or ["expand"])[0]
     n_steps_prof = max(1, min(steps, 3))
     fwd_us = sum(k["avg_us"] * k["launches"] for name, k in kern.items() if name != "build") / n_steps_prof   # per step
     per_launch = w["fwd_bytes"] / w["launches"]
-    if dom in ONE_LAUNCH:
-        dom_bytes = per_launch
+    one = [k for k in ONE_LAUNCH if k in kern]
+    if one:
+        # one launch per call (LQ_VARIANT_AUTO picks the slab or the fused kernel call by call): bytes and duration
+        # are averages over all the step's forward launches
+        dom, dom_bytes = " + ".join(one), per_launch
+        dom_us = sum(kern[k]["avg_us"] * kern[k]["launches"] for k in one) / sum(kern[k]["launches"] for k in one)
     else:   # two launches: the expand kernel carries y, B and the saved h
         n_ft = int((st.batch.token_kind == 0).sum())
+        dom = "expand"
         dom_bytes = sum(st.T * c["d_out"] * 4 + st.n_adapters * st.rank * c["d_out"] * 2 + n_ft * st.rank * 4 for c in st.calls) / w["launches"]
-    dom_gbps = dom_bytes / (kern[dom]["avg_us"] * 1e-6) / 1e9
+        dom_us = kern[dom]["avg_us"]
+    dom_gbps = dom_bytes / (dom_us * 1e-6) / 1e9
     name = LAYER_STACK_NAME if grouped else LAYER_STACK_NAME + "_single_calls"
-    traffic = counter_traffic(name, dom)
+    traffic = counter_traffic(name, one[0] if one else dom)
     head = dict(
         workload=name, tokens=w["tokens"], calls=w["calls"], launches=w["launches"], ms_per_step=s_per_step * 1e3, per_step=per_step,
         tokens_per_s=w["tokens"] / s_per_step, forward_us=fwd_us,
@@ -333,7 +338,7 @@ def measure_layer_stack(variant, steps, warmup, with_backward, grouped=True):
         algorithmic_bytes=w["fwd_bytes"], flops=w["fwd_flops"], kernels=kern,
         roofline=dict(bound="hbm", kernel=dom, achieved=dom_gbps, peak=HBM_PEAK_GBPS, unit="GB/s", frac=dom_gbps / HBM_PEAK_GBPS,
                       traffic=traffic, traffic_source=traffic_source(name) if traffic else None,
-                      algorithmic_bytes=dom_bytes, avg_launch_us=kern[dom]["avg_us"],
+                      algorithmic_bytes=dom_bytes, avg_launch_us=dom_us,
                       note=f"average over the step's {w['launches']} launches of 4 shapes: bytes and duration are both per launch"),
         error_word=st.error_word())
     bwd = None
@@ -411,8 +416,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--variant", choices=["auto", "split", "fused", "slab"], default="auto",
-                    help="auto: the single-launch (fused) variant, which is at least as fast as two launches on every "
-                         "workload here; split: two launches, with the shrink / expand breakdown")
+                    help="auto: LQ_VARIANT_AUTO, one launch per call (the library picks the slab or the fused kernel); slab, fused: "
+                         "that one-launch variant for every call; split: two launches, with the shrink / expand breakdown")
     ap.add_argument("--workload", default="cfg5",
                     help="headline workload: cfg5 (the 32-layer stack's forward, the largest configuration), or one of the "
                          "single-call ones cfg1, cfg2, cfg3, cfg4up, cfg4down")
@@ -447,7 +452,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps(dict(copy_bytes_read=src.numel(), copy_bytes_written=dst.numel(), copies=8)))
         return
-    variant = dict(split=lq.LQ_VARIANT_SPLIT, slab=lq.LQ_VARIANT_SLAB).get(args.variant, lq.LQ_VARIANT_FUSED)
+    variant = dict(split=lq.LQ_VARIANT_SPLIT, slab=lq.LQ_VARIANT_SLAB, fused=lq.LQ_VARIANT_FUSED)[args.variant] if args.variant != "auto" \
+        else lq.LQ_VARIANT_AUTO
     makers = dict(cfg1=synth.config1, cfg2=synth.config2, cfg3=synth.config3,
                   cfg4up=lambda: synth.config4("up"), cfg4down=lambda: synth.config4("down"))
     # single-call workloads take microseconds per step: they are timed over more steps than a layer-stack step needs
@@ -494,7 +500,8 @@ def main():
         metric=METRIC, value=head["tokens_per_s"], unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
         ms_per_step=head["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
         data="synthetic",
-        config=dict(workload=workload, variant={lq.LQ_VARIANT_FUSED: "fused", lq.LQ_VARIANT_SPLIT: "split", lq.LQ_VARIANT_SLAB: "slab"}[variant], step=step, **extra),
+        config=dict(workload=workload, variant={lq.LQ_VARIANT_FUSED: "fused", lq.LQ_VARIANT_SPLIT: "split", lq.LQ_VARIANT_SLAB: "slab",
+                             lq.LQ_VARIANT_AUTO: "auto (one launch per call: the slab or the fused kernel, picked by the library from rank and output width)"}[variant], step=step, **extra),
         roofline=head["roofline"], cpu_baseline=cpu,
         forward=dict(us=head["forward_us"], gbps=head["forward_gbps"], tflops=head["forward_tflops"],
                      hbm_frac=head["forward_hbm_frac"], mfma_frac=head["forward_mfma_frac"], kernels=head["kernels"],

@@ -66,9 +66,13 @@ enum { LQ_SEG_FINETUNE = 0, LQ_SEG_PREFILL = 1, LQ_SEG_DECODE = 2 };
  * through both products, so that h stays on the compute unit: no partial-h traffic and no device-wide wait
  * (hence no residency requirement); every slab re-reads its adapter's matrices, which come from the L2 cache
  * when slabs of one segment run side by side.  The faster variant on batches whose segments are long compared
- * with the adapters' rank (fine-tuning and prefill rows); same results up to fp32 summation order. */
+ * with the adapters' rank (fine-tuning and prefill rows); same results up to fp32 summation order.
+ * LQ_VARIANT_AUTO: the library picks between the slab and the fused variant from the host arguments alone (a pure
+ * function of max_rank and the output widths): slab for ranks up to 32 and up to 16384 output columns in all,
+ * fused otherwise (wide outputs, where re-reading B per slab costs more than the partial-h round trip; and
+ * larger ranks).  Where it picks fused, that variant's residency requirement applies. */
 enum { LQ_VARIANT_SPLIT = 0, LQ_VARIANT_FUSED = 1, LQ_VARIANT_SHRINK_ONLY = 2, LQ_VARIANT_EXPAND_ONLY = 3,
-       LQ_VARIANT_SLAB = 4 };
+       LQ_VARIANT_SLAB = 4, LQ_VARIANT_AUTO = 5 };
 
 #define LQ_MAX_RANK 128
 #define LQ_MAX_GROUP 4      /* linear layers per grouped call */
@@ -198,7 +202,7 @@ lq_status lora_segmented_forward_group(const void* x, int64_t ldx, int32_t d_in,
  * device array that belongs to the library (LQ_STATIC_WORKSPACE_BYTES, held by every GPU the
  * library runs on until the process ends).  The call allocates nothing and enqueues only kernels
  * (one small fill kernel that clears the counters, then the forward's).
- *   variant     LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED or LQ_VARIANT_SLAB (else LQ_ERR_INVALID_ARG)
+ *   variant     LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED, LQ_VARIANT_SLAB or LQ_VARIANT_AUTO (else LQ_ERR_INVALID_ARG)
  *   error_word  device int32, may be NULL: receives (ORed in) the bits the workspace's word 0 would;
  *               with NULL those bits are not visible to the caller
  *   LQ_ERR_WORKSPACE if lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) exceeds
@@ -238,7 +242,8 @@ lq_status lora_segmented_forward_static(const void* x, int64_t ldx, void* y, int
  *   variant  LQ_VARIANT_FUSED: g and dx in one launch (same residency requirement as the forward's fused
  *            variant; falls back to two launches where the partial-g region would reach 2 GiB);
  *            LQ_VARIANT_SPLIT: two launches, no device-wide wait; LQ_VARIANT_SLAB: g and dx in one launch of the
- *            forward's slab variant, no device-wide wait.  Other values: LQ_ERR_INVALID_ARG.
+ *            forward's slab variant, no device-wide wait; LQ_VARIANT_AUTO: slab or fused by the forward's rule
+ *            applied to this step (its outputs are the d_in columns of dx).  Other values: LQ_ERR_INVALID_ARG.
  *   workspace lora_backward_workspace_bytes(...) bytes; its first 4096 bytes zero as for the forward.
  *   Then the weight gradients: a fine-tune segment of up to 512 rows is accumulated straight into dA / dB;
  *   a longer one is cut into row chunks whose partial sums go to the workspace and are added in chunk

@@ -16,7 +16,7 @@ import torch
 
 LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, LQ_ERR_HIP = range(5)
 LQ_SEG_FINETUNE, LQ_SEG_PREFILL, LQ_SEG_DECODE = 0, 1, 2
-LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED, LQ_VARIANT_SHRINK_ONLY, LQ_VARIANT_EXPAND_ONLY, LQ_VARIANT_SLAB = 0, 1, 2, 3, 4
+LQ_VARIANT_SPLIT, LQ_VARIANT_FUSED, LQ_VARIANT_SHRINK_ONLY, LQ_VARIANT_EXPAND_ONLY, LQ_VARIANT_SLAB, LQ_VARIANT_AUTO = 0, 1, 2, 3, 4, 5
 LQ_MAX_RANK = 128
 LQ_MAX_GROUP = 4
 LQ_STATIC_WORKSPACE_BYTES = 4096 + (32 << 20)

@@ -351,7 +351,9 @@ extern "C" lq_status lora_segmented_backward(const void* x, int64_t ldx, const v
     using namespace lq;
     if (n_tokens < 0 || d_in <= 0 || d_out <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1)
         return LQ_ERR_INVALID_ARG;
-    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED && variant != LQ_VARIANT_SLAB) return LQ_ERR_INVALID_ARG;
+    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED && variant != LQ_VARIANT_SLAB && variant != LQ_VARIANT_AUTO)
+        return LQ_ERR_INVALID_ARG;
+    if (variant == LQ_VARIANT_AUTO) variant = auto_variant(max_rank, d_in);  // (the step's outputs are dx's columns)
     if (!A_ptrs || !B_ptrs || !ranks || !scales || !seg_starts || !seg_adapter || !seg_kind || !n_segments)
         return LQ_ERR_INVALID_ARG;
     if (n_tokens > 0 && (!x || !dy || !dx)) return LQ_ERR_INVALID_ARG;

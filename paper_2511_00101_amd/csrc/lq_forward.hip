@@ -1317,6 +1317,15 @@ hipError_t launch_fused(const FwdParams& p, hipStream_t st)
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// LQ_VARIANT_AUTO: slab or fused, from the host arguments alone.  Measured on the layer-stack shapes (5632 tokens,
+// rank 32): slab wins up to 14336 output columns in all (q 40 vs 47 us, k 25 vs 30, q+k+v 64 vs 72, down 71 vs 76, gate
+// 96 vs 101), fused beyond (gate+up 167 vs 178: a slab re-reads all of B for its 32 rows, the fused expand phase stages a
+// block of B once per 256 rows) and for ranks above 32 (the Zipf batch with ranks up to 64: 125 vs 152 us).
+int auto_variant(int max_rank, long long out_columns)
+{
+    return max_rank <= 32 && out_columns <= 16384 ? LQ_VARIANT_SLAB : LQ_VARIANT_FUSED;
+}
+
 int rstride_for(int max_rank) { return max_rank <= 32 ? 32 : max_rank <= 64 ? 64 : 128; }  // what the expand kernel reads per row
 
 size_t h_slices_bytes(int n_tokens, int max_rank)
@@ -1374,7 +1383,7 @@ lq_status forward_checked(const void* x, int64_t ldx, int32_t d_in, int32_t n_pr
 {
     if (n_proj < 1 || n_proj > kMaxProj || !projs) return LQ_ERR_INVALID_ARG;
     if (n_tokens < 0 || d_in <= 0 || n_adapters <= 0 || max_segments < 0 || max_rank < 1) return LQ_ERR_INVALID_ARG;
-    if (variant < LQ_VARIANT_SPLIT || variant > LQ_VARIANT_SLAB) return LQ_ERR_INVALID_ARG;
+    if (variant < LQ_VARIANT_SPLIT || variant > LQ_VARIANT_AUTO) return LQ_ERR_INVALID_ARG;
     if (!ranks || !scales || !seg_starts || !seg_adapter || !seg_kind || !n_segments) return LQ_ERR_INVALID_ARG;
     if (n_tokens > 0 && !x) return LQ_ERR_INVALID_ARG;
     if (ldx < d_in) return LQ_ERR_INVALID_ARG;
@@ -1391,6 +1400,12 @@ lq_status forward_checked(const void* x, int64_t ldx, int32_t d_in, int32_t n_pr
     for (int k = 0; k < n_proj; ++k)
         if ((projs[k].d_out % 8) || (projs[k].ldy % 8) || !aligned16(projs[k].y)) return LQ_ERR_UNSUPPORTED;
     const size_t h_bytes = (size_t)n_proj * h_slices_bytes(n_tokens, max_rank);
+    if (variant == LQ_VARIANT_AUTO) {
+        long long columns = 0;
+        for (int k = 0; k < n_proj; ++k) columns += projs[k].d_out;
+        variant = auto_variant(max_rank, columns);
+        if (variant == LQ_VARIANT_FUSED && h_bytes > 0x7fffffffull) variant = LQ_VARIANT_SLAB;  // (beyond the fused variant's reach)
+    }
     if (!workspace || workspace_bytes < (size_t)kWsHeaderBytes + h_bytes || !aligned16(workspace)) return LQ_ERR_WORKSPACE;
     // the fused variant addresses the partial-h region through a buffer descriptor with 32-bit offsets
     if (variant == LQ_VARIANT_FUSED && h_bytes > 0x7fffffffull) return LQ_ERR_UNSUPPORTED;
@@ -1537,7 +1552,8 @@ extern "C" lq_status lora_segmented_forward_static(const void* x, int64_t ldx, v
 {
     using namespace lq;
     static_assert(kWsHeaderBytes == 1024 * sizeof(int), "clear_header_kernel clears one word per thread");
-    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED && variant != LQ_VARIANT_SLAB) return LQ_ERR_INVALID_ARG;
+    if (variant != LQ_VARIANT_SPLIT && variant != LQ_VARIANT_FUSED && variant != LQ_VARIANT_SLAB && variant != LQ_VARIANT_AUTO)
+        return LQ_ERR_INVALID_ARG;
     // (sizes first: a batch beyond the array's capacity is refused whatever else is wrong with the call)
     if (n_tokens > 0 && max_rank >= 1 && max_rank <= LQ_MAX_RANK &&
         lora_forward_workspace_bytes(n_tokens, max_rank, d_in, d_out, variant) > (size_t)LQ_STATIC_WORKSPACE_BYTES)

@@ -163,6 +163,7 @@ struct DeviceGrid {
 
 bool aligned16(const void* p);
 int rstride_for(int max_rank);
+int auto_variant(int max_rank, long long out_columns);  // LQ_VARIANT_AUTO's choice: LQ_VARIANT_SLAB or LQ_VARIANT_FUSED
 size_t h_slices_bytes(int n_tokens, int max_rank);   // bytes of the partial-h region of a workspace
 
 // Fills p.ksplit and enqueues: variant LQ_VARIANT_SPLIT / _FUSED / _SHRINK_ONLY / _EXPAND_ONLY.

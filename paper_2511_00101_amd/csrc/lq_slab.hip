@@ -1,335 +1,22 @@
 // Row-slab variant of the segmented multi-adapter LoRA forward (Section 3.3): one launch in which a
-// workgroup takes a slab of at most 32 rows of one segment through BOTH products,
-//     h = x A_a^T   (all of d_in; the 8 waves take alternate 64-wide k blocks and add their results in LDS)
-//     y += s h B_a  (the 8 waves take alternate 64-column blocks)
-// so that h never leaves the compute unit: no partial-h buffer, no device-wide wait, and both phases are
-// spread over the machine the same way.  The price is that every slab re-reads its adapter's matrices; they
-// come from the L2 cache (slabs of one segment run side by side), which the measured access pattern bears:
-// 256 workgroups that each stream 22 rows of x and y and re-read 512 KB of A and B run at 4.3 TB/s of
-// algorithmic bytes, against 4.9 TB/s without the re-reads.
-//
-// All global accesses are row-wise 16-byte accesses (an instruction covers 8 rows x 128 contiguous bytes);
-// data reaches the MFMA operand layout through slabs of LDS that belong to one wave, so the streaming loops
-// contain no workgroup barrier.  Loads are issued one block ahead into the registers the previous block has
-// just left (x and y: two blocks ahead), unconditionally and from clamped addresses, so that the number in
-// flight is static.
-#include "lq_internal.h"
+// workgroup takes a slab of at most 32 rows of one segment through BOTH products, so that h never leaves the
+// compute unit: no partial-h buffer, no device-wide wait, and both phases are spread over the machine the same
+// way.  The price is that every slab re-reads its adapter's matrices; they come from the L2 cache (slabs of
+// one segment run side by side), which the measured access pattern bears: 256 workgroups that each stream 22
+// rows of x and y and re-read 512 KB of A and B run at 4.3 TB/s of algorithmic bytes, against 4.9 TB/s without
+// the re-reads.
+#include "lq_slab.h"
 
 namespace lq {
 namespace {
 
-constexpr int kSlabRows = 32;          // rows of a unit: two 16-row MFMA tiles
-constexpr int kKB = 64;                // k elements per block (phase 1), columns per block (phase 2)
-constexpr int kPitch = kKB + 8;        // elements per slab row (16-byte aligned, bank spread)
-constexpr int kChunk = 32 * kPitch;    // elements of a 32-row slab
-constexpr int kBig = 0x7fffffff;
 constexpr int kMaxParts = 8;           // column parts a short batch's units are cut into
 constexpr size_t kHfragBytes = 16384;  // [projection of the pass][row tile][k step][high | low][lane] x 16 B
-constexpr size_t kWaveBytes = 16384;   // LDS of one wave: its slabs, later its share of the reduction buffer
-constexpr int kStashInts = 24;         // per lane: the segment tables and chunk counts a wave holds in registers
-constexpr size_t kStashOffset = kHfragBytes + kWaves * kWaveBytes + 2 * kSlabRows * sizeof(int);
-constexpr size_t kSlabLdsBytes = kStashOffset + (size_t)kStashInts * kWave * sizeof(int);
-
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// 16 bytes of an adapter matrix at element offset `off` (< 2^31): a wave-uniform base and a 32-bit byte offset per
-// lane, the form that needs no 64-bit address arithmetic in vector registers
-__device__ __forceinline__ u32x4 load_at(gconst_u16 base, unsigned int off)
-{
-    typedef const __attribute__((address_space(1))) char* gconst_char;
-    return *reinterpret_cast<gconst_u32x4>(reinterpret_cast<gconst_char>(base) + (size_t)(off * 2u));
-}
-
-// projections a pass can hold in registers: its accumulators are NP x 2 x NT MFMA tiles
-template <int NT> constexpr int pass_projections() { return NT == 1 ? kMaxProj : NT == 2 ? 3 : 1; }
-
-// =================================================================================================
-// phase 1: acc[q][mt][nt] = this wave's share of x[rows] . A_q[ranks]^T for the NP projections of the pass
-// (D[row][rank]: lane (c, kg) receives rows 4 kg .. + 3 of tile mt, rank c of tile nt)
-// =================================================================================================
-template <int NT, int NP, int MT, class PP>
-__device__ __forceinline__ void slab_shrink(const PP& p, const Unit& u, const SegInfo (&s)[NP], const int* lds_row,
-                                            u16* slab, f32x4 (&acc)[NP][2][NT])
-{
-    constexpr int NJ = 2 * MT;            // load instructions per block of x (8 rows each)
-    constexpr int NA = 2 * NT;            // load instructions per block of one A (8 rank rows each)
-    constexpr int NCH = (NT + 1) / 2;     // 32-rank chunks of A
-    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, kg = lane >> 4;
-    const int r8 = lane >> 3, piece = lane & 7;
-    u16* xs = slab;             // [32][kPitch]
-    u16* as = slab + kChunk;    // [2][32][kPitch]
-    const int rank = s[0].rank;
-
-    const int nblk = (p.d_in + kKB - 1) / kKB;
-    const int n_mine = w < nblk ? (nblk - w + kWaves - 1) / kWaves : 0;  // blocks w, w + 8, ...
-    if (n_mine == 0) return;  // wave uniform
-    // Slabs that run side by side would otherwise sweep the same k range in step, which (with a power-of-two row
-    // pitch) keeps hitting the same few channels; so every slab starts its sweep at a different block.
-    const int rot = (int)(((unsigned)u.pos * 5u) % (unsigned)nblk);
-    auto k_of = [&](int j) {  // first k of this wave's j-th block (past the end: the last one again)
-        int b = w + kWaves * min(j, n_mine - 1) + rot;
-        if (b >= nblk) b -= nblk;
-        return b * kKB;
-    };
-
-    const int safe_row = max(lds_row[0], 0);
-    const u16* xrow[NJ];
-#pragma unroll
-    for (int i = 0; i < NJ; ++i) {
-        const int r = lds_row[r8 + 8 * i];
-        xrow[i] = p.x + (long long)(r >= 0 ? r : safe_row) * p.ldx + piece * 8;
-    }
-    unsigned int aoff[NA];
-#pragma unroll
-    for (int i = 0; i < NA; ++i) aoff[i] = (unsigned int)(min(r8 + 8 * i, rank - 1) * p.d_in);
-
-    // a lane's 8 columns lie wholly inside or wholly beyond d_in; beyond, it re-reads column 0 (and A counts as zero)
-    auto col_of = [&](int k0) { return k0 + piece * 8 < p.d_in ? k0 : -piece * 8; };
-    constexpr int XS = NP >= 3 ? 1 : 2;  // register sets of x = blocks it is requested ahead (one where registers are short)
-    u32x4 xv[XS][NJ];
-    auto x_load = [&](int j, u32x4 (&v)[NJ]) {
-        const int kc = col_of(k_of(j));
-#pragma unroll
-        for (int i = 0; i < NJ; ++i) v[i] = *reinterpret_cast<const u32x4*>(xrow[i] + kc);
-    };
-    // The A stream: a block's A is NC chunks (projection q, 32 ranks ch), four load instructions each; chunk n of
-    // block j is number j NC + n of the stream, lives in register set (j NC + n) % 2 and goes through LDS buffer
-    // (j NC + n) % 2.  A set is refilled with the chunk two further on as soon as it has been written to LDS.
-    constexpr int NC = NP * NCH;
-    constexpr int NL = NA < 4 ? NA : 4;  // load instructions per chunk
-    u32x4 av[2][NL];
-    auto a_load = [&](int j, auto chunk, u32x4 (&v)[NL]) {
-        constexpr int N = decltype(chunk)::value;  // chunk N of block j (N may run past NC: the blocks further on)
-        constexpr int q = (N % NC) / NCH, ch = (N % NC) % NCH;
-        const unsigned int kc = (unsigned int)(col_of(k_of(j + N / NC)) + piece * 8);  // >= 0
-#pragma unroll
-        for (int i2 = 0; i2 < NL; ++i2) v[i2] = load_at(s[q].A, aoff[ch * 4 + i2] + kc);
-    };
-    // (loads return in order, so they are issued in the order they are consumed, and the scheduler is kept from
-    // reordering them: a wait for the oldest then leaves all younger ones in flight)
-    x_load(0, xv[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    a_load(0, std::integral_constant<int, 0>{}, av[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    a_load(0, std::integral_constant<int, 1>{}, av[1]);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (XS == 2) x_load(1, xv[1]);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // (live: false for the block that pads an odd count to the pair the loop below runs; it adds zeros)
-    auto block = [&](int j, auto slot, bool live_block) {
-        constexpr int J = decltype(slot)::value;
-        // x of block j: registers -> slab -> fragments; the registers take block j + XS
-#pragma unroll
-        for (int i = 0; i < NJ; ++i) *reinterpret_cast<u32x4*>(xs + (r8 + 8 * i) * kPitch + piece * 8) = xv[J % XS][i];
-        x_load(j + XS, xv[J % XS]);
-        __builtin_amdgcn_sched_barrier(0);
-        wave_sync();
-        u32x4 xf[MT][2];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) xf[mt][h] = *reinterpret_cast<const u32x4*>(xs + (mt * 16 + c) * kPitch + 32 * h + kg * 8);
-        const bool in_cur = live_block && k_of(j) + piece * 8 < p.d_in;
-        auto chunk = [&](auto index) {
-            constexpr int N = decltype(index)::value;
-            constexpr int q = N / NCH, ch = N % NCH, S = (J * NC + N) & 1;
-            u16* buf = as + S * kChunk;
-#pragma unroll
-            for (int i2 = 0; i2 < NL; ++i2) {
-                constexpr u32x4 zero = {0u, 0u, 0u, 0u};
-                const bool live = in_cur && r8 + 8 * (ch * 4 + i2) < rank;
-                *reinterpret_cast<u32x4*>(buf + (r8 + 8 * i2) * kPitch + piece * 8) = live ? av[S][i2] : zero;
-            }
-            a_load(j, std::integral_constant<int, N + 2>{}, av[S]);
-            __builtin_amdgcn_sched_barrier(0);
-            wave_sync();
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                constexpr int dummy = 0;
-                const int nt = ch * 2 + t < NT ? ch * 2 + t : dummy;  // (keeps the dead branch's index inside the array)
-                if (ch * 2 + t < NT) {
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const u32x4 af = *reinterpret_cast<const u32x4*>(buf + (t * 16 + c) * kPitch + 32 * h + kg * 8);
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            acc[q][mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(xf[mt][h]), as_bf16x8(af),
-                                                                                     acc[q][mt][nt], 0, 0, 0);
-                    }
-                }
-            }
-        };
-        // (a buffer is rewritten two chunks later, behind the wave_sync of the chunk in between; with a single
-        // chunk per block, behind the one at the end of the block)
-        chunk(std::integral_constant<int, 0>{});
-        if constexpr (NC > 1) chunk(std::integral_constant<int, 1>{});
-        if constexpr (NC > 2) chunk(std::integral_constant<int, 2>{});
-        if constexpr (NC > 3) chunk(std::integral_constant<int, 3>{});
-        static_assert(NC <= 4, "the chunks of a block are listed by name");
-        wave_sync();  // the x slab is rewritten by the next block
-    };
-    // (pairs of blocks with a single exit: the accumulators stay where they are across the loop)
-    for (int j = 0; j < n_mine; j += 2) {
-        block(j, std::integral_constant<int, 0>{}, true);
-        block(j + 1, std::integral_constant<int, 1>{}, j + 1 < n_mine);
-    }
-}
-
-// =================================================================================================
-// phase 2 for one projection: y[rows][columns of the part] += (scaled h, as bf16 high + low fragments) . B
-// D[column][row] with the columns of two MFMA tiles interleaved, so that a lane ends up with 4 consecutive
-// columns of a row; every 16-row tile of products makes a round trip through the wave's 4 KB slab to reach the
-// row-wise layout y is accessed in.
-// =================================================================================================
-template <int NT, int MT, class PP>
-__device__ __forceinline__ void slab_expand(const PP&, const Unit& u, const SegInfo& s, const Proj& pj,
-                                            const int* lds_row, const u32x4* hf, u16* bs, float* ds, int blk_begin,
-                                            int blk_end)
-{
-    constexpr int NJ = 2 * MT;
-    constexpr int NB = 2 * NT;
-    constexpr int KSTEPS = (NT + 1) / 2;
-    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave), c = lane & 15, g = lane >> 4;
-    const int r8 = lane >> 3, piece = lane & 7;
-    const int nblk = blk_end - blk_begin;
-    const int n_mine = w < nblk ? (nblk - w + kWaves - 1) / kWaves : 0;
-    if (n_mine == 0) return;  // wave uniform
-    const int rot = (int)(((unsigned)u.pos * 3u) % (unsigned)nblk);
-    auto n_of = [&](int j) {  // first column of this wave's j-th block (past the end: the last one again)
-        int b = w + kWaves * min(j, n_mine - 1) + rot;
-        if (b >= nblk) b -= nblk;
-        return (blk_begin + b) * kKB;
-    };
-    const int safe_row = max(lds_row[0], 0);
-    int row[NJ];
-    u16* yrow[NJ];
-#pragma unroll
-    for (int i = 0; i < NJ; ++i) {
-        row[i] = lds_row[r8 + 8 * i];
-        yrow[i] = pj.y + (long long)(row[i] >= 0 ? row[i] : safe_row) * pj.ldy;
-    }
-    unsigned int boff[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) boff[i] = (unsigned int)(min(r8 + 8 * i, s.rank - 1) * pj.d_out);
-
-    // The B stream: a block's B is KSTEPS chunks of 32 rank rows, four load instructions each; chunk ks of block j is
-    // number j KSTEPS + ks of the stream and lives in register set (j KSTEPS + ks) % 2; a set is refilled with the
-    // chunk two further on as soon as it has been written to LDS.
-    constexpr int NL = NB < 4 ? NB : 4;  // load instructions per chunk
-    u32x4 yv[2][NJ], bv[2][NL];
-    auto y_load = [&](int j, u32x4 (&v)[NJ]) {
-        const int n_ld = min(n_of(j) + 8 * piece, pj.d_out - 8);
-#pragma unroll
-        for (int i = 0; i < NJ; ++i) v[i] = *reinterpret_cast<const u32x4*>(yrow[i] + n_ld);
-    };
-    auto b_load = [&](int j, auto chunk, u32x4 (&v)[NL]) {
-        constexpr int N = decltype(chunk)::value;
-        const unsigned int n_ld = (unsigned int)min(n_of(j + N / KSTEPS) + 8 * piece, pj.d_out - 8);
-#pragma unroll
-        for (int i2 = 0; i2 < NL; ++i2) v[i2] = load_at(s.B, boff[(N % KSTEPS) * 4 + i2] + n_ld);
-    };
-    // (issued in the order they are consumed, see phase 1; with KSTEPS > 1 both chunks belong to block 0)
-    b_load(0, std::integral_constant<int, 0>{}, bv[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (KSTEPS == 1) {
-        y_load(0, yv[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        b_load(0, std::integral_constant<int, 1>{}, bv[1]);
-    } else {
-        b_load(0, std::integral_constant<int, 1>{}, bv[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        y_load(0, yv[0]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    y_load(1, yv[1]);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // (live: false for the block that pads an odd count to the pair the loop below runs; it stores nothing)
-    auto block = [&](int j, auto slot, bool live_block) {
-        constexpr int J = decltype(slot)::value;
-        const int n_c = n_of(j) + 8 * piece;
-        // B of block j, 32 ranks at a time: registers -> slab -> transposed fragments
-        u32x4 bfrag[2][2][KSTEPS];
-        auto chunk = [&](auto index) {
-            constexpr int ks = decltype(index)::value, S = (J * KSTEPS + ks) & 1;
-#pragma unroll
-            for (int i2 = 0; i2 < 4; ++i2) {
-                constexpr u32x4 zero = {0u, 0u, 0u, 0u};
-                u32x4 v = zero;  // rank rows beyond the adapter's (and beyond the tiles of this launch) are zero
-                if (i2 < NL && r8 + 8 * (ks * 4 + i2) < s.rank) v = bv[S][i2 < NL ? i2 : 0];
-                *reinterpret_cast<u32x4*>(bs + (r8 + 8 * i2) * kPitch + piece * 8) = v;
-            }
-            b_load(j, std::integral_constant<int, ks + 2>{}, bv[S]);
-            __builtin_amdgcn_sched_barrier(0);
-            wave_sync();
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-#pragma unroll
-                for (int m = 0; m < 2; ++m)
-                    // lane c: column 32 q + 8 (c / 4) + 4 m + c % 4 of the block, rank rows 32 ks + 8 g .. + 7
-                    bfrag[q][m][ks] = lds_read_transposed_16x32(bs + 32 * q + 4 * m, kPitch, 8);
-            wave_sync();  // the slab is rewritten by the next chunk
-        };
-        chunk(std::integral_constant<int, 0>{});
-        if constexpr (KSTEPS > 1) chunk(std::integral_constant<int, 1>{});
-        if constexpr (KSTEPS > 2) chunk(std::integral_constant<int, 2>{});
-        if constexpr (KSTEPS > 3) chunk(std::integral_constant<int, 3>{});
-        static_assert(KSTEPS <= 4, "the chunks of a block are listed by name");
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            u32x4 h_hi[KSTEPS], h_lo[KSTEPS];
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                h_hi[ks] = hf[((t * KSTEPS + ks) * 2 + 0) * kWave + lane];
-                h_lo[ks] = hf[((t * KSTEPS + ks) * 2 + 1) * kWave + lane];
-            }
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-#pragma unroll
-                for (int m = 0; m < 2; ++m) {
-                    f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < KSTEPS; ++ks) {
-                        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bfrag[q][m][ks]), as_bf16x8(h_lo[ks]), d, 0, 0, 0);
-                        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(bfrag[q][m][ks]), as_bf16x8(h_hi[ks]), d, 0, 0, 0);
-                    }
-                    // row c of the tile, columns 32 q + 8 g + 4 m .. + 3 = 16-byte chunk 8 q + 2 g + m (swizzled with the row)
-                    *reinterpret_cast<f32x4*>(ds + c * 64 + (((8 * q + 2 * g + m) ^ c) & 15) * 4) = d;
-                }
-            wave_sync();
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-                const int i = 2 * t + jj, rt = 8 * jj + r8;  // load instruction i of the block = row rt of tile t
-                const f32x4 d0 = *reinterpret_cast<const f32x4*>(ds + rt * 64 + (((2 * piece) ^ rt) & 15) * 4);
-                const f32x4 d1 = *reinterpret_cast<const f32x4*>(ds + rt * 64 + (((2 * piece + 1) ^ rt) & 15) * 4);
-                if (live_block && row[i] >= 0 && t * 16 + rt < u.len && n_c < pj.d_out) {
-                    float yf[8];
-                    unpack8(yv[J][i], yf);
-                    u32x4 o;
-                    o.x = pack_bf16x2(yf[0] + d0[0], yf[1] + d0[1]);
-                    o.y = pack_bf16x2(yf[2] + d0[2], yf[3] + d0[3]);
-                    o.z = pack_bf16x2(yf[4] + d1[0], yf[5] + d1[1]);
-                    o.w = pack_bf16x2(yf[6] + d1[2], yf[7] + d1[3]);
-                    *reinterpret_cast<u32x4*>(pj.y + (long long)row[i] * pj.ldy + n_c) = o;
-                }
-            }
-            wave_sync();  // the slab is rewritten by the next tile
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        y_load(j + 2, yv[J]);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    for (int j = 0; j < n_mine; j += 2) {
-        block(j, std::integral_constant<int, 0>{}, true);
-        block(j + 1, std::integral_constant<int, 1>{}, j + 1 < n_mine);
-    }
-}
+// LDS of the kernel: the h fragments, the waves' shares, the unit's row indices and scales, the stashed tables
+constexpr size_t kWorkOffset = kHfragBytes;
+constexpr size_t kRowsOffset = kWorkOffset + kWaves * kWaveBytes;
+constexpr size_t kStashOffset = kRowsOffset + 2 * kSlabRows * sizeof(int);
+constexpr size_t kSlabLdsBytes = kStashOffset + kStashBytes;
 
 // =================================================================================================
 // one pass of a unit: NP projections (pi0 ..) through phase 1, the sum over the waves, and phase 2
@@ -339,30 +26,15 @@ __device__ __forceinline__ void slab_pass(const PP& p, const Unit& u0, const Seg
                                           unsigned char* lds)
 {
     constexpr int KSTEPS = (NT + 1) / 2;
-    constexpr int REGS = NP * 2 * NT * 4;  // accumulator registers of a wave
-    static_assert((size_t)REGS * kWave * sizeof(float) <= kWaveBytes, "a wave's accumulators fit its share of the LDS");
     static_assert((size_t)NP * 2 * KSTEPS * 2 * kWave * 16 <= kHfragBytes, "the pass's h fragments fit");
-    static_assert((size_t)3 * kChunk * sizeof(u16) <= kWaveBytes, "a wave's slabs fit its share of the LDS");
     u32x4* hfrag = reinterpret_cast<u32x4*>(lds);
-    unsigned char* work = lds + kHfragBytes;
-    int* lds_row = reinterpret_cast<int*>(lds + kHfragBytes + kWaves * kWaveBytes);
+    unsigned char* work = lds + kWorkOffset;
+    const int* lds_row = reinterpret_cast<const int*>(lds + kRowsOffset);
     const float* lds_scale = reinterpret_cast<const float*>(lds_row + kSlabRows);
-    const int lane = lane_id(), w = uniform((int)threadIdx.x / kWave);
+    const int w = uniform((int)threadIdx.x / kWave);
 
     SegInfo s[NP];
-    bool ok = true;
-#pragma unroll
-    for (int q = 0; q < NP; ++q) {
-        if (pi0 + q == 0) {
-            s[q] = s0;
-        } else {
-            Unit uq = u0;
-            uq.pi = pi0 + q;
-            s[q] = load_adapter(p, uq);
-        }
-        ok = ok && s[q].ok;
-    }
-    if (!ok) return;  // workgroup uniform; the error bit is set
+    if (!slab_adapters(p, u0, s0, pi0, s)) return;  // workgroup uniform; the error bit is set
     const int rank = s[0].rank;
 
     // the fragments start as zeros: rows and ranks beyond the live ones stay that way
@@ -372,69 +44,29 @@ __device__ __forceinline__ void slab_pass(const PP& p, const Unit& u0, const Seg
         hfrag[threadIdx.x] = zero;
         hfrag[threadIdx.x + kThreads] = zero;
     }
-
-    f32x4 acc[NP][2][NT];
-#pragma unroll
-    for (int q = 0; q < NP; ++q)
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[q][mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    u16* slab = reinterpret_cast<u16*>(work + (size_t)w * kWaveBytes);
-    const bool one_tile = u0.len <= 16;  // workgroup uniform
-    if (one_tile) slab_shrink<NT, NP, 1>(p, u0, s, lds_row, slab, acc);
-    else slab_shrink<NT, NP, 2>(p, u0, s, lds_row, slab, acc);
-
-    // Sum over the 8 waves in a fixed order: every wave parks its accumulators in its own share of the LDS
-    // ([register][lane]); after one barrier the 512 threads share the (register, lane) values, add the eight
-    // partial sums as a balanced tree, store h_out (fine-tune segments) and write the scaled value as bf16 high
-    // and low parts into the fragments phase 2 reads.
-    {
-        float* mine = reinterpret_cast<float*>(slab) + lane;
-#pragma unroll
-        for (int q = 0; q < NP; ++q)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) mine[(((q * 2 + mt) * NT + nt) * 4 + v) * kWave] = acc[q][mt][nt][v];
-    }
-    __syncthreads();
-    {
-        u16* hf16 = reinterpret_cast<u16*>(hfrag);
-        // thread (wave w, lane) takes register 8 it + w of lane `lane`: NP * NT iterations, projection it / NT
-#pragma unroll
-        for (int it = 0; it < NP * NT; ++it) {
-            constexpr int PER_WAVE = (int)(kWaveBytes / sizeof(float));
-            const int q = it / NT;                 // compile-time per iteration
-            const int r = 8 * (it % NT) + w;       // register within the projection: (mt * NT + nt) * 4 + v
-            const int v = r & 3, nt = (r >> 2) % NT, mt = (r >> 2) / NT;
-            const float* at = reinterpret_cast<const float*>(work) + (q * 2 * NT * 4 + r) * kWave + lane;
-            float t[kWaves];
-#pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) t[ww] = at[ww * PER_WAVE];
-            const float sum = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
-            const int i = mt * 16 + (lane >> 4) * 4 + v, j = nt * 16 + (lane & 15);
-            if (i < u0.len && j < rank) {
-                const Proj pj = proj_of(p, pi0 + q);
-                if (u0.kd == LQ_SEG_FINETUNE && pj.h_out && p.h_offsets && part == 0)
-                    pj.h_out[p.h_offsets[u0.seg] + (long long)(u0.pos - u0.first + i) * rank + j] = sum;
-                const float scaled = sum * lds_scale[i];
-                const unsigned int hi = pack_bf16x2(scaled, 0.f) & 0xffffu;
-                const unsigned int lo = pack_bf16x2(scaled - bf16_lo(hi), 0.f) & 0xffffu;
-                // fragment (projection q, row tile i / 16, k step j / 32): lane (j % 32 / 8) * 16 + i % 16 holds ranks 8 (j / 8) .. + 7
-                const int slot = ((q * 2 + (i >> 4)) * KSTEPS + (j >> 5)) * 2;
-                const int ln = ((j >> 3) & 3) * 16 + (i & 15);
-                hf16[((slot + 0) * kWave + ln) * 8 + (j & 7)] = (u16)hi;
-                hf16[((slot + 1) * kWave + ln) * 8 + (j & 7)] = (u16)lo;
-            }
+    // phase 1; every finished h element goes to h_out (fine-tune segments) and, scaled and split into a bf16 high and
+    // low part, into the fragments phase 2 reads
+    u16* hf16 = reinterpret_cast<u16*>(hfrag);
+    const bool save = u0.kd == LQ_SEG_FINETUNE && p.h_offsets && part == 0;
+    slab_shrink_sum<NT, NP>(p, u0, s, lds_row, work, [&](auto qc, int i, int j, float sum) {
+        constexpr int q = decltype(qc)::value;
+        if (save) {
+            float* h_out = proj_of(p, pi0 + q).h_out;
+            if (h_out) h_out[p.h_offsets[u0.seg] + (long long)(u0.pos - u0.first + i) * rank + j] = sum;
         }
-    }
+        const float scaled = sum * lds_scale[i];
+        const unsigned int hi = pack_bf16x2(scaled, 0.f) & 0xffffu;
+        const unsigned int lo = pack_bf16x2(scaled - bf16_lo(hi), 0.f) & 0xffffu;
+        // fragment (projection q, row tile i / 16, k step j / 32): lane (j % 32 / 8) * 16 + i % 16 holds ranks 8 (j / 8) .. + 7
+        const int slot = ((q * 2 + (i >> 4)) * KSTEPS + (j >> 5)) * 2;
+        const int ln = ((j >> 3) & 3) * 16 + (i & 15);
+        hf16[((slot + 0) * kWave + ln) * 8 + (j & 7)] = (u16)hi;
+        hf16[((slot + 1) * kWave + ln) * 8 + (j & 7)] = (u16)lo;
+    });
     __syncthreads();
 
-    u16* bs = slab;
-    float* ds = reinterpret_cast<float*>(slab + kChunk);
+    u16* bs = reinterpret_cast<u16*>(work + (size_t)w * kWaveBytes);
+    float* ds = reinterpret_cast<float*>(bs + kChunk);
     static_assert(kChunk * sizeof(u16) % 16 == 0, "the D slab is 16-byte aligned");
 #pragma unroll
     for (int q = 0; q < NP; ++q) {
@@ -442,7 +74,7 @@ __device__ __forceinline__ void slab_pass(const PP& p, const Unit& u0, const Seg
         const int nblk = (pj.d_out + kKB - 1) / kKB;
         const int begin = small_div(part * nblk, parts), end = small_div((part + 1) * nblk, parts);
         const u32x4* hf = hfrag + q * 2 * KSTEPS * 2 * kWave;
-        if (one_tile) slab_expand<NT, 1>(p, u0, s[q], pj, lds_row, hf, bs, ds, begin, end);
+        if (u0.len <= 16) slab_expand<NT, 1>(p, u0, s[q], pj, lds_row, hf, bs, ds, begin, end);  // workgroup uniform
         else slab_expand<NT, 2>(p, u0, s[q], pj, lds_row, hf, bs, ds, begin, end);
     }
     __syncthreads();  // before the next pass or unit reuses the LDS
@@ -451,15 +83,7 @@ __device__ __forceinline__ void slab_pass(const PP& p, const Unit& u0, const Seg
 template <int NT, bool GROUP, class PP>
 __device__ __forceinline__ void slab_unit(const PP& p, const Unit& u, const SegInfo& s0, int part, int parts, unsigned char* lds)
 {
-    int* lds_row = reinterpret_cast<int*>(lds + kHfragBytes + kWaves * kWaveBytes);
-    float* lds_scale = reinterpret_cast<float*>(lds_row + kSlabRows);
-    if ((int)threadIdx.x < kSlabRows) {
-        const int i = (int)threadIdx.x;
-        const int row = i < u.len ? row_of(p, u.pos + i) : -1;
-        lds_row[i] = row;
-        // the row's scale: the adapter's, or the token's own (dynamic scaling, Section 3.3)
-        lds_scale[i] = p.token_scales ? p.token_scales[max(row, 0)] : s0.scale;
-    }
+    slab_unit_rows(p, u, s0, reinterpret_cast<int*>(lds + kRowsOffset));
     __syncthreads();
     constexpr int NPP = GROUP ? pass_projections<NT>() : 1;
     const int n_proj = n_proj_of(p);
@@ -480,34 +104,15 @@ __global__ __launch_bounds__(kThreads) void slab_kernel(KernelArg<GROUP> p)
     __shared__ int s_slot[2];
     auto sg = load_segs(p);
     const int grid = (int)gridDim.x;
-
-    // Rows per unit: the segments are cut into even chunks of at most `per` rows; `per` is the smallest value (16
-    // to 32) for which the chunks fit one round of the grid (sum of ceil(len / per) <= live rows / per + segments).
-    // A batch that does not fit one round at 32 rows takes several, handed out by tickets.
-    int per = kSlabRows;
-    if (sg.n_seg <= kCachedBatches * kWave) {
-        int live = 0, n_live = 0;
-#pragma unroll
-        for (int b = 0; b < kCachedBatches; ++b) {
-            const int len = sg.c[b].en - sg.c[b].st;
-            const bool on = len > 0 && ((p.kinds >> sg.c[b].kd) & 1);
-            live += wave_sum(on ? len : 0);
-            n_live += wave_sum(on ? 1 : 0);
-        }
-        const int slots = grid - n_live;
-        if (slots > 0) per = min(kSlabRows, max(16, small_div(live + slots - 1, slots)));
-    }
-    const LenClass all{1, kBig, p.kinds, true};
+    const int per = slab_rows_per(p, sg);
+    const LenClass all{1, kSlabBig, p.kinds, true};
     ClassScan cc = scan_class(p, sg, per, all);
     // A batch with few chunks is also cut by columns: every part of a chunk repeats phase 1 and takes its share of
     // the column blocks in phase 2.  Parts of one chunk get ids r, r + 8, ...: workgroups whose indices differ by 8
     // sit on the same XCD, so the chunk's x and A cross the HBM interface once.
     const int parts = cc.total > 0 && 2 * cc.total <= grid ? min(kMaxParts, small_div(grid, cc.total)) : 1;
     const int n_units = parts == 1 ? cc.total : ((cc.total + 7) & ~7) * parts;
-    // While a unit runs, the tables and chunk counts that every wave holds in registers (one segment and one adapter
-    // per lane) wait in LDS: the unit needs the registers, the search for the next unit needs the tables.
-    int* stash = reinterpret_cast<int*>(lds_raw + kStashOffset) + lane_id();
-    const bool keeper = (int)threadIdx.x < kWave;  // all waves hold the same values
+    int* stash = reinterpret_cast<int*>(lds_raw + kStashOffset);
     for_each_unit(p.tickets + 0, n_units, s_slot, [&](int gid, int) {
         int chunk = gid, part = 0;
         if (parts > 1) {
@@ -520,27 +125,9 @@ __global__ __launch_bounds__(kThreads) void slab_kernel(KernelArg<GROUP> p)
         SegInfo s;
         u.pi = 0;
         if (!find_unit(p, sg, cc, chunk, per, all, u, s)) return;
-        if (keeper) {
-#pragma unroll
-            for (int b = 0; b < kCachedBatches; ++b) {
-                int* at = stash + b * 12 * kWave;
-                at[0 * kWave] = sg.c[b].st; at[1 * kWave] = sg.c[b].en; at[2 * kWave] = sg.c[b].ad; at[3 * kWave] = sg.c[b].kd;
-                at[4 * kWave] = (int)sg.a[b].a_lo; at[5 * kWave] = (int)sg.a[b].a_hi;
-                at[6 * kWave] = (int)sg.a[b].b_lo; at[7 * kWave] = (int)sg.a[b].b_hi;
-                at[8 * kWave] = sg.a[b].rank; at[9 * kWave] = __float_as_int(sg.a[b].scale);
-                at[10 * kWave] = cc.nch[b]; at[11 * kWave] = cc.incl[b];
-            }
-        }
-        slab_unit<NT, GROUP>(p, u, s, part, parts, lds_raw);  // (begins and ends with a workgroup barrier)
-#pragma unroll
-        for (int b = 0; b < kCachedBatches; ++b) {
-            const int* at = stash + b * 12 * kWave;
-            sg.c[b].st = at[0 * kWave]; sg.c[b].en = at[1 * kWave]; sg.c[b].ad = at[2 * kWave]; sg.c[b].kd = at[3 * kWave];
-            sg.a[b].a_lo = (unsigned int)at[4 * kWave]; sg.a[b].a_hi = (unsigned int)at[5 * kWave];
-            sg.a[b].b_lo = (unsigned int)at[6 * kWave]; sg.a[b].b_hi = (unsigned int)at[7 * kWave];
-            sg.a[b].rank = at[8 * kWave]; sg.a[b].scale = __int_as_float(at[9 * kWave]);
-            cc.nch[b] = at[10 * kWave]; cc.incl[b] = at[11 * kWave];
-        }
+        stash_tables(sg, cc, stash);
+        slab_unit<NT, GROUP>(p, u, s, part, parts, lds_raw);  // (has a workgroup barrier after its first step)
+        unstash_tables(sg, cc, stash);
     });
 }
 

@@ -38,7 +38,7 @@ def test_algorithmic_work_counts_saved_h_and_skips_dropped_tokens():
 
 
 def test_counter_traffic_is_read_from_the_committed_summaries():
-    for workload, phase in (("cfg2_decode_heavy", "forward_fused"), ("cfg4_mlp_up", "forward_fused")):
+    for workload, phase in (("cfg2_decode_heavy", "forward_slab"), ("cfg4_mlp_up", "forward_fused")):
         t = bench.counter_traffic(workload, phase)
         assert t is not None and t > 0
         # what the counters saw is the algorithmic traffic plus re-reads: between 1x and 2x

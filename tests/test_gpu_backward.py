@@ -16,7 +16,7 @@ WGRAD_REL_FROBENIUS = 1e-3
 WGRAD_REL_MAX = 2e-3   # of the largest reference magnitude
 
 
-VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SLAB]
+VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SLAB, lq.LQ_VARIANT_AUTO]
 
 
 def run_backward(oracle_mod, p, variant=lq.LQ_VARIANT_FUSED, dx0_seed=5, token_scales=None):

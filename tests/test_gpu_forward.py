@@ -11,7 +11,7 @@ from gpu_util import (long_batch_problem, DeviceProblem, assert_close, assert_ta
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SLAB]
+VARIANTS = [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SLAB, lq.LQ_VARIANT_AUTO]
 
 
 # ---------------------------------------------------------------------------------------------------
