@@ -43,7 +43,7 @@ template <int NT> constexpr int pass_projections() { return NT == 1 ? kMaxProj :
 // (D[row][rank]: lane (c, kg) receives rows 4 kg .. + 3 of tile mt, rank c of tile nt)
 // =================================================================================================
 template <int NT, int NP, int MT, class PP>
-__device__ __forceinline__ void slab_shrink(const PP& p, const Unit& u, const SegInfo (&s)[NP], const int* lds_row,
+__device__ __forceinline__ void slab_shrink(const PP& p, const Unit&, const SegInfo (&s)[NP], const int* lds_row,
                                             u16* slab, f32x4 (&acc)[NP][2][NT])
 {
     constexpr int NJ = 2 * MT;            // load instructions per block of x (8 rows each)
@@ -58,9 +58,11 @@ __device__ __forceinline__ void slab_shrink(const PP& p, const Unit& u, const Se
     const int nblk = (p.d_in + kKB - 1) / kKB;
     const int n_mine = w < nblk ? (nblk - w + kWaves - 1) / kWaves : 0;  // blocks w, w + 8, ...
     if (n_mine == 0) return;  // wave uniform
-    // Slabs that run side by side would otherwise sweep the same k range in step, which (with a power-of-two row
-    // pitch) keeps hitting the same few channels; so every slab starts its sweep at a different block.
-    const int rot = (int)(((unsigned)u.pos * 5u) % (unsigned)nblk);
+    // Slabs that run side by side would otherwise all sweep the same k range in step, which (with a power-of-two row
+    // pitch) keeps hitting the same few channels; so the sweep starts at a block that depends on the XCD the
+    // workgroup runs on (workgroups are dealt to the 8 XCDs in turn).  The slabs of one XCD keep the same order: they
+    // share its L2, and slabs of one segment then find the adapter's A there instead of fetching it again.
+    const int rot = (int)((((unsigned)blockIdx.x & 7u) * (unsigned)nblk) >> 3);
     auto k_of = [&](int j) {  // first k of this wave's j-th block (past the end: the last one again)
         int b = w + kWaves * min(j, n_mine - 1) + rot;
         if (b >= nblk) b -= nblk;
@@ -190,7 +192,7 @@ __device__ __forceinline__ void slab_expand(const PP&, const Unit& u, const SegI
     const int nblk = blk_end - blk_begin;
     const int n_mine = w < nblk ? (nblk - w + kWaves - 1) / kWaves : 0;
     if (n_mine == 0) return;  // wave uniform
-    const int rot = (int)(((unsigned)u.pos * 3u) % (unsigned)nblk);
+    const int rot = (int)((((unsigned)blockIdx.x & 7u) * (unsigned)nblk) >> 3);  // as in phase 1: one order per XCD
     auto n_of = [&](int j) {  // first column of this wave's j-th block (past the end: the last one again)
         int b = w + kWaves * min(j, n_mine - 1) + rot;
         if (b >= nblk) b -= nblk;

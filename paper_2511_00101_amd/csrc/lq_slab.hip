@@ -107,20 +107,24 @@ __global__ __launch_bounds__(kThreads) void slab_kernel(KernelArg<GROUP> p)
     const int per = slab_rows_per(p, sg);
     const LenClass all{1, kSlabBig, p.kinds, true};
     ClassScan cc = scan_class(p, sg, per, all);
+    // Workgroups are dealt to the 8 XCDs in turn (workgroup i runs on XCD i % 8), and every XCD has its own L2.  The
+    // chunks are numbered segment by segment, so XCD x takes the x-th eighth of them: the slabs of one segment then
+    // sit on one XCD (or two) and find their adapter's matrices in its L2, instead of every XCD fetching every adapter.
     // A batch with few chunks is also cut by columns: every part of a chunk repeats phase 1 and takes its share of
-    // the column blocks in phase 2.  Parts of one chunk get ids r, r + 8, ...: workgroups whose indices differ by 8
-    // sit on the same XCD, so the chunk's x and A cross the HBM interface once.
+    // the column blocks in phase 2; the parts of one chunk get ids r, r + 8, ..., the same XCD again.
+    const int n8 = (cc.total + 7) >> 3;  // chunks per XCD
     const int parts = cc.total > 0 && 2 * cc.total <= grid ? min(kMaxParts, small_div(grid, cc.total)) : 1;
-    const int n_units = parts == 1 ? cc.total : ((cc.total + 7) & ~7) * parts;
+    const int n_units = 8 * n8 * parts;
     int* stash = reinterpret_cast<int*>(lds_raw + kStashOffset);
     for_each_unit(p.tickets + 0, n_units, s_slot, [&](int gid, int) {
-        int chunk = gid, part = 0;
+        int slot = gid, part = 0;
         if (parts > 1) {
             const int blk = small_div(gid, 8 * parts), r = gid - blk * 8 * parts;
             part = r >> 3;
-            chunk = blk * 8 + (r & 7);
-            if (chunk >= cc.total) return;  // (padding of the last block)
+            slot = blk * 8 + (r & 7);
         }
+        const int chunk = (slot & 7) * n8 + (slot >> 3);
+        if (chunk >= cc.total) return;  // (padding)
         Unit u;
         SegInfo s;
         u.pi = 0;
