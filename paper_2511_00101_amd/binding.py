@@ -383,6 +383,35 @@ def workspace(n_bytes: int, device="cuda") -> torch.Tensor:
     return torch.zeros((max(n_bytes, 4096) + 7) // 8, dtype=torch.int64, device=device)
 
 
+LQ_DEVICE_ERR_BAD_SEGMENT = 1      # a segment was skipped: adapter id, rank, matrix pointer or row range unusable
+LQ_DEVICE_ERR_BARRIER_TIMEOUT = 2  # the single-launch kernel's device-wide wait ran out: y / dx were left untouched
+
+
+class LqDeviceError(RuntimeError):
+    """The kernels reported a problem in the workspace's error word (the library itself never synchronises)."""
+
+    def __init__(self, bits: int, where: str):
+        names = [n for b, n in ((LQ_DEVICE_ERR_BAD_SEGMENT, "bad segment table entry (segment skipped)"),
+                                (LQ_DEVICE_ERR_BARRIER_TIMEOUT, "device-wide wait timed out (outputs left untouched; "
+                                 "use LQ_VARIANT_SLAB or LQ_VARIANT_SPLIT when the device is shared)")) if bits & b]
+        super().__init__(f"{where}: device error word {bits:#x}: " + "; ".join(names or ["unknown bits"]))
+        self.bits = bits
+
+
+def device_error_word(workspace_or_word: torch.Tensor) -> int:
+    """The error word of a workspace (its first 32 bits) or of a one-element int32 tensor; waits for the stream."""
+    t = workspace_or_word.view(-1)[:1]
+    return int(t.view(torch.int32)[0].item()) & 0xffffffff
+
+
+def raise_on_device_error(workspace_or_word: torch.Tensor, where: str = "lqlora") -> None:
+    """Checked mode for callers that can afford a synchronisation: raises LqDeviceError if the kernels that used this
+    workspace set a bit of its error word.  The word is left as it is (the caller zeroes the header to clear it)."""
+    bits = device_error_word(workspace_or_word)
+    if bits:
+        raise LqDeviceError(bits, where)
+
+
 def lora_profile_enable(on: bool) -> None:
     """Start (or stop) timing the library's own launches; either way what was recorded is discarded."""
     st = lib().lora_profile_enable(1 if on else 0)

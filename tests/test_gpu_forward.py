@@ -137,6 +137,11 @@ def test_bad_device_metadata_is_skipped_and_flagged(variant):
     rows = d.seg.to_host()
     first = rows["perm"][rows["seg_starts"][0]: rows["seg_starts"][1]]
     assert np.array_equal(y_bits[first], p.y0[first])
+    # the binding's checked mode turns the word into an exception
+    word = torch.tensor([err], dtype=torch.int32, device="cuda")
+    with pytest.raises(lq.LqDeviceError, match="bad segment"):
+        lq.raise_on_device_error(word, "forward")
+    lq.raise_on_device_error(torch.zeros(1, dtype=torch.int32, device="cuda"))   # a clean word raises nothing
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -227,6 +232,16 @@ def test_group_small_mixed(oracle_mod, variant, n_proj):
     check_forward_group(oracle_mod, group, variant)
     if n_proj == 3:
         check_forward_group(oracle_mod, group, variant, token_scales=request_scales(base, 11))
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("ranks,n_tokens", [([16, 7, 12], 700), ([32, 20, 3, 17], 6000), ([64, 40, 33], 700)])
+def test_group_of_four_by_rank_class(oracle_mod, variant, ranks, n_tokens):
+    """Four layers in one call at ranks up to 16, 32 and 64: the slab kernel keeps the accumulators of four, three
+    and one projection(s) per pass, so these run as one pass, as 3 + 1 and as 1 + 1 + 1 + 1; 700 tokens give slabs of
+    one 16-row tile, 6000 tokens slabs of two; saved h per layer."""
+    base = synth.small_mixed(171, n_tokens, 520, 264, ranks, drop_frac=0.05, w_std=0.03)
+    check_forward_group(oracle_mod, group_of(base, [1032, 8, 776], 1700), variant)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -422,6 +437,15 @@ def test_fused_wait_that_runs_out_leaves_y_untouched(oracle_mod):
         torch.cuda.synchronize()
         assert int(words[0].item()) & 2
         assert np.array_equal(lq.bits_from_bf16(d.y), p.y0)
+        with pytest.raises(lq.LqDeviceError, match="timed out"):
+            lq.raise_on_device_error(ws, "forward")
+    # the slab variant has no device-wide wait: it works on the same workspace as it is
+    words[0] = 0
+    lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, lq.LQ_VARIANT_SLAB)
+    torch.cuda.synchronize()
+    assert int(words[0].item()) == 0
+    assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(d.y)), ref.y, "y after the slab call")
+    d.y.copy_(lq.bf16_from_bits(p.y0))
     # two launches do not use the barrier words: same workspace, error word cleared by the caller
     words[0] = 0
     lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, lq.LQ_VARIANT_SPLIT)
@@ -438,7 +462,7 @@ def test_fused_wait_that_runs_out_leaves_y_untouched(oracle_mod):
 
 
 def test_one_workspace_many_calls(oracle_mod):
-    """One workspace reused by consecutive calls (two launches, one launch, two launches, one launch) on a batch
+    """One workspace reused by consecutive calls (two launches, one launch, slabs, two launches, one launch, slabs) on a batch
     with many more units than resident workgroups, so that the ticket counters are drawn from: every call must
     match the oracle, and the header's counters must be back at zero after every call."""
     p = synth.config4("up")
@@ -447,7 +471,8 @@ def test_one_workspace_many_calls(oracle_mod):
     d.build()
     ws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, d.adapters.max_rank, p.d_in, p.d_out, lq.LQ_VARIANT_FUSED))
     y0 = lq.bf16_from_bits(p.y0)
-    for variant in (lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED):
+    for variant in (lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SLAB, lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED,
+                    lq.LQ_VARIANT_SLAB):
         d.y.copy_(y0)
         h_out = torch.full((ref.segments.h_elems,), float("nan"), dtype=torch.float32, device="cuda")
         lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, variant)
