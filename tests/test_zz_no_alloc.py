@@ -52,7 +52,7 @@ def _one(oracle_mod, p, variant):
     assert_close(h_st, ref.h, f"{p.name} h_out")
 
 
-@pytest.mark.parametrize("variant", [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED])
+@pytest.mark.parametrize("variant", [lq.LQ_VARIANT_SPLIT, lq.LQ_VARIANT_FUSED, lq.LQ_VARIANT_SLAB, lq.LQ_VARIANT_AUTO])
 def test_static_workspace_forward_two_calls_in_a_row(oracle_mod, variant):
     """Two calls in a row on the same GPU (they share its array, which keeps the first call's contents), the second
     with a smaller batch, a smaller rank stride and no k split."""
