@@ -2,8 +2,9 @@
 """Benchmark of the segmented multi-LoRA hot path on one MI355X.
 
 Headline (`value`, `roofline`, `cpu_baseline`): the forward of the 8B-shaped 32-layer stack, the largest
-configuration (benchmark configs[4]): a step = segment-metadata builder + the forward of the 224 LoRA linears
-(7 projections x 32 layers; shrink, h-save, expand in one launch per call; q, k, v and gate, up as grouped calls
+configuration: a step = segment-metadata builder + the forward of the 224 LoRA linears
+(7 projections x 32 layers; shrink, h-save, expand in one launch per call, the library choosing between its two
+one-launch kernels call by call; q, k, v and gate, up as grouped calls
 that read their common x once, so 4 launches per layer) over one mixed batch of 5632 tokens; `value` = tokens of
 the batch / step time.  `configs` carries the single-call workloads (a step = builder + forward,
 operands rotated over > 1 GiB of replicas) and the layer stack's backward.  Inputs are synthetic, resident in HBM
@@ -33,7 +34,7 @@ METRIC = "segmented multi-LoRA fwd: tokens/s, HBM GB/s & MFMA util vs peak (1 MI
 
 
 def algorithmic_work(p):
-    """Bytes the method must move and flops it must do for one call ('Algorithmic bytes'):
+    """Bytes the method must move and flops it must do for one call:
     x once, y read + write, A and B of every adapter in use once, saved h once; 2 r (d_in + d_out) flops/token."""
     import numpy as np
     ta, tk = p.batch.token_adapter, p.batch.token_kind
@@ -166,7 +167,7 @@ ONE_LAUNCH = ("forward_fused", "forward_slab")   # kernel names of the variants 
 
 
 class LayerStack:
-    """The 8B-shaped 32-layer stack (benchmark configs[4]): 7 LoRA linears per layer with their own adapter
+    """The 8B-shaped 32-layer stack: 7 LoRA linears per layer with their own adapter
     weights, one batch structure for all 224.  grouped: q, k, v read one x and gate, up read one x, as in a real
     decoder layer (Algorithm 1), and each such group is one lora_segmented_forward_group call; x is then counted
     once per group.  Not grouped: one call per linear, and every call has its OWN x.  Either way no two launches share an
@@ -433,7 +434,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's throughput; --gpus must be 1 "
-              "(the path shards by token segments with no exchange, see DESIGN.md)", file=sys.stderr)
+              "(the path shards by token segments with no exchange between GPUs; nothing here uses a second one)", file=sys.stderr)
         sys.exit(2)
 
     import torch
