@@ -1,5 +1,5 @@
-// Device code of the row-slab forward, shared by the slab kernel and by the single-launch kernel whose shrink phase
-// works on slabs: a workgroup takes a slab of at most 32 rows of one segment;
+// Device code of the row-slab forward (the kernel and its launch are in lq_slab.hip): a workgroup takes a slab of at
+// most 32 rows of one segment;
 //   phase 1: h = x A_a^T over all of d_in (the 8 waves take alternate 64-wide k blocks and add their results in LDS)
 //   phase 2: y += s h B_a (the 8 waves take alternate 64-column blocks)
 // All global accesses are row-wise 16-byte accesses (an instruction covers 8 rows x 128 contiguous bytes); data
