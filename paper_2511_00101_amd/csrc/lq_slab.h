@@ -435,8 +435,20 @@ __device__ __forceinline__ int slab_rows_per(const PP& p, const Segs<PP>& sg)
             live += wave_sum(on ? len : 0);
             n_live += wave_sum(on ? 1 : 0);
         }
-        const int slots = (int)gridDim.x - n_live;
+        const int grid = (int)gridDim.x, slots = grid - n_live;
         if (slots > 0) per = min(kSlabRows, max(16, small_div(live + slots - 1, slots)));
+        // (that bound charges every segment a whole extra chunk.  Just above 16 rows it matters: a slab of 17 rows
+        // runs two row tiles, the second nearly empty; so 16 is tried by the exact count)
+        if (per > 16 && per <= 20) {
+            int n = 0;
+#pragma unroll
+            for (int b = 0; b < kCachedBatches; ++b) {
+                const int len = sg.c[b].en - sg.c[b].st;
+                const bool on = len > 0 && ((p.kinds >> sg.c[b].kd) & 1);
+                n += wave_sum(on ? (len + 15) >> 4 : 0);
+            }
+            if (n <= grid) per = 16;
+        }
     }
     return per;
 }
