@@ -482,3 +482,30 @@ def test_one_workspace_many_calls(oracle_mod):
         assert not np.any(header[np.arange(1024) != 32]), "counters of the header must be back at zero"  # word 32 counts barriers
         assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(d.y)), ref.y, "y")
         assert_close(h_out.cpu().numpy(), ref.h, "h_out")
+
+
+def test_slab_variant_runs_beside_other_kernels(oracle_mod):
+    """The slab variant has no device-wide wait, so it needs no compute unit to itself: here it runs while another
+    stream keeps the device busy with matrix products (the paper's setting: base-model work of other requests on the
+    same GPU), and gives the oracle's result; the error word stays clean."""
+    p = synth.config3()
+    ref = oracle_mod.forward(p.x, p.y0, p.A, p.B, p.ranks, p.scales, p.batch.token_adapter, p.batch.token_kind)
+    d = DeviceProblem(p)
+    d.build()
+    ws = lq.workspace(lq.lora_forward_workspace_bytes(p.n_tokens, d.adapters.max_rank, p.d_in, p.d_out, lq.LQ_VARIANT_SLAB))
+    h_out = torch.full((ref.segments.h_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    a = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+    other = torch.cuda.Stream()            # default priority
+    torch.cuda.synchronize()
+    with torch.cuda.stream(other):
+        for _ in range(40):                # a few milliseconds of work on the other stream
+            c = a @ b
+    for _ in range(3):                     # meanwhile, on this stream
+        d.y.copy_(lq.bf16_from_bits(p.y0))
+        lq.lora_segmented_forward(d.x, d.y, d.adapters, d.seg, h_out, ws, lq.LQ_VARIANT_SLAB)
+    torch.cuda.synchronize()
+    assert c.shape == (4096, 4096)
+    lq.raise_on_device_error(ws, "slab beside other kernels")
+    assert_close(synth.bf16_bits_to_f64(lq.bits_from_bf16(d.y)), ref.y, "y")
+    assert_close(h_out.cpu().numpy(), ref.h, "h_out")
