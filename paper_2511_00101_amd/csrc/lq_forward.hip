@@ -15,7 +15,7 @@
 //                        a fixed order.  The MFMA does the k reduction even when few rows are live.
 //   (with ksplit > 1 every shrink unit stores the h of its slice and the expand kernel adds the slices
 //    in order, so no workgroup waits for another and the sum does not depend on timing)
-//   expand, long unit  : up to 256 rows of a segment with >= 16 rows x a group of 512-column blocks of
+//   expand, long unit  : up to 512 rows (256 for ranks above 32) of a segment with >= 16 rows x a group of 512-column blocks of
 //                        d_out.  The B_a block is staged in LDS and transposed into MFMA fragments
 //                        that stay in registers; the unit's h rows are scaled, split into bf16 high and
 //                        low parts and laid out as fragments in LDS once; then y streams by, 32 rows
@@ -436,7 +436,10 @@ struct ExpandCfg {
     static constexpr int WN = 32 * PAIRS;            // columns per wave
     static constexpr int UN = kWaves * WN;           // columns per block
     static constexpr int ROWS = 32 * KSTEPS;         // rank rows staged (ranks beyond the adapter's are zero)
-    static constexpr int CT = KSTEPS >= 4 ? 128 : 256;  // token rows per unit
+    // token rows per unit, as many as the h fragments leave room for: every unit reads its block of B from HBM (y
+    // streaming through the L2 leaves nothing of it for the next unit), so the B traffic of a launch is its row
+    // chunks x the adapter's B (gate + up of the layer stack, 512 vs 256 rows: 166 -> 163 us, the step 10.95 -> 10.87 ms)
+    static constexpr int CT = KSTEPS >= 4 ? 128 : KSTEPS == 1 ? 512 : 256;
     static constexpr int BPITCH = UN + 8;            // elements per staged B row
     static constexpr size_t B_BYTES = (size_t)ROWS * BPITCH * sizeof(u16);
     static constexpr size_t H_BYTES = (size_t)(CT / 16) * KSTEPS * 2 * kWave * 16;  // [tile][kstep][hi|lo][lane] x 16 B
@@ -1320,7 +1323,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // LQ_VARIANT_AUTO: slab or fused, from the host arguments alone.  Measured on the layer-stack shapes (5632 tokens,
 // rank 32): slab wins up to 14336 output columns in all (q 40 vs 47 us, k 25 vs 30, q+k+v 64 vs 72, down 71 vs 76, gate
 // 96 vs 101), fused beyond (gate+up 167 vs 178: a slab re-reads all of B for its 32 rows, the fused expand phase stages a
-// block of B once per 256 rows) and for ranks above 32 (the Zipf batch with ranks up to 64: 125 vs 152 us).
+// block of B once per 512 rows) and for ranks above 32 (the Zipf batch with ranks up to 64: 125 vs 152 us).
 int auto_variant(int max_rank, long long out_columns)
 {
     return max_rank <= 32 && out_columns <= 16384 ? LQ_VARIANT_SLAB : LQ_VARIANT_FUSED;
