@@ -220,7 +220,7 @@ template <int NT>
 __global__ __launch_bounds__(kThreads, NT <= 2 ? 4 : 2) void wgrad_kernel(BwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
+    int n_seg;
     const SegCache c0 = load_seg_cache(p, n_seg);
     const LenClass cut = cut_class(), whole = whole_class();
     const int blocks_b = (p.d_out + kWgCols - 1) / kWgCols, blocks_a = (p.d_in + kWgCols - 1) / kWgCols;
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(kThreads, NT <= 2 ? 4 : 2) void wgrad_kernel(BwdPar
 constexpr int kRedRanks = 8;
 __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
 {
-    const int n_seg = uniform(min(*p.n_segments, p.max_segments));
+    int n_seg;
     const SegCache c0 = load_seg_cache(p, n_seg);
     const LenClass cut = cut_class();
     const int dsum = p.d_out + p.d_in;
@@ -265,28 +265,39 @@ __global__ __launch_bounds__(kThreads) void wreduce_kernel(BwdParams p)
         if (!find_chunk(p, n_seg, c0, chunk_id, kWgRows, cut, u)) continue;
         if (u.pos != u.first) continue;  // only the segment's first chunk adds up the segment
         if (u.ad < 0 || u.ad >= p.n_adapters) continue;
-        const int rank = p.ranks[u.ad];
-        if (rank < 1 || rank > p.max_rank) continue;
-        const float scale = p.token_scales ? 1.f : p.scales[u.ad];  // (per-token scales were applied row by row)
         const int n_chunks = (u.seg_len + kWgRows - 1) / kWgRows;
         const int j0 = (sub / col_blocks) * kRedRanks;
         const int col = (sub % col_blocks) * kThreads + (int)threadIdx.x;
-        if (col >= dsum || j0 >= rank) continue;
+        if (col >= dsum) continue;
+        const float* __restrict__ part = p.wpart + ((long long)chunk_id * p.rstride + j0) * dsum + col;
+        // Four chunks' partials are requested together (a chunk that does not exist re-reads the last one and is not
+        // added): one round trip for the segments of the layer stack instead of one per chunk; the additions keep
+        // the chunk order.  The first four go out before the adapter's rank, scale and pointer are asked for: where
+        // the partials lie depends on the tables alone (rows beyond the rank lie inside the rstride rows of a partial).
+        float v[4][kRedRanks];
+        auto request = [&](int cc) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int jj = 0; jj < kRedRanks; ++jj) v[k][jj] = part[((long long)min(cc + k, n_chunks - 1) * p.rstride + jj) * dsum];
+        };
+        request(0);
+        __builtin_amdgcn_sched_barrier(0);
+        const int rank = p.ranks[u.ad];
+        const float scale = p.token_scales ? 1.f : p.scales[u.ad];  // (per-token scales were applied row by row)
         const bool for_b = col < p.d_out;
         float* __restrict__ dst = for_b ? (p.dB_ptrs ? p.dB_ptrs[u.ad] : nullptr) : (p.dA_ptrs ? p.dA_ptrs[u.ad] : nullptr);
-        if (!dst) continue;
+        if (rank < 1 || rank > p.max_rank || j0 >= rank || !dst) continue;
         const int d = for_b ? p.d_out : p.d_in, n = for_b ? col : col - p.d_out;
-        const float* __restrict__ part = p.wpart + ((long long)chunk_id * p.rstride + j0) * dsum + col;
         float sum[kRedRanks];
 #pragma unroll
         for (int jj = 0; jj < kRedRanks; ++jj) sum[jj] = 0.f;
-        for (int cc = 0; cc < n_chunks; ++cc) {
-            float v[kRedRanks];
+        for (int cc = 0; cc < n_chunks; cc += 4) {
+            if (cc > 0) request(cc);
 #pragma unroll
-            for (int jj = 0; jj < kRedRanks; ++jj)  // rows beyond the rank lie inside the rstride rows of the partial
-                v[jj] = part[((long long)cc * p.rstride + jj) * dsum];
+            for (int k = 0; k < 4; ++k)
 #pragma unroll
-            for (int jj = 0; jj < kRedRanks; ++jj) sum[jj] += v[jj];
+                for (int jj = 0; jj < kRedRanks; ++jj) sum[jj] = cc + k < n_chunks ? sum[jj] + v[k][jj] : sum[jj];
         }
 #pragma unroll
         for (int jj = 0; jj < kRedRanks; ++jj)

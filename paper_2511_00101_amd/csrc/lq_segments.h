@@ -48,12 +48,26 @@ __device__ __forceinline__ SegLane load_seg_lane(const P& p, int n_seg, int s)
 constexpr int kCachedBatches = 2;
 struct SegCache { SegLane c[kCachedBatches]; };
 
+// (the table entries are requested before the segment count is waited for: one round trip, not two)
 template <class P>
-__device__ __forceinline__ SegCache load_seg_cache(const P& p, int n_seg)
+__device__ __forceinline__ SegCache load_seg_cache(const P& p, int& n_seg)
 {
     SegCache sc;
+    const int n_raw = *p.n_segments;
 #pragma unroll
-    for (int b = 0; b < kCachedBatches; ++b) sc.c[b] = load_seg_lane(p, n_seg, b * kWave + lane_id());
+    for (int b = 0; b < kCachedBatches; ++b) {
+        const int s = min(b * kWave + lane_id(), p.max_segments - 1);  // the tables hold max_segments entries
+        sc.c[b].st = p.seg_starts[s];
+        sc.c[b].en = p.seg_starts[s + 1];
+        sc.c[b].ad = p.seg_adapter[s];
+        sc.c[b].kd = p.seg_kind[s];
+    }
+    n_seg = __builtin_amdgcn_readfirstlane(min(n_raw, p.max_segments));
+#pragma unroll
+    for (int b = 0; b < kCachedBatches; ++b) {
+        if (b * kWave + lane_id() >= n_seg) sc.c[b].st = sc.c[b].en = sc.c[b].ad = sc.c[b].kd = 0;
+        guard_seg_range(p, sc.c[b]);
+    }
     return sc;
 }
 
